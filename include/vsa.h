@@ -1,0 +1,114 @@
+/*
+ * vsa.h -- C ABI of the MI355X (gfx950) Video Sparse Attention library, libvsa.so.
+ *
+ * Video Sparse Attention (arxiv 2505.13389, Sec. 2.2) replaces dense 3D attention of a
+ * video diffusion transformer by two stages over (Ct,Ch,Cw) = (4,4,4) token cubes: a
+ * coarse stage (mean-pooled cube-level attention that also picks, per query cube, the
+ * top-K key cubes) and a fine stage (token-level block-sparse attention over the picked
+ * cubes); the output is the gated sum O = O_c * G_c + O_f * G_f.
+ *
+ * Conventions shared by every entry point
+ *   - All data pointers are DEVICE pointers (HIP), 16-byte aligned, contiguous, row-major.
+ *     `const vsa_params_t*` and the out-parameters of vsa_padded_tokens are HOST pointers.
+ *   - The caller owns every buffer.  The library never allocates, frees or synchronises:
+ *     calls enqueue kernels on `hip_stream` (a hipStream_t passed as void*; NULL = the
+ *     default stream) and return.  Scratch comes from `workspace` (>= vsa_workspace_bytes).
+ *   - "raster" order: token (t,h,w) of the valid T x Hh x W grid at n = t*Hh*W + h*W + w
+ *     (Sec. 2.1).  "tiled" order: the index equation of Sec. 2.2 on the grid padded up to
+ *     cube multiples, Np tokens = Nc cubes x 64; each cube is 64 consecutive rows.
+ *   - Pad slots (tiled rows outside the valid grid) are defined by geometry alone.  They
+ *     are never keys, are excluded from pooled means, and their rows of every output and
+ *     gradient are written as zero; whatever the caller stores there in an input is ignored.
+ *   - Results are deterministic (bit-identical across calls on the same inputs).
+ *   - Return value: VSA_OK (0) or a negative vsa_status; on an error nothing was enqueued.
+ */
+#ifndef VSA_H_
+#define VSA_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  VSA_OK = 0,
+  VSA_ERR_NULL = -1,        /* a required pointer is NULL                              */
+  VSA_ERR_BAD_ARG = -2,     /* non-positive dimension, topk outside 1..Nc              */
+  VSA_ERR_UNSUPPORTED = -3, /* cube volume != 64, d not in {64,128}, Nc above the limit */
+  VSA_ERR_ALIGN = -4,       /* a device pointer is not 16-byte aligned                 */
+  VSA_ERR_WORKSPACE = -5,   /* workspace NULL or smaller than vsa_workspace_bytes      */
+  VSA_ERR_HIP = -6          /* a kernel launch was rejected by the runtime             */
+} vsa_status;
+
+#define VSA_FLAG_INDICES_GIVEN 1u /* vsa_forward: block_idx is an INPUT, top-K is skipped */
+#define VSA_MAX_CUBES 4096        /* largest supported Nc                                 */
+
+typedef struct {
+  int32_t B, H;        /* batch, heads                                                   */
+  int32_t T, Hh, W;    /* valid latent grid in tokens                                    */
+  int32_t Ct, Ch, Cw;  /* cube shape; Ct*Ch*Cw must be 64 (Sec. 2.2: (4,4,4))            */
+  int32_t d;           /* head dimension: 64 or 128                                      */
+  int32_t topk;        /* key cubes per query cube, 1..Nc; Nc = the dense path           */
+  float softmax_scale; /* <= 0 selects 1/sqrt(d) (Sec. 2.1)                              */
+  uint32_t flags;      /* VSA_FLAG_*                                                     */
+} vsa_params_t;
+
+/* Padded token count Np and cube count Nc of the grid in `p` (Sec. 2.2: (Nt,Nh,Nw) =
+ * ceil(T/Ct), ceil(Hh/Ch), ceil(W/Cw); Np = 64*Nc).  Host-only. */
+int vsa_padded_tokens(const vsa_params_t* p, int64_t* Np, int32_t* Nc);
+
+/* Bytes of scratch vsa_forward (backward == 0) or vsa_backward (backward != 0) needs.
+ * Returns 0 for invalid parameters.  Host-only. */
+size_t vsa_workspace_bytes(const vsa_params_t* p, int backward);
+
+/* Raster <-> tiled token permutation of one bf16 tensor (Sec. 2.2 index equation; App. B
+ * tile()/untile()).
+ *   inverse == 0: src [B,H,T*Hh*W,d] raster -> dst [B,H,Np,d] tiled, pad rows zero-filled.
+ *   inverse != 0: src [B,H,Np,d] tiled -> dst [B,H,T*Hh*W,d] raster, pad rows dropped.
+ * src and dst must not overlap. */
+int vsa_tile_permute(const vsa_params_t* p, const void* src, void* dst, int inverse, void* hip_stream);
+
+/* Forward (Sec. 2.2; App. B): pooling -> coarse attention -> per-row top-K -> fine
+ * block-sparse attention -> gated sum.
+ *   q,k,v        in   bf16 [B,H,Np,d] tiled
+ *   gate_c       in   bf16 [B,H,Np,d] tiled (G_c)
+ *   gate_f       in   bf16 [B,H,Np,d] tiled (G_f), or NULL = ones (Sec. 2.3)
+ *   out          out  bf16 [B,H,Np,d] tiled: O_c[cube]*G_c + O_f*G_f, one rounding to bf16
+ *   block_idx    out  int32 [B,H,Nc,topk]: selected key cubes of each query cube, ascending
+ *                     (the topk largest coarse logits, ties to the lower cube index);
+ *                in   when flags has VSA_FLAG_INDICES_GIVEN (must be ascending, distinct,
+ *                     each in [0,Nc); not validated on the device)
+ *   out_fine     out  bf16 [B,H,Np,d]  O_f           } saved for vsa_backward;
+ *   lse_fine     out  fp32 [B,H,Np]    log-sum-exp of the scaled fine logits (0 on pads)
+ *   out_coarse   out  fp32 [B,H,Nc,d]  O_c per cube  } any of these four may be NULL
+ *   lse_coarse   out  fp32 [B,H,Nc]    log-sum-exp of the coarse logits
+ * block_idx may be NULL only without VSA_FLAG_INDICES_GIVEN (the list then lives in the
+ * workspace). */
+int vsa_forward(const vsa_params_t* p, const void* q, const void* k, const void* v, const void* gate_c,
+                const void* gate_f, void* out, int32_t* block_idx, void* out_fine, float* lse_fine,
+                float* out_coarse, float* lse_coarse, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Backward of vsa_forward with the selection held constant (Sec. 2.4 states that a
+ * backward kernel exists; the gradients are the chain rule through Sec. 2.2's steps:
+ * gated sum, fine attention recomputed from lse_fine, coarse attention recomputed from
+ * the pooled tensors, mean pooling).  No gradient flows through the top-K.
+ *   q,k,v,gate_c,gate_f   as given to vsa_forward
+ *   dout         in   bf16 [B,H,Np,d] tiled, gradient of the loss w.r.t. `out`
+ *   block_idx, out_fine, lse_fine, out_coarse, lse_coarse   as written by vsa_forward
+ *   dq,dk,dv,dgate_c      out  bf16 [B,H,Np,d] tiled
+ *   dgate_f      out  bf16 [B,H,Np,d], must be NULL iff gate_f is NULL */
+int vsa_backward(const vsa_params_t* p, const void* q, const void* k, const void* v, const void* gate_c,
+                 const void* gate_f, const void* dout, const int32_t* block_idx, const void* out_fine,
+                 const float* lse_fine, const float* out_coarse, const float* lse_coarse, void* dq, void* dk,
+                 void* dv, void* dgate_c, void* dgate_f, void* workspace, size_t workspace_bytes,
+                 void* hip_stream);
+
+/* Human-readable name of a status code (static string, never NULL). */
+const char* vsa_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* VSA_H_ */

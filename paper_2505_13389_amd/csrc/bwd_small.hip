@@ -1,0 +1,290 @@
+// Small backward steps: the elementwise preprocess, the coarse-stage backward (fp32) and the
+// transposed block map.  The gradient formulas are the chain rule through Sec. 2.2's gated sum,
+// coarse softmax attention and mean pooling.
+#include "vsa_kernels.h"
+
+namespace vsa {
+
+// ---------------------------------------------------------------------------------------------
+// Preprocess.  Per token i of cube c (pad rows produce zeros):
+//   dGc_i = dO_i * Oc[c]      dGf_i = dO_i * Of_i      dOf_i = dO_i * Gf_i  (bf16, feeds the MFMAs)
+//   Delta_i = sum_d dOf_i * Of_i                       dOc[c] = sum_i dO_i * Gc_i
+// One workgroup per (b*h, cube); thread layout as in the pooling kernel.
+template <int D>
+__global__ __launch_bounds__(256) void k_bwd_pre(int Nc, const uint64_t* __restrict__ mask, const uint4* __restrict__ dout,
+                                                 const uint4* __restrict__ gc, const uint4* __restrict__ gf,
+                                                 const uint4* __restrict__ of, const float* __restrict__ oc,
+                                                 uint4* __restrict__ dgc, uint4* __restrict__ dgf,
+                                                 uint4* __restrict__ dof, float* __restrict__ delta,
+                                                 float* __restrict__ doc) {
+  constexpr int CPR = D / 8, RG = 256 / CPR, RPT = kTile / RG;
+  __shared__ float part[RG][D + 4];
+  const int c = blockIdx.x % Nc;
+  const long long bh = blockIdx.x / Nc;
+  const uint64_t m = mask[c];
+  const int ch = threadIdx.x % CPR, rg = threadIdx.x / CPR;
+  const long long row0 = (bh * Nc + c) * (long long)kTile;
+  float ocv[8];
+  {
+    const float* p = oc + (bh * Nc + c) * D + ch * 8;
+    const float4 a = *(const float4*)p, b = *(const float4*)(p + 4);
+    ocv[0] = a.x; ocv[1] = a.y; ocv[2] = a.z; ocv[3] = a.w; ocv[4] = b.x; ocv[5] = b.y; ocv[6] = b.z; ocv[7] = b.w;
+  }
+  float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+  for (int i = 0; i < RPT; ++i) {
+    const int r = rg + i * RG;
+    const long long g = (row0 + r) * CPR + ch;
+    const bool valid = (m >> r) & 1;
+    uint4 z = make_uint4(0, 0, 0, 0), o_gc = z, o_gf = z, o_dof = z;
+    float dsum = 0.f;
+    if (valid) {
+      float go[8], gcv[8], gfv[8], ofv[8], t0[8], t1[8], t2[8];
+      unpack8(dout[g], go);
+      unpack8(gc[g], gcv);
+      unpack8(of[g], ofv);
+      if (gf) unpack8(gf[g], gfv);
+      else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) gfv[e] = 1.f;
+      }
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        t0[e] = go[e] * ocv[e];
+        t1[e] = go[e] * ofv[e];
+        t2[e] = go[e] * gfv[e];
+        acc[e] += go[e] * gcv[e];
+      }
+      o_gc = pack8(t0); o_gf = pack8(t1); o_dof = pack8(t2);
+      float t2r[8];
+      unpack8(o_dof, t2r);  // Delta uses the rounded dOf, the value the fine kernels multiply with
+#pragma unroll
+      for (int e = 0; e < 8; ++e) dsum = fmaf(t2r[e], ofv[e], dsum);
+    }
+    dgc[g] = o_gc;
+    if (dgf) dgf[g] = o_gf;
+    dof[g] = o_dof;
+#pragma unroll
+    for (int o = CPR / 2; o > 0; o >>= 1) dsum += __shfl_xor(dsum, o);
+    if (ch == 0) delta[row0 + r] = dsum;
+  }
+#pragma unroll
+  for (int e = 0; e < 8; ++e) part[rg][ch * 8 + e] = acc[e];
+  __syncthreads();
+  if (threadIdx.x < D) {
+    float s = 0;
+    for (int r = 0; r < RG; ++r) s += part[r][threadIdx.x];
+    doc[(bh * Nc + c) * D + threadIdx.x] = s;
+  }
+}
+
+hipError_t launch_bwd_pre(int BH, int Nc, int d, const uint64_t* mask, const void* dout, const void* gate_c,
+                          const void* gate_f, const void* out_fine, const float* oc, void* dgate_c, void* dgate_f,
+                          void* dof, float* delta, float* doc, hipStream_t s) {
+  const unsigned grid = (unsigned)(BH * Nc);
+  if (d == 128)
+    k_bwd_pre<128><<<grid, 256, 0, s>>>(Nc, mask, (const uint4*)dout, (const uint4*)gate_c, (const uint4*)gate_f,
+                                        (const uint4*)out_fine, oc, (uint4*)dgate_c, (uint4*)dgate_f, (uint4*)dof, delta,
+                                        doc);
+  else
+    k_bwd_pre<64><<<grid, 256, 0, s>>>(Nc, mask, (const uint4*)dout, (const uint4*)gate_c, (const uint4*)gate_f,
+                                       (const uint4*)out_fine, oc, (uint4*)dgate_c, (uint4*)dgate_f, (uint4*)dof, delta,
+                                       doc);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// Batched fp32 GEMM with arbitrary strides: C[b][m][n] = alpha * sum_k A(b,m,k) * B(b,k,n),
+// A(b,m,k) = a[b*sab + m*sam + k*sak], B(b,k,n) = bm[b*sbb + k*sbk + n*sbn], C row-major.
+// 64x64 output tile per workgroup, 16-deep k slices through LDS, 4x4 outputs per thread.
+// The summation order over k is fixed, so results are deterministic.
+__global__ __launch_bounds__(256) void k_sgemm(int M, int N, int Kd, float alpha, const float* __restrict__ a,
+                                               long long sab, int sam, int sak, const float* __restrict__ bm,
+                                               long long sbb, int sbk, int sbn, float* __restrict__ cm, long long scb) {
+  __shared__ float As[16][68];
+  __shared__ float Bs[16][68];
+  const int b = blockIdx.z, m0 = blockIdx.y * 64, n0 = blockIdx.x * 64;
+  const float* ab = a + b * sab;
+  const float* bb = bm + b * sbb;
+  const int tid = threadIdx.x, tm = tid / 16, tn = tid % 16;
+  float acc[4][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc[i][j] = 0.f;
+  for (int k0 = 0; k0 < Kd; k0 += 16) {
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+      const int e = it * 256 + tid;
+      // keep the unit-stride axis on consecutive threads
+      int mm, kk;
+      if (sak == 1) { kk = e % 16; mm = e / 16; } else { mm = e % 64; kk = e / 64; }
+      float va = 0.f;
+      if (m0 + mm < M && k0 + kk < Kd) va = ab[(long long)(m0 + mm) * sam + (long long)(k0 + kk) * sak];
+      As[kk][mm] = va;
+      int nn, kb;
+      if (sbk == 1) { kb = e % 16; nn = e / 16; } else { nn = e % 64; kb = e / 64; }
+      float vb = 0.f;
+      if (n0 + nn < N && k0 + kb < Kd) vb = bb[(long long)(k0 + kb) * sbk + (long long)(n0 + nn) * sbn];
+      Bs[kb][nn] = vb;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int kk = 0; kk < 16; ++kk) {
+      const float4 av = *(const float4*)&As[kk][tm * 4];
+      const float4 bv = *(const float4*)&Bs[kk][tn * 4];
+      const float ar[4] = {av.x, av.y, av.z, av.w}, br[4] = {bv.x, bv.y, bv.z, bv.w};
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(ar[i], br[j], acc[i][j]);
+    }
+    __syncthreads();
+  }
+  float* cb = cm + b * scb;
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int m = m0 + tm * 4 + i, n = n0 + tn * 4 + j;
+      if (m < M && n < N) cb[(long long)m * N + n] = alpha * acc[i][j];
+    }
+}
+
+static hipError_t sgemm(int batch, int M, int N, int Kd, float alpha, const float* a, long long sab, int sam, int sak,
+                        const float* b, long long sbb, int sbk, int sbn, float* c, long long scb, hipStream_t s) {
+  dim3 grid((N + 63) / 64, (M + 63) / 64, batch);
+  k_sgemm<<<grid, 256, 0, s>>>(M, N, Kd, alpha, a, sab, sam, sak, b, sbb, sbk, sbn, c, scb);
+  return hipGetLastError();
+}
+
+// Row-wise softmax backward on the coarse score matrix, in place:
+//   sc  holds scale*Qc.Kc^T  -> becomes Ac  = exp(sc - lse_c[row])
+//   dsc holds dOc.Vc^T (dAc) -> becomes dSc = Ac * (dAc - sum_j Ac*dAc)
+// One wavefront per row, fixed reduction order.
+__global__ __launch_bounds__(256) void k_coarse_softmax_bwd(int rows, int Nc, const float* __restrict__ lse_c,
+                                                            float* __restrict__ sc, float* __restrict__ dsc) {
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (row >= rows) return;
+  float* s = sc + (long long)row * Nc;
+  float* ds = dsc + (long long)row * Nc;
+  const float lse = lse_c[row];
+  float dot = 0.f;
+  for (int j = lane; j < Nc; j += 64) {
+    const float a = fast_exp2((s[j] - lse) * kLog2e);
+    s[j] = a;
+    dot = fmaf(a, ds[j], dot);
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) dot += __shfl_xor(dot, o);
+  for (int j = lane; j < Nc; j += 64) ds[j] = s[j] * (ds[j] - dot);
+}
+
+// Coarse backward: dVc = Ac^T dOc, dQc = scale dSc Kc, dKc = scale dSc^T Qc.
+// `ac` and `dsc` are [BH,Nc,Nc] scratch.
+hipError_t launch_coarse_bwd(int BH, int Nc, int d, float scale, const float* qc, const float* kc, const float* vc,
+                             const float* lse_c, const float* doc, float* ac, float* dsc, float* dqc, float* dkc,
+                             float* dvc, hipStream_t s) {
+  const long long sx = (long long)Nc * d, ss = (long long)Nc * Nc;
+  hipError_t e;
+  // sc = scale * Qc Kc^T ; dAc = dOc Vc^T
+  if ((e = sgemm(BH, Nc, Nc, d, scale, qc, sx, d, 1, kc, sx, 1, d, ac, ss, s)) != hipSuccess) return e;
+  if ((e = sgemm(BH, Nc, Nc, d, 1.f, doc, sx, d, 1, vc, sx, 1, d, dsc, ss, s)) != hipSuccess) return e;
+  k_coarse_softmax_bwd<<<(BH * Nc + 3) / 4, 256, 0, s>>>(BH * Nc, Nc, lse_c, ac, dsc);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  // dVc[j][e] = sum_c Ac[c][j] dOc[c][e]
+  if ((e = sgemm(BH, Nc, d, Nc, 1.f, ac, ss, 1, Nc, doc, sx, d, 1, dvc, sx, s)) != hipSuccess) return e;
+  // dQc[c][e] = scale sum_j dSc[c][j] Kc[j][e]
+  if ((e = sgemm(BH, Nc, d, Nc, scale, dsc, ss, Nc, 1, kc, sx, d, 1, dqc, sx, s)) != hipSuccess) return e;
+  // dKc[j][e] = scale sum_c dSc[c][j] Qc[c][e]
+  return sgemm(BH, Nc, d, Nc, scale, dsc, ss, 1, Nc, qc, sx, d, 1, dkc, sx, s);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Transposed block map: for every key cube j of a (b,h), the ascending list of query cubes
+// whose index list contains j (CSR: row_ptr[bh][Nc+1], col[bh][Nc*K]).
+// One workgroup per (b,h) does a stable counting sort of the (query cube, key cube) pairs.
+// Wavefront w owns a contiguous range of query cubes; since the key cubes within one query
+// row are distinct, a wavefront can bump per-key counters row by row without atomics, and the
+// per-wavefront counters are combined by a prefix over w.  No float math, fully deterministic.
+constexpr int kMapCounters = 32768;
+constexpr int kMaxCubes = 4096;  // = 4 entries per thread of a 1024-thread scan
+__global__ __launch_bounds__(1024) void k_transpose_map(int Nc, int K, int W, const int32_t* __restrict__ idx,
+                                                        int32_t* __restrict__ row_ptr, int32_t* __restrict__ col) {
+  __shared__ int cnt[kMapCounters];   // [W][Nc]
+  __shared__ int total[kMaxCubes];
+  __shared__ int wsum[16];
+  const int bh = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int32_t* my = idx + (long long)bh * Nc * K;
+  int32_t* rp = row_ptr + (long long)bh * (Nc + 1);
+  int32_t* cl = col + (long long)bh * Nc * K;
+  const int per = (Nc + W - 1) / W;
+  const int c_lo = min(Nc, wave * per), c_hi = min(Nc, c_lo + per);
+
+  for (int i = tid; i < W * Nc; i += 1024) cnt[i] = 0;
+  __syncthreads();
+  if (wave < W)
+    for (int c = c_lo; c < c_hi; ++c)
+      for (int r = lane; r < K; r += 64) cnt[wave * Nc + my[(long long)c * K + r]] += 1;
+  __syncthreads();
+  // per key cube: exclusive prefix over wavefronts, total in-degree
+  for (int j = tid; j < Nc; j += 1024) {
+    int run = 0;
+    for (int w = 0; w < W; ++w) {
+      int t = cnt[w * Nc + j];
+      cnt[w * Nc + j] = run;
+      run += t;
+    }
+    total[j] = run;
+  }
+  __syncthreads();
+  // exclusive scan of total[0..Nc) -> row_ptr.  Each thread scans a contiguous slice of 4.
+  {
+    const int j0 = tid * 4;
+    int v[4], sum = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      v[i] = (j0 + i < Nc) ? total[j0 + i] : 0;
+      sum += v[i];
+    }
+    int incl = sum;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      int t = __shfl_up(incl, o);
+      if (lane >= o) incl += t;
+    }
+    if (lane == 63) wsum[wave] = incl;
+    __syncthreads();
+    int base = 0;
+    for (int w = 0; w < wave; ++w) base += wsum[w];
+    int run = base + incl - sum;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      if (j0 + i < Nc) {
+        total[j0 + i] = run;  // now the row start
+        rp[j0 + i] = run;
+      }
+      run += v[i];
+    }
+    if (tid == 1023) rp[Nc] = run;
+  }
+  __syncthreads();
+  if (wave < W)
+    for (int c = c_lo; c < c_hi; ++c)
+      for (int r = lane; r < K; r += 64) {
+        const int j = my[(long long)c * K + r];
+        const int pos = total[j] + cnt[wave * Nc + j];
+        cnt[wave * Nc + j] += 1;
+        cl[pos] = c;
+      }
+}
+
+hipError_t launch_transpose_map(int BH, int Nc, int K, const int32_t* idx, int32_t* row_ptr, int32_t* col,
+                                hipStream_t s) {
+  int W = kMapCounters / Nc;
+  if (W > 16) W = 16;
+  k_transpose_map<<<BH, 1024, 0, s>>>(Nc, K, W, idx, row_ptr, col);
+  return hipGetLastError();
+}
+
+}  // namespace vsa

@@ -1,0 +1,331 @@
+// Fine stage backward (Sec. 2.4 states a backward kernel exists; this is FlashAttention-style
+// recomputation of P from the saved log-sum-exp, on the block-sparse pattern):
+//   P_ij = exp(S_ij - lse_i),  dP_ij = dOf_i . v_j,  dS_ij = P_ij (dP_ij - Delta_i)
+//   dQ_i = scale sum_j dS_ij k_j      (query-tile-major pass over the index list)
+//   dK_j = scale sum_i dS_ij q_i,  dV_j = sum_i P_ij dOf_i   (key-tile-major pass over the
+//                                                             transposed block map)
+// Both passes add the pooled-path gradient dXc[cube]/cnt to every valid row in their epilogue
+// and write zeros to pad rows.  Work split and operand layouts follow the forward kernel: all
+// products are computed transposed, the streamed tiles sit in a double-buffered LDS stage, the
+// resident tile sits in registers, and each wavefront pair owning the same output rows is
+// merged once at the end.
+#include "fine_tile.h"
+#include "vsa_kernels.h"
+
+namespace vsa {
+
+// ---------------------------------------------------------------------------------------------
+// dQ pass: one workgroup per (b, h, query cube); streams the K selected (K tile, V tile) pairs.
+// Wavefront (qh, kh): query rows qh*32..+31, key rows kh*32..+31 of each tile.
+template <int D>
+__global__ __launch_bounds__(256, 2) void k_fine_bwd_dq(int Nc, int K, float sl2, float scale, const uint4* __restrict__ q,
+                                                        const uint4* __restrict__ k, const uint4* __restrict__ v,
+                                                        const uint4* __restrict__ dof, const int32_t* __restrict__ idx,
+                                                        const float* __restrict__ lse_f, const float* __restrict__ delta,
+                                                        const float* __restrict__ dqc, const uint64_t* __restrict__ mask,
+                                                        uint4* __restrict__ dq) {
+  using TL = Tile<D>;
+  constexpr int CPR = TL::CPR, KS = D / 16, DVB = D / 32, LPT = TL::LPT;
+  constexpr int OS = D + 4;
+  constexpr int STAGE = 2 * TL::BYTES;
+  constexpr int MERGE = 4 * 32 * OS * 4;
+  constexpr int LDS = (2 * STAGE > MERGE) ? 2 * STAGE : MERGE;
+  __shared__ __attribute__((aligned(16))) unsigned char smem[LDS];
+
+  const int c = blockIdx.x % Nc;
+  const long long bh = blockIdx.x / Nc;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int qh = wave & 1, kh = wave >> 1, l32 = lane & 31, h = lane >> 5;
+  const long long rows0 = bh * (long long)Nc * kTile;
+  const int32_t* my_idx = idx + (bh * Nc + c) * (long long)K;
+  const uint64_t qmask = mask[c];
+
+  const long long qrow_g = rows0 + c * kTile + qh * 32 + l32;
+  bf16x8 qreg[KS], doreg[KS];
+  {
+    const uint4* qrow = q + qrow_g * CPR;
+    const uint4* dorow = dof + qrow_g * CPR;
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+      qreg[s] = __builtin_bit_cast(bf16x8, qrow[2 * s + h]);
+      doreg[s] = __builtin_bit_cast(bf16x8, dorow[2 * s + h]);
+    }
+  }
+  // pad query rows: lse = +inf makes P = 0, so they contribute nothing
+  const bool qvalid = (qmask >> (qh * 32 + l32)) & 1;
+  const float lse2 = qvalid ? lse_f[qrow_g] * kLog2e : INFINITY;
+  const float dl = qvalid ? delta[qrow_g] : 0.f;
+
+  uint4 pk[LPT], pv[LPT];
+  int jt = my_idx[0];
+  TL::gload(k, rows0 + (long long)jt * kTile, tid, pk);
+  TL::gload(v, rows0 + (long long)jt * kTile, tid, pv);
+  TL::lstore(smem, tid, pk);
+  TL::lstore(smem + TL::BYTES, tid, pv);
+  __syncthreads();
+
+  f32x16 acc[DVB];
+#pragma unroll
+  for (int x = 0; x < DVB; ++x)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[x][i] = 0.f;
+
+  for (int t = 0; t < K; ++t) {
+    const uint64_t kmask = mask[jt];
+    if (t + 1 < K) {
+      jt = my_idx[t + 1];
+      TL::gload(k, rows0 + (long long)jt * kTile, tid, pk);
+      TL::gload(v, rows0 + (long long)jt * kTile, tid, pv);
+    }
+    const unsigned char* Ks = smem + (t & 1) * STAGE;
+    const unsigned char* Vs = Ks + TL::BYTES;
+
+    f32x16 sacc, dpacc;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) { sacc[i] = 0.f; dpacc[i] = 0.f; }
+#pragma unroll
+    for (int s = 0; s < KS; ++s) sacc = mfma32(TL::rowmajor_operand(Ks, kh * 32, s, lane), qreg[s], sacc);
+#pragma unroll
+    for (int s = 0; s < KS; ++s) dpacc = mfma32(TL::rowmajor_operand(Vs, kh * 32, s, lane), doreg[s], dpacc);
+
+    const uint32_t mh = (uint32_t)(kmask >> (kh * 32));
+    float ds[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      float p = fast_exp2(fmaf(sacc[i], sl2, -lse2));
+      if (!((mh >> (8 * (i / 4) + 4 * h + (i % 4))) & 1)) p = 0.f;
+      ds[i] = p * (dpacc[i] - dl);
+    }
+    const bf16x8 b0 = acc_to_operand(ds), b1 = acc_to_operand(ds + 8);
+#pragma unroll
+    for (int x = 0; x < DVB; ++x) {
+      acc[x] = mfma32(TL::transposed_operand(Ks, kh * 32, 0, x * 32, lane), b0, acc[x]);
+      acc[x] = mfma32(TL::transposed_operand(Ks, kh * 32, 1, x * 32, lane), b1, acc[x]);
+    }
+
+    if (t + 1 < K) {
+      unsigned char* nxt = smem + ((t + 1) & 1) * STAGE;
+      TL::lstore(nxt, tid, pk);
+      TL::lstore(nxt + TL::BYTES, tid, pv);
+    }
+    __syncthreads();
+  }
+
+  float* Op = (float*)smem + wave * 32 * OS;
+#pragma unroll
+  for (int x = 0; x < DVB; ++x)
+#pragma unroll
+    for (int g4 = 0; g4 < 4; ++g4) {
+      float4 val = make_float4(acc[x][4 * g4], acc[x][4 * g4 + 1], acc[x][4 * g4 + 2], acc[x][4 * g4 + 3]);
+      *(float4*)&Op[l32 * OS + x * 32 + 8 * g4 + 4 * h] = val;
+    }
+  __syncthreads();
+
+  const float inv_cnt = 1.0f / (float)__popcll(qmask);
+  const float* dqcr = dqc + (bh * Nc + c) * D;
+#pragma unroll
+  for (int it = 0; it < LPT; ++it) {
+    const int item = it * 256 + tid, r = item / CPR, ch = item % CPR;
+    const int wa = r >> 5, wb = wa + 2, ql = r & 31;
+    const float* Oa = (const float*)smem + (wa * 32 + ql) * OS + ch * 8;
+    const float* Ob = (const float*)smem + (wb * 32 + ql) * OS + ch * 8;
+    uint4 ov = make_uint4(0, 0, 0, 0);
+    if ((qmask >> r) & 1) {
+      float res[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) res[e] = fmaf(Oa[e] + Ob[e], scale, dqcr[ch * 8 + e] * inv_cnt);
+      ov = pack8(res);
+    }
+    dq[(rows0 + c * kTile + r) * CPR + ch] = ov;
+  }
+}
+
+hipError_t launch_fine_bwd_dq(int BH, int Nc, int d, int K, float scale, const void* q, const void* k, const void* v,
+                              const void* dof, const int32_t* idx, const float* lse_f, const float* delta,
+                              const float* dqc, const uint64_t* mask, void* dq, hipStream_t s) {
+  const float sl2 = scale * kLog2e;
+  const unsigned grid = (unsigned)(BH * Nc);
+  if (d == 128)
+    k_fine_bwd_dq<128><<<grid, 256, 0, s>>>(Nc, K, sl2, scale, (const uint4*)q, (const uint4*)k, (const uint4*)v,
+                                            (const uint4*)dof, idx, lse_f, delta, dqc, mask, (uint4*)dq);
+  else
+    k_fine_bwd_dq<64><<<grid, 256, 0, s>>>(Nc, K, sl2, scale, (const uint4*)q, (const uint4*)k, (const uint4*)v,
+                                           (const uint4*)dof, idx, lse_f, delta, dqc, mask, (uint4*)dq);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// dK/dV pass: one workgroup per (b, h, key cube); streams the (Q tile, dOf tile) pairs of the
+// query cubes that selected this key cube.  Wavefront (kh, qh): key rows kh*32..+31 (its output
+// rows; K and V of those rows stay in registers), query rows qh*32..+31 of each streamed tile.
+// Here S (not S^T) is formed, so a lane holds one key column and 16 query rows; lse and Delta
+// of the streamed query tile are staged in LDS next to the tiles.
+template <int D>
+__global__ __launch_bounds__(256, 1) void k_fine_bwd_dkv(int Nc, int K, float sl2, float scale, const uint4* __restrict__ q,
+                                                         const uint4* __restrict__ k, const uint4* __restrict__ v,
+                                                         const uint4* __restrict__ dof,
+                                                         const int32_t* __restrict__ row_ptr,
+                                                         const int32_t* __restrict__ col,
+                                                         const float* __restrict__ lse_f, const float* __restrict__ delta,
+                                                         const float* __restrict__ dkc, const float* __restrict__ dvc,
+                                                         const uint64_t* __restrict__ mask, uint4* __restrict__ dk,
+                                                         uint4* __restrict__ dv) {
+  using TL = Tile<D>;
+  constexpr int CPR = TL::CPR, KS = D / 16, DVB = D / 32, LPT = TL::LPT;
+  constexpr int OS = D + 4;
+  constexpr int STAGE = 2 * TL::BYTES + 2 * kTile * 4;  // Q tile, dOf tile, lse2[64], delta[64]
+  constexpr int MERGE = 4 * 32 * OS * 4;
+  constexpr int LDS = (2 * STAGE > MERGE) ? 2 * STAGE : MERGE;
+  __shared__ __attribute__((aligned(16))) unsigned char smem[LDS];
+
+  const int j = blockIdx.x % Nc;
+  const long long bh = blockIdx.x / Nc;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int kh = wave & 1, qh = wave >> 1, l32 = lane & 31, h = lane >> 5;
+  const long long rows0 = bh * (long long)Nc * kTile;
+  const uint64_t kmask = mask[j];
+  const int32_t* rp = row_ptr + bh * (Nc + 1);
+  const int beg = rp[j], end = rp[j + 1];
+  const int32_t* my_col = col + bh * (long long)Nc * K;
+
+  bf16x8 kreg[KS], vreg[KS];
+  {
+    const uint4* krow = k + (rows0 + j * kTile + kh * 32 + l32) * CPR;
+    const uint4* vrow = v + (rows0 + j * kTile + kh * 32 + l32) * CPR;
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+      kreg[s] = __builtin_bit_cast(bf16x8, krow[2 * s + h]);
+      vreg[s] = __builtin_bit_cast(bf16x8, vrow[2 * s + h]);
+    }
+  }
+  const bool kvalid = (kmask >> (kh * 32 + l32)) & 1;
+
+  f32x16 dka[DVB], dva[DVB];
+#pragma unroll
+  for (int x = 0; x < DVB; ++x)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) { dka[x][i] = 0.f; dva[x][i] = 0.f; }
+
+  uint4 pq[LPT], pd[LPT];
+  float pl = 0.f, pdl = 0.f;  // threads 0..63 carry lse2 / delta of one query row
+  auto fetch = [&](int cq) {
+    TL::gload(q, rows0 + (long long)cq * kTile, tid, pq);
+    TL::gload(dof, rows0 + (long long)cq * kTile, tid, pd);
+    if (tid < kTile) {
+      const bool qv = (mask[cq] >> tid) & 1;
+      pl = qv ? lse_f[rows0 + (long long)cq * kTile + tid] * kLog2e : INFINITY;
+      pdl = qv ? delta[rows0 + (long long)cq * kTile + tid] : 0.f;
+    }
+  };
+  auto stash = [&](unsigned char* stage) {
+    TL::lstore(stage, tid, pq);
+    TL::lstore(stage + TL::BYTES, tid, pd);
+    if (tid < kTile) {
+      ((float*)(stage + 2 * TL::BYTES))[tid] = pl;
+      ((float*)(stage + 2 * TL::BYTES))[kTile + tid] = pdl;
+    }
+  };
+
+  if (beg < end) {
+    fetch(my_col[beg]);
+    stash(smem);
+  }
+  __syncthreads();
+
+  for (int t = beg; t < end; ++t) {
+    if (t + 1 < end) fetch(my_col[t + 1]);
+    const unsigned char* st = smem + ((t - beg) & 1) * STAGE;
+    const unsigned char* Qs = st;
+    const unsigned char* Ds = st + TL::BYTES;
+    const float* ls = (const float*)(st + 2 * TL::BYTES);
+
+    f32x16 sacc, dpacc;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) { sacc[i] = 0.f; dpacc[i] = 0.f; }
+#pragma unroll
+    for (int s = 0; s < KS; ++s) sacc = mfma32(TL::rowmajor_operand(Qs, qh * 32, s, lane), kreg[s], sacc);
+#pragma unroll
+    for (int s = 0; s < KS; ++s) dpacc = mfma32(TL::rowmajor_operand(Ds, qh * 32, s, lane), vreg[s], dpacc);
+
+    float p[16], ds[16];
+#pragma unroll
+    for (int g4 = 0; g4 < 4; ++g4) {
+      const float4 l4 = *(const float4*)&ls[qh * 32 + 8 * g4 + 4 * h];
+      const float4 d4 = *(const float4*)&ls[kTile + qh * 32 + 8 * g4 + 4 * h];
+      const float lv[4] = {l4.x, l4.y, l4.z, l4.w}, dvv[4] = {d4.x, d4.y, d4.z, d4.w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int i = 4 * g4 + e;
+        float pi = fast_exp2(fmaf(sacc[i], sl2, -lv[e]));
+        if (!kvalid) pi = 0.f;
+        p[i] = pi;
+        ds[i] = pi * (dpacc[i] - dvv[e]);
+      }
+    }
+    const bf16x8 pb0 = acc_to_operand(p), pb1 = acc_to_operand(p + 8);
+    const bf16x8 sb0 = acc_to_operand(ds), sb1 = acc_to_operand(ds + 8);
+#pragma unroll
+    for (int x = 0; x < DVB; ++x) {
+      dva[x] = mfma32(TL::transposed_operand(Ds, qh * 32, 0, x * 32, lane), pb0, dva[x]);
+      dva[x] = mfma32(TL::transposed_operand(Ds, qh * 32, 1, x * 32, lane), pb1, dva[x]);
+      dka[x] = mfma32(TL::transposed_operand(Qs, qh * 32, 0, x * 32, lane), sb0, dka[x]);
+      dka[x] = mfma32(TL::transposed_operand(Qs, qh * 32, 1, x * 32, lane), sb1, dka[x]);
+    }
+
+    if (t + 1 < end) stash(smem + ((t + 1 - beg) & 1) * STAGE);
+    __syncthreads();
+  }
+
+  // merge the two query halves; dK first, then dV through the same buffer
+  const float inv_cnt = 1.0f / (float)__popcll(kmask);
+  for (int pass = 0; pass < 2; ++pass) {
+    float* Op = (float*)smem + wave * 32 * OS;
+#pragma unroll
+    for (int x = 0; x < DVB; ++x)
+#pragma unroll
+      for (int g4 = 0; g4 < 4; ++g4) {
+        const f32x16& a = pass == 0 ? dka[x] : dva[x];
+        float4 val = make_float4(a[4 * g4], a[4 * g4 + 1], a[4 * g4 + 2], a[4 * g4 + 3]);
+        *(float4*)&Op[l32 * OS + x * 32 + 8 * g4 + 4 * h] = val;
+      }
+    __syncthreads();
+    const float* pooled = (pass == 0 ? dkc : dvc) + (bh * Nc + j) * D;
+    const float mul = pass == 0 ? scale : 1.0f;
+    uint4* dst = pass == 0 ? dk : dv;
+#pragma unroll
+    for (int it = 0; it < LPT; ++it) {
+      const int item = it * 256 + tid, r = item / CPR, ch = item % CPR;
+      const int wa = r >> 5, wb = wa + 2, kl = r & 31;  // waves (kh = r/32, qh = 0) and (kh, qh = 1)
+      const float* Oa = (const float*)smem + (wa * 32 + kl) * OS + ch * 8;
+      const float* Ob = (const float*)smem + (wb * 32 + kl) * OS + ch * 8;
+      uint4 ov = make_uint4(0, 0, 0, 0);
+      if ((kmask >> r) & 1) {
+        float res[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) res[e] = fmaf(Oa[e] + Ob[e], mul, pooled[ch * 8 + e] * inv_cnt);
+        ov = pack8(res);
+      }
+      dst[(rows0 + j * kTile + r) * CPR + ch] = ov;
+    }
+    __syncthreads();
+  }
+}
+
+hipError_t launch_fine_bwd_dkv(int BH, int Nc, int d, int K, float scale, const void* q, const void* k, const void* v,
+                               const void* dof, const int32_t* row_ptr, const int32_t* col, const float* lse_f,
+                               const float* delta, const float* dkc, const float* dvc, const uint64_t* mask, void* dk,
+                               void* dv, hipStream_t s) {
+  const float sl2 = scale * kLog2e;
+  const unsigned grid = (unsigned)(BH * Nc);
+  if (d == 128)
+    k_fine_bwd_dkv<128><<<grid, 256, 0, s>>>(Nc, K, sl2, scale, (const uint4*)q, (const uint4*)k, (const uint4*)v,
+                                             (const uint4*)dof, row_ptr, col, lse_f, delta, dkc, dvc, mask, (uint4*)dk,
+                                             (uint4*)dv);
+  else
+    k_fine_bwd_dkv<64><<<grid, 256, 0, s>>>(Nc, K, sl2, scale, (const uint4*)q, (const uint4*)k, (const uint4*)v,
+                                            (const uint4*)dof, row_ptr, col, lse_f, delta, dkc, dvc, mask, (uint4*)dk,
+                                            (uint4*)dv);
+  return hipGetLastError();
+}
+
+}  // namespace vsa

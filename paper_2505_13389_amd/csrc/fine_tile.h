@@ -1,0 +1,78 @@
+// LDS tile layout and MFMA operand access shared by the fine-stage kernels.
+//
+// A tile is 64 token rows x D bf16, row-major, stored in LDS WITHOUT padding; the 16-byte
+// chunk c of row r lives at chunk position c ^ swz(r).  The swizzle is chosen so that both
+// access patterns of the 32x32x16 MFMA operands are spread over distinct 16-byte bank groups:
+//   - row-major reads (lane = row, same chunk): 16 consecutive rows hit 16 distinct slots;
+//   - transposed reads (ds_read_b64_tr_b16: 4 consecutive rows x 64 contiguous bytes): the
+//     4 rows land in 4 different 64-byte groups of the 256-byte bank line.
+#pragma once
+#include "vsa_common.h"
+
+namespace vsa {
+
+typedef bf16x4 __attribute__((address_space(3))) * lds_bf16x4_ptr;
+
+template <int D>
+struct Tile {
+  static constexpr int CPR = D / 8;               // 16-byte chunks per row
+  static constexpr int ROW_BYTES = D * 2;
+  static constexpr int BYTES = kTile * ROW_BYTES;
+  static constexpr int LPT = kTile * CPR / 256;    // chunks per thread when 256 threads copy a tile
+
+  __device__ static __forceinline__ int swz(int r) {
+    if (D == 128) return ((r & 3) << 2) | ((r >> 2) & 3);
+    return (((r >> 1) & 1) << 2) | ((r >> 2) & 3);
+  }
+  __device__ static __forceinline__ int off(int r, int c) { return r * ROW_BYTES + ((c ^ swz(r)) << 4); }
+
+  // 256 threads fetch one tile (rows row0..row0+63 of `src`, CPR chunks per row) into registers.
+  __device__ static __forceinline__ void gload(const uint4* __restrict__ src, long long row0, int tid, uint4* regs) {
+#pragma unroll
+    for (int it = 0; it < LPT; ++it) {
+      int item = it * 256 + tid;
+      regs[it] = src[(row0 + item / CPR) * CPR + item % CPR];
+    }
+  }
+  __device__ static __forceinline__ void lstore(unsigned char* tile, int tid, const uint4* regs) {
+#pragma unroll
+    for (int it = 0; it < LPT; ++it) {
+      int item = it * 256 + tid;
+      *(uint4*)(tile + off(item / CPR, item % CPR)) = regs[it];
+    }
+  }
+
+  // MFMA 32x32x16 operand whose 32-index is the tile ROW and whose contraction index runs
+  // along D: lane l supplies tile[row0 + l%32][16*s + 8*(l/32) .. +7]  (one 16-byte read).
+  __device__ static __forceinline__ bf16x8 rowmajor_operand(const unsigned char* tile, int row0, int s, int lane) {
+    int r = row0 + (lane & 31);
+    return *(const bf16x8*)(tile + off(r, 2 * s + (lane >> 5)));
+  }
+
+  // MFMA 32x32x16 operand whose 32-index runs along D (columns col0..col0+31) and whose
+  // contraction index is the tile ROW, in the order the 32x32 accumulator layout produces:
+  // for k-step s, lane half h = l/32 and j = 0..7 the row is row0 + 16*s + 8*(j/4) + 4*h + j%4.
+  // Two transposing 8-byte LDS reads; in each 16-lane block, lanes 4e..4e+3 read row e.
+  __device__ static __forceinline__ bf16x8 transposed_operand(const unsigned char* tile, int row0, int s, int col0,
+                                                              int lane) {
+    int L = lane & 15;
+    int r1 = row0 + 16 * s + 4 * (lane >> 5) + (L >> 2);
+    int col = col0 + ((lane >> 4) & 1) * 16 + 4 * (L & 3);
+    int ch = col >> 3, sub = (col & 7) * 2;
+    bf16x4 a0 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4_ptr)(tile + off(r1, ch) + sub));
+    bf16x4 a1 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4_ptr)(tile + off(r1 + 8, ch) + sub));
+    return __builtin_shufflevector(a0, a1, 0, 1, 2, 3, 4, 5, 6, 7);
+  }
+};
+
+// fp32 accumulator values [8s .. 8s+7] -> bf16 operand of k-step s (see transposed_operand).
+__device__ __forceinline__ bf16x8 acc_to_operand(const float* p) {
+  uint4 u = pack8(p);
+  return __builtin_bit_cast(bf16x8, u);
+}
+
+__device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+}  // namespace vsa

@@ -1,0 +1,113 @@
+// Token permutation (raster <-> cube-contiguous), cube validity masks and mean pooling.
+// All three are pure data movement / fp32 adds: HBM-bandwidth bound, 16-byte accesses.
+#include "vsa_kernels.h"
+
+namespace vsa {
+
+// One thread per 16-byte chunk of a destination row.
+// Forward: destination = tiled row; its source is the raster row of the same (t,h,w), or
+// zeros for a pad slot.  Inverse: destination = raster row.  (Sec. 2.2 index equation.)
+template <bool kInverse>
+__global__ __launch_bounds__(256) void k_tile_permute(Geo g, int BH, int chunks_per_row, const uint4* __restrict__ src,
+                                                      uint4* __restrict__ dst) {
+  const long long rows_dst = kInverse ? (long long)g.L : g.Np;
+  const long long total = (long long)BH * rows_dst * chunks_per_row;
+  long long gid = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (gid >= total) return;
+  int ch = (int)(gid % chunks_per_row);
+  long long row = gid / chunks_per_row;
+  int n = (int)(row % rows_dst);
+  long long bh = row / rows_dst;
+  if (!kInverse) {
+    int c = n / kTile, in = n % kTile;
+    int cw = c % g.Nw, chh = (c / g.Nw) % g.Nh, ct = c / (g.Nw * g.Nh);
+    int pw = in % g.Cw, ph = (in / g.Cw) % g.Ch, pt = in / (g.Cw * g.Ch);
+    int t = ct * g.Ct + pt, h = chh * g.Ch + ph, w = cw * g.Cw + pw;
+    uint4 val = make_uint4(0, 0, 0, 0);
+    if (t < g.T && h < g.Hh && w < g.W) {
+      long long nr = ((long long)t * g.Hh + h) * g.W + w;
+      val = src[(bh * g.L + nr) * chunks_per_row + ch];
+    }
+    dst[gid] = val;
+  } else {
+    int w = n % g.W, h = (n / g.W) % g.Hh, t = n / (g.W * g.Hh);
+    long long c = ((long long)(t / g.Ct) * g.Nh + (h / g.Ch)) * g.Nw + (w / g.Cw);
+    int in = ((t % g.Ct) * g.Ch + (h % g.Ch)) * g.Cw + (w % g.Cw);
+    dst[gid] = src[(bh * g.Np + c * kTile + in) * chunks_per_row + ch];
+  }
+}
+
+hipError_t launch_tile_permute(const Geo& g, int BH, int d, const void* src, void* dst, bool inverse, hipStream_t s) {
+  int cpr = d / 8;
+  long long total = (long long)BH * (inverse ? (long long)g.L : g.Np) * cpr;
+  unsigned blocks = (unsigned)((total + 255) / 256);
+  if (inverse)
+    k_tile_permute<true><<<blocks, 256, 0, s>>>(g, BH, cpr, (const uint4*)src, (uint4*)dst);
+  else
+    k_tile_permute<false><<<blocks, 256, 0, s>>>(g, BH, cpr, (const uint4*)src, (uint4*)dst);
+  return hipGetLastError();
+}
+
+__global__ void k_cube_masks(Geo g, uint64_t* __restrict__ mask) {
+  int c = blockIdx.x * blockDim.x + threadIdx.x;
+  if (c < g.Nc) mask[c] = cube_valid_mask(g, c);
+}
+
+hipError_t launch_cube_masks(const Geo& g, uint64_t* mask, hipStream_t s) {
+  k_cube_masks<<<(g.Nc + 255) / 256, 256, 0, s>>>(g, mask);
+  return hipGetLastError();
+}
+
+// Mean over the valid tokens of each cube (Sec. 2.2 coarse stage), fp32 result.
+// One workgroup per (tensor, b*h, cube): 64 rows x D bf16 in, D floats out.  Thread t owns
+// 16-byte chunk t % (D/8) of rows t / (D/8), t / (D/8) + 256/(D/8), ...; the partial sums
+// are added across row groups in a fixed order, so the result is deterministic.
+template <int D>
+__global__ __launch_bounds__(256) void k_pool(int Nc, long long Np, const uint64_t* __restrict__ mask,
+                                              const uint4* __restrict__ q, const uint4* __restrict__ k,
+                                              const uint4* __restrict__ v, float* __restrict__ qc,
+                                              float* __restrict__ kc, float* __restrict__ vc) {
+  constexpr int CPR = D / 8;        // chunks per row
+  constexpr int RG = 256 / CPR;     // row groups
+  constexpr int RPT = kTile / RG;   // rows per thread
+  __shared__ float part[RG][D + 4];
+  const int c = blockIdx.x % Nc;
+  const long long bh = blockIdx.x / Nc;
+  const uint4* src = blockIdx.y == 0 ? q : (blockIdx.y == 1 ? k : v);
+  float* dst = blockIdx.y == 0 ? qc : (blockIdx.y == 1 ? kc : vc);
+  const uint64_t m = mask[c];
+  const int ch = threadIdx.x % CPR, rg = threadIdx.x / CPR;
+  float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  const uint4* base = src + (bh * Np + (long long)c * kTile) * CPR;
+#pragma unroll
+  for (int i = 0; i < RPT; ++i) {
+    int r = rg + i * RG;
+    uint4 u = base[r * CPR + ch];
+    if ((m >> r) & 1) {
+      float f[8];
+      unpack8(u, f);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[e] += f[e];
+    }
+  }
+#pragma unroll
+  for (int e = 0; e < 8; ++e) part[rg][ch * 8 + e] = acc[e];
+  __syncthreads();
+  if (threadIdx.x < D) {
+    float s = 0;
+    for (int r = 0; r < RG; ++r) s += part[r][threadIdx.x];
+    dst[(bh * Nc + c) * D + threadIdx.x] = s / (float)__popcll(m);
+  }
+}
+
+hipError_t launch_pool(const Geo& g, int BH, int d, const uint64_t* mask, const void* q, const void* k, const void* v,
+                       float* qc, float* kc, float* vc, hipStream_t s) {
+  dim3 grid((unsigned)(BH * g.Nc), 3);
+  if (d == 128)
+    k_pool<128><<<grid, 256, 0, s>>>(g.Nc, g.Np, mask, (const uint4*)q, (const uint4*)k, (const uint4*)v, qc, kc, vc);
+  else
+    k_pool<64><<<grid, 256, 0, s>>>(g.Nc, g.Np, mask, (const uint4*)q, (const uint4*)k, (const uint4*)v, qc, kc, vc);
+  return hipGetLastError();
+}
+
+}  // namespace vsa

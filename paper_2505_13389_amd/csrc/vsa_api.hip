@@ -1,0 +1,223 @@
+// C ABI of libvsa.so: argument validation, workspace carving and kernel sequencing.
+// See include/vsa.h for the contract of every entry point.
+#include "../../include/vsa.h"
+
+#include "vsa_kernels.h"
+
+namespace {
+
+using vsa::Geo;
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+int check_params(const vsa_params_t* p, Geo* g) {
+  if (!p) return VSA_ERR_NULL;
+  if (p->B < 1 || p->H < 1 || p->T < 1 || p->Hh < 1 || p->W < 1 || p->Ct < 1 || p->Ch < 1 || p->Cw < 1 || p->d < 1)
+    return VSA_ERR_BAD_ARG;
+  if ((long long)p->Ct * p->Ch * p->Cw != vsa::kTile) return VSA_ERR_UNSUPPORTED;
+  if (p->d != 64 && p->d != 128) return VSA_ERR_UNSUPPORTED;
+  g->T = p->T; g->Hh = p->Hh; g->W = p->W;
+  g->Ct = p->Ct; g->Ch = p->Ch; g->Cw = p->Cw;
+  g->Nt = (p->T + p->Ct - 1) / p->Ct;
+  g->Nh = (p->Hh + p->Ch - 1) / p->Ch;
+  g->Nw = (p->W + p->Cw - 1) / p->Cw;
+  long long nc = (long long)g->Nt * g->Nh * g->Nw;
+  if (nc > VSA_MAX_CUBES) return VSA_ERR_UNSUPPORTED;
+  long long L = (long long)p->T * p->Hh * p->W;
+  g->Nc = (int)nc;
+  g->L = (int)L;
+  g->Np = nc * vsa::kTile;
+  if ((long long)p->B * p->H * nc > 0x7fffffffLL / 4) return VSA_ERR_UNSUPPORTED;  // grid sizes stay in 32 bits
+  return VSA_OK;
+}
+
+int check_topk(const vsa_params_t* p, const Geo& g) {
+  return (p->topk < 1 || p->topk > g.Nc) ? VSA_ERR_BAD_ARG : VSA_OK;
+}
+
+bool misaligned(const void* ptr) { return ptr && ((uintptr_t)ptr & 15u); }
+
+float scale_of(const vsa_params_t* p) { return p->softmax_scale > 0.f ? p->softmax_scale : 1.0f / sqrtf((float)p->d); }
+
+// Bump allocator over the caller's workspace.
+struct Carver {
+  unsigned char* base;
+  size_t used = 0;
+  explicit Carver(void* b) : base((unsigned char*)b) {}
+  template <typename T>
+  T* take(size_t count) {
+    T* r = (T*)(base + used);
+    used += align_up(count * sizeof(T));
+    return r;
+  }
+};
+
+struct FwdWs {
+  uint64_t* mask;
+  float *qc, *kc, *vc, *oc, *lse_c;
+  int32_t* idx;
+  size_t bytes;
+};
+FwdWs carve_fwd(const vsa_params_t* p, const Geo& g, void* ws) {
+  Carver c(ws);
+  size_t bh = (size_t)p->B * p->H;
+  FwdWs w;
+  w.mask = c.take<uint64_t>(g.Nc);
+  w.qc = c.take<float>(bh * g.Nc * p->d);
+  w.kc = c.take<float>(bh * g.Nc * p->d);
+  w.vc = c.take<float>(bh * g.Nc * p->d);
+  w.oc = c.take<float>(bh * g.Nc * p->d);
+  w.lse_c = c.take<float>(bh * g.Nc);
+  w.idx = c.take<int32_t>(bh * g.Nc * p->topk);
+  w.bytes = c.used;
+  return w;
+}
+
+struct BwdWs {
+  uint64_t* mask;
+  float *qc, *kc, *vc, *delta, *doc, *ac, *dsc, *dqc, *dkc, *dvc;
+  void* dof;
+  int32_t *row_ptr, *col;
+  size_t bytes;
+};
+BwdWs carve_bwd(const vsa_params_t* p, const Geo& g, void* ws) {
+  Carver c(ws);
+  size_t bh = (size_t)p->B * p->H;
+  BwdWs w;
+  w.mask = c.take<uint64_t>(g.Nc);
+  w.qc = c.take<float>(bh * g.Nc * p->d);
+  w.kc = c.take<float>(bh * g.Nc * p->d);
+  w.vc = c.take<float>(bh * g.Nc * p->d);
+  w.delta = c.take<float>(bh * g.Np);
+  w.doc = c.take<float>(bh * g.Nc * p->d);
+  w.ac = c.take<float>(bh * g.Nc * g.Nc);
+  w.dsc = c.take<float>(bh * g.Nc * g.Nc);
+  w.dqc = c.take<float>(bh * g.Nc * p->d);
+  w.dkc = c.take<float>(bh * g.Nc * p->d);
+  w.dvc = c.take<float>(bh * g.Nc * p->d);
+  w.dof = c.take<uint16_t>(bh * g.Np * p->d);
+  w.row_ptr = c.take<int32_t>(bh * (g.Nc + 1));
+  w.col = c.take<int32_t>(bh * g.Nc * p->topk);
+  w.bytes = c.used;
+  return w;
+}
+
+#define VSA_TRY(expr)                      \
+  do {                                     \
+    if ((expr) != hipSuccess) return VSA_ERR_HIP; \
+  } while (0)
+
+}  // namespace
+
+extern "C" {
+
+int vsa_padded_tokens(const vsa_params_t* p, int64_t* Np, int32_t* Nc) {
+  Geo g;
+  int rc = check_params(p, &g);
+  if (rc != VSA_OK) return rc;
+  if (Np) *Np = g.Np;
+  if (Nc) *Nc = g.Nc;
+  return VSA_OK;
+}
+
+size_t vsa_workspace_bytes(const vsa_params_t* p, int backward) {
+  Geo g;
+  if (check_params(p, &g) != VSA_OK || check_topk(p, g) != VSA_OK) return 0;
+  return backward ? carve_bwd(p, g, nullptr).bytes : carve_fwd(p, g, nullptr).bytes;
+}
+
+int vsa_tile_permute(const vsa_params_t* p, const void* src, void* dst, int inverse, void* hip_stream) {
+  Geo g;
+  int rc = check_params(p, &g);
+  if (rc != VSA_OK) return rc;
+  if (!src || !dst) return VSA_ERR_NULL;
+  if (misaligned(src) || misaligned(dst)) return VSA_ERR_ALIGN;
+  VSA_TRY(vsa::launch_tile_permute(g, p->B * p->H, p->d, src, dst, inverse != 0, (hipStream_t)hip_stream));
+  return VSA_OK;
+}
+
+int vsa_forward(const vsa_params_t* p, const void* q, const void* k, const void* v, const void* gate_c,
+                const void* gate_f, void* out, int32_t* block_idx, void* out_fine, float* lse_fine,
+                float* out_coarse, float* lse_coarse, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  Geo g;
+  int rc = check_params(p, &g);
+  if (rc != VSA_OK) return rc;
+  if ((rc = check_topk(p, g)) != VSA_OK) return rc;
+  const bool given = (p->flags & VSA_FLAG_INDICES_GIVEN) != 0;
+  if (!q || !k || !v || !gate_c || !out || (given && !block_idx)) return VSA_ERR_NULL;
+  if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(gate_c) || misaligned(gate_f) || misaligned(out) ||
+      misaligned(block_idx) || misaligned(out_fine) || misaligned(lse_fine) || misaligned(out_coarse) ||
+      misaligned(lse_coarse) || misaligned(workspace))
+    return VSA_ERR_ALIGN;
+  if (!workspace || workspace_bytes < carve_fwd(p, g, nullptr).bytes) return VSA_ERR_WORKSPACE;
+
+  hipStream_t s = (hipStream_t)hip_stream;
+  FwdWs w = carve_fwd(p, g, workspace);
+  const int BH = p->B * p->H;
+  const float scale = scale_of(p);
+  float* oc = out_coarse ? out_coarse : w.oc;
+  float* lse_c = lse_coarse ? lse_coarse : w.lse_c;
+  int32_t* idx = block_idx ? block_idx : w.idx;
+
+  VSA_TRY(vsa::launch_cube_masks(g, w.mask, s));
+  VSA_TRY(vsa::launch_pool(g, BH, p->d, w.mask, q, k, v, w.qc, w.kc, w.vc, s));
+  VSA_TRY(vsa::launch_coarse(BH, g.Nc, p->d, p->topk, scale, w.qc, w.kc, w.vc, oc, lse_c, idx, given ? 0 : 1, s));
+  VSA_TRY(vsa::launch_fine_fwd(BH, g.Nc, p->d, p->topk, scale, q, k, v, gate_c, gate_f, idx, oc, w.mask, out, out_fine,
+                               lse_fine, s));
+  return VSA_OK;
+}
+
+int vsa_backward(const vsa_params_t* p, const void* q, const void* k, const void* v, const void* gate_c,
+                 const void* gate_f, const void* dout, const int32_t* block_idx, const void* out_fine,
+                 const float* lse_fine, const float* out_coarse, const float* lse_coarse, void* dq, void* dk,
+                 void* dv, void* dgate_c, void* dgate_f, void* workspace, size_t workspace_bytes,
+                 void* hip_stream) {
+  Geo g;
+  int rc = check_params(p, &g);
+  if (rc != VSA_OK) return rc;
+  if ((rc = check_topk(p, g)) != VSA_OK) return rc;
+  if (!q || !k || !v || !gate_c || !dout || !block_idx || !out_fine || !lse_fine || !out_coarse || !lse_coarse ||
+      !dq || !dk || !dv || !dgate_c)
+    return VSA_ERR_NULL;
+  if ((gate_f == nullptr) != (dgate_f == nullptr)) return VSA_ERR_BAD_ARG;
+  if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(gate_c) || misaligned(gate_f) ||
+      misaligned(dout) || misaligned(block_idx) || misaligned(out_fine) || misaligned(lse_fine) ||
+      misaligned(out_coarse) || misaligned(lse_coarse) || misaligned(dq) || misaligned(dk) || misaligned(dv) ||
+      misaligned(dgate_c) || misaligned(dgate_f) || misaligned(workspace))
+    return VSA_ERR_ALIGN;
+  if (!workspace || workspace_bytes < carve_bwd(p, g, nullptr).bytes) return VSA_ERR_WORKSPACE;
+
+  hipStream_t s = (hipStream_t)hip_stream;
+  BwdWs w = carve_bwd(p, g, workspace);
+  const int BH = p->B * p->H;
+  const float scale = scale_of(p);
+
+  VSA_TRY(vsa::launch_cube_masks(g, w.mask, s));
+  VSA_TRY(vsa::launch_pool(g, BH, p->d, w.mask, q, k, v, w.qc, w.kc, w.vc, s));
+  VSA_TRY(vsa::launch_bwd_pre(BH, g.Nc, p->d, w.mask, dout, gate_c, gate_f, out_fine, out_coarse, dgate_c, dgate_f,
+                              w.dof, w.delta, w.doc, s));
+  VSA_TRY(vsa::launch_coarse_bwd(BH, g.Nc, p->d, scale, w.qc, w.kc, w.vc, lse_coarse, w.doc, w.ac, w.dsc, w.dqc, w.dkc,
+                                 w.dvc, s));
+  VSA_TRY(vsa::launch_transpose_map(BH, g.Nc, p->topk, block_idx, w.row_ptr, w.col, s));
+  VSA_TRY(vsa::launch_fine_bwd_dq(BH, g.Nc, p->d, p->topk, scale, q, k, v, w.dof, block_idx, lse_fine, w.delta,
+                                  w.dqc, w.mask, dq, s));
+  VSA_TRY(vsa::launch_fine_bwd_dkv(BH, g.Nc, p->d, p->topk, scale, q, k, v, w.dof, w.row_ptr, w.col, lse_fine, w.delta, w.dkc,
+                                   w.dvc, w.mask, dk, dv, s));
+  return VSA_OK;
+}
+
+const char* vsa_status_string(int status) {
+  switch (status) {
+    case VSA_OK: return "ok";
+    case VSA_ERR_NULL: return "a required pointer is NULL";
+    case VSA_ERR_BAD_ARG: return "bad argument (dimension or topk out of range, gate_f/dgate_f mismatch)";
+    case VSA_ERR_UNSUPPORTED: return "unsupported configuration (cube volume != 64, d not 64/128, too many cubes)";
+    case VSA_ERR_ALIGN: return "a device pointer is not 16-byte aligned";
+    case VSA_ERR_WORKSPACE: return "workspace missing or too small";
+    case VSA_ERR_HIP: return "a kernel launch failed";
+    default: return "unknown status";
+  }
+}
+
+}  // extern "C"

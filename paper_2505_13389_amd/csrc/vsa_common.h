@@ -1,0 +1,63 @@
+// Shared device-side definitions of the gfx950 Video Sparse Attention kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace vsa {
+
+constexpr int kTile = 64;  // tokens per cube = rows per attention tile (Sec. 2.2: B = 4*4*4)
+
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+// Geometry of the padded latent grid (Sec. 2.2), passed to kernels by value.
+struct Geo {
+  int T, Hh, W;     // valid grid
+  int Ct, Ch, Cw;   // cube
+  int Nt, Nh, Nw;   // cubes per axis
+  int Nc;           // cubes
+  int L;            // valid tokens
+  long long Np;     // padded tokens = 64 * Nc
+};
+
+// bf16 bits <-> fp32.  Widening is exact; narrowing rounds to nearest even in hardware.
+__device__ __forceinline__ float bf_lo(uint32_t u) { return __uint_as_float(u << 16); }
+__device__ __forceinline__ float bf_hi(uint32_t u) { return __uint_as_float(u & 0xffff0000u); }
+__device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
+  f32x2 x = {a, b};
+  bf16x2 y = __builtin_convertvector(x, bf16x2);
+  return __builtin_bit_cast(uint32_t, y);
+}
+__device__ __forceinline__ void unpack8(const uint4& u, float* f) {
+  f[0] = bf_lo(u.x); f[1] = bf_hi(u.x); f[2] = bf_lo(u.y); f[3] = bf_hi(u.y);
+  f[4] = bf_lo(u.z); f[5] = bf_hi(u.z); f[6] = bf_lo(u.w); f[7] = bf_hi(u.w);
+}
+__device__ __forceinline__ uint4 pack8(const float* f) {
+  uint4 u;
+  u.x = pack_bf16(f[0], f[1]); u.y = pack_bf16(f[2], f[3]);
+  u.z = pack_bf16(f[4], f[5]); u.w = pack_bf16(f[6], f[7]);
+  return u;
+}
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+__device__ __forceinline__ float fast_log2(float x) { return __builtin_amdgcn_logf(x); }
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+// Bit p of a cube's mask is set iff in-cube slot p = (pt*Ch + ph)*Cw + pw holds a valid token.
+__device__ __forceinline__ uint64_t cube_valid_mask(const Geo& g, int c) {
+  int cw = c % g.Nw, ch = (c / g.Nw) % g.Nh, ct = c / (g.Nw * g.Nh);
+  int vt = min(g.Ct, g.T - ct * g.Ct), vh = min(g.Ch, g.Hh - ch * g.Ch), vw = min(g.Cw, g.W - cw * g.Cw);
+  uint64_t m = 0;
+  for (int pt = 0; pt < vt; ++pt)
+    for (int ph = 0; ph < vh; ++ph)
+      for (int pw = 0; pw < vw; ++pw) m |= 1ull << ((pt * g.Ch + ph) * g.Cw + pw);
+  return m;
+}
+
+}  // namespace vsa

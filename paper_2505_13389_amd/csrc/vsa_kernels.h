@@ -1,0 +1,36 @@
+// Host-side launchers of the gfx950 kernels (one per step of the forward/backward path).
+// Each enqueues on `s` and returns hipGetLastError(); none allocates or synchronises.
+#pragma once
+#include "vsa_common.h"
+
+namespace vsa {
+
+hipError_t launch_tile_permute(const Geo& g, int BH, int d, const void* src, void* dst, bool inverse, hipStream_t s);
+hipError_t launch_cube_masks(const Geo& g, uint64_t* mask, hipStream_t s);
+hipError_t launch_pool(const Geo& g, int BH, int d, const uint64_t* mask, const void* q, const void* k, const void* v,
+                       float* qc, float* kc, float* vc, hipStream_t s);
+hipError_t launch_coarse(int BH, int Nc, int d, int K, float scale, const float* qc, const float* kc, const float* vc,
+                         float* oc, float* lse_c, int32_t* idx, int emit_idx, hipStream_t s);
+hipError_t launch_fine_fwd(int BH, int Nc, int d, int K, float scale, const void* q, const void* k, const void* v,
+                           const void* gate_c, const void* gate_f, const int32_t* idx, const float* oc,
+                           const uint64_t* mask, void* out, void* out_fine, float* lse_f, hipStream_t s);
+
+// backward
+hipError_t launch_bwd_pre(int BH, int Nc, int d, const uint64_t* mask, const void* dout, const void* gate_c,
+                          const void* gate_f, const void* out_fine, const float* oc, void* dgate_c, void* dgate_f,
+                          void* dof, float* delta, float* doc, hipStream_t s);
+hipError_t launch_coarse_bwd(int BH, int Nc, int d, float scale, const float* qc, const float* kc, const float* vc,
+                             const float* lse_c, const float* doc, float* ac, float* dsc, float* dqc, float* dkc,
+                             float* dvc,
+                             hipStream_t s);
+hipError_t launch_transpose_map(int BH, int Nc, int K, const int32_t* idx, int32_t* row_ptr, int32_t* col,
+                                hipStream_t s);
+hipError_t launch_fine_bwd_dq(int BH, int Nc, int d, int K, float scale, const void* q, const void* k, const void* v,
+                              const void* dof, const int32_t* idx, const float* lse_f, const float* delta,
+                              const float* dqc, const uint64_t* mask, void* dq, hipStream_t s);
+hipError_t launch_fine_bwd_dkv(int BH, int Nc, int d, int K, float scale, const void* q, const void* k, const void* v,
+                               const void* dof, const int32_t* row_ptr, const int32_t* col, const float* lse_f,
+                               const float* delta, const float* dkc, const float* dvc, const uint64_t* mask, void* dk,
+                               void* dv, hipStream_t s);
+
+}  // namespace vsa

@@ -1,0 +1,224 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle, element by element.
+
+Small workloads span several tiles, both head dims, ragged (padded) grids and the degenerate
+cases; the full-size workloads are checked on sampled heads / cubes in test_gpu_fullsize.py.
+"""
+import numpy as np
+import pytest
+
+from oracle import vsa_oracle as orc
+from paper_2505_13389_amd.synth import WORKLOADS, Workload
+
+from helpers import (assert_close, bf16_to_np, check_index_sets, grid_of, problem_of, tiled_bits, to_dev, widen)
+
+pytestmark = pytest.mark.gpu
+
+SMALL = {
+    "tiny": WORKLOADS["tiny"],
+    "tiny_dense": WORKLOADS["tiny_dense"],
+    "tiny128": Workload("tiny128", 1, 2, 8, 16, 16, 128, 8),
+    "pad64": Workload("pad64", 1, 2, 5, 6, 7, 64, 3),
+    "pad128": Workload("pad128", 2, 1, 6, 10, 9, 128, 5),
+    "one_cube": Workload("one_cube", 1, 1, 4, 4, 4, 64, 1),
+    "k1": Workload("k1", 1, 2, 8, 8, 8, 128, 1),
+    "planted": Workload("planted", 1, 2, 8, 16, 16, 64, 8, planted=True),
+    "planted_pad128": Workload("planted_pad128", 1, 2, 7, 14, 15, 128, 6, planted=True),
+}
+
+
+@pytest.fixture(scope="module")
+def vsa():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2505_13389_amd import vsa as m
+    m.lib()
+    return m
+
+
+def run_oracle_fwd(wl, x, block_idx=None, want_sc=False):
+    return orc.forward(grid_of(wl), x["q"], x["k"], x["v"], x["gate_c"], x["gate_f"], wl.topk, block_idx=block_idx,
+                       real="f32", want_sc=want_sc)
+
+
+def run_gpu_fwd(vsa, wl, dev, block_idx=None, backward=False):
+    import torch
+    pb = problem_of(wl)
+    buf = vsa.Buffers(pb, backward=backward, with_gate_f=dev["gate_f"] is not None)
+    if block_idx is not None:
+        buf.block_idx.copy_(torch.from_numpy(block_idx))
+    buf.forward(dev["q"], dev["k"], dev["v"], dev["gate_c"], dev["gate_f"], indices_given=block_idx is not None)
+    torch.cuda.synchronize()
+    return buf
+
+
+# ------------------------------------------------------------------------------ permutation
+@pytest.mark.parametrize("grid3,d", [((8, 16, 16), 64), ((5, 6, 7), 64), ((21, 30, 52), 128), ((4, 4, 4), 128)])
+def test_tile_permute_bit_exact_and_round_trip(vsa, grid3, d):
+    import torch
+    wl = Workload("perm", 2, 3, *grid3, d, 1)
+    g = grid_of(wl)
+    rng = np.random.default_rng(3)
+    src = rng.integers(0, 65536, size=(wl.B, wl.H, wl.L, d), dtype=np.uint16)
+    ref = orc.tile_u16(g, src)
+    pb = problem_of(wl)
+    dsrc = torch.from_numpy(src.view(np.int16)).cuda()
+    dtiled = torch.full((wl.B, wl.H, g.Np, d), 0x5555, dtype=torch.int16, device="cuda")
+    vsa.vsa_tile_permute(pb, dsrc, dtiled, inverse=False)
+    back = torch.empty_like(dsrc)
+    vsa.vsa_tile_permute(pb, dtiled, back, inverse=True)
+    torch.cuda.synchronize()
+    assert np.array_equal(dtiled.cpu().numpy().view(np.uint16), ref)
+    assert np.array_equal(back.cpu().numpy().view(np.uint16), src)
+
+
+# ------------------------------------------------------------------------------ coarse stage + top-K
+@pytest.mark.parametrize("name", ["tiny", "tiny_dense", "tiny128", "pad64", "pad128", "one_cube", "k1", "planted"])
+def test_coarse_stage_and_topk(vsa, name):
+    wl = SMALL[name]
+    bits = tiled_bits(wl, seed=1)
+    ref = run_oracle_fwd(wl, widen(bits), want_sc=True)
+    buf = run_gpu_fwd(vsa, wl, to_dev(bits))
+    assert_close(buf.out_coarse.cpu().numpy(), ref["out_coarse"], "out_coarse", max_abs=1e-4, rel_l2=1e-4)
+    assert np.abs(buf.lse_coarse.cpu().numpy() - ref["lse_coarse"]).max() < 1e-4
+    differ = check_index_sets(buf.block_idx.cpu().numpy(), ref["block_idx"], ref["sc"])
+    rows = np.prod(ref["block_idx"].shape[:3])
+    assert len(differ) <= max(1, rows // 50), f"{len(differ)} of {rows} rows differ (near-ties only are expected)"
+
+
+def test_topk_ties_go_to_the_lower_index(vsa):
+    wl = SMALL["tiny"]
+    bits = tiled_bits(wl, seed=2)
+    bits["q"][:] = 0  # all coarse logits equal -> the first K cubes win
+    buf = run_gpu_fwd(vsa, wl, to_dev(bits))
+    idx = buf.block_idx.cpu().numpy()
+    assert np.array_equal(idx, np.broadcast_to(np.arange(wl.topk, dtype=np.int32), idx.shape))
+
+
+# ------------------------------------------------------------------------------ forward
+@pytest.mark.parametrize("name", ["tiny", "tiny_dense", "tiny128", "pad64", "pad128", "one_cube", "k1"])
+@pytest.mark.parametrize("with_gate_f", [True, False])
+def test_forward_on_oracle_indices(vsa, name, with_gate_f):
+    """The fine kernel on the oracle's own selection: a near-tie flip can neither hide nor fake an error."""
+    wl = SMALL[name]
+    bits = tiled_bits(wl, seed=3, with_gate_f=with_gate_f, pad_garbage=True)
+    ref = run_oracle_fwd(wl, widen(bits))
+    buf = run_gpu_fwd(vsa, wl, to_dev(bits), block_idx=ref["block_idx"])
+    assert_close(bf16_to_np(buf.out), ref["out"], "out")
+    assert_close(bf16_to_np(buf.out_fine), ref["out_fine"], "out_fine")
+    assert np.abs(buf.lse_fine.cpu().numpy() - ref["lse_fine"]).max() < 2e-3
+    valid, _ = orc.valid_mask(grid_of(wl))
+    assert not bf16_to_np(buf.out)[:, :, ~valid].any(), "pad rows must be zero"
+
+
+@pytest.mark.parametrize("name", ["planted", "planted_pad128"])
+def test_forward_end_to_end_with_own_selection(vsa, name):
+    """Structured inputs have wide logit gaps at rank K, so the selection must match exactly."""
+    wl = SMALL[name]
+    bits = tiled_bits(wl, seed=4)
+    ref = run_oracle_fwd(wl, widen(bits), want_sc=True)
+    buf = run_gpu_fwd(vsa, wl, to_dev(bits))
+    differ = check_index_sets(buf.block_idx.cpu().numpy(), ref["block_idx"], ref["sc"])
+    assert len(differ) == 0
+    assert_close(bf16_to_np(buf.out), ref["out"], "out")
+
+
+def test_forward_end_to_end_iid_rows_with_equal_selection(vsa):
+    wl = SMALL["tiny"]
+    bits = tiled_bits(wl, seed=5)
+    ref = run_oracle_fwd(wl, widen(bits), want_sc=True)
+    buf = run_gpu_fwd(vsa, wl, to_dev(bits))
+    gi = buf.block_idx.cpu().numpy()
+    check_index_sets(gi, ref["block_idx"], ref["sc"])
+    same = np.repeat((gi == ref["block_idx"]).all(-1), 64, axis=-1)  # [B,H,Np]
+    assert same.mean() > 0.9
+    assert_close(bf16_to_np(buf.out)[same], ref["out"][same], "out (rows with identical selection)")
+
+
+def test_all_tiles_selected_is_dense_attention(vsa):
+    """K = Nc, G_c = 0, no fine gate: the library's dense path equals brute-force attention [Sec. 2.3]."""
+    wl = SMALL["tiny_dense"]
+    bits = tiled_bits(wl, seed=6, with_gate_f=False)
+    bits["gate_c"][:] = 0
+    x = widen(bits)
+    q, k, v = (x[n].astype(np.float64) for n in ("q", "k", "v"))
+    s = np.einsum("bhid,bhjd->bhij", q, k) / np.sqrt(wl.d)
+    p = np.exp(s - s.max(-1, keepdims=True)); p /= p.sum(-1, keepdims=True)
+    dense = p @ v
+    buf = run_gpu_fwd(vsa, wl, to_dev(bits))
+    assert_close(bf16_to_np(buf.out), dense, "out vs dense attention")
+
+
+def test_forward_is_deterministic_and_ignores_pad_slots(vsa):
+    wl = SMALL["pad128"]
+    clean = tiled_bits(wl, seed=7)
+    dirty = tiled_bits(wl, seed=7, pad_garbage=True)
+    a = run_gpu_fwd(vsa, wl, to_dev(clean))
+    b = run_gpu_fwd(vsa, wl, to_dev(clean))
+    c = run_gpu_fwd(vsa, wl, to_dev(dirty))
+    import torch
+    for name in ("out", "out_fine", "lse_fine", "out_coarse", "lse_coarse", "block_idx"):
+        assert torch.equal(getattr(a, name), getattr(b, name)), name
+        assert torch.equal(getattr(a, name), getattr(c, name)), name
+
+
+# ------------------------------------------------------------------------------ backward
+@pytest.mark.parametrize("name", ["tiny", "tiny_dense", "tiny128", "pad64", "pad128", "one_cube", "k1", "planted"])
+@pytest.mark.parametrize("with_gate_f", [True, False])
+def test_backward_on_oracle_indices(vsa, name, with_gate_f):
+    import torch
+    wl = SMALL[name]
+    bits = tiled_bits(wl, seed=8, with_gate_f=with_gate_f, pad_garbage=True)
+    x = widen(bits)
+    g = grid_of(wl)
+    fwd = run_oracle_fwd(wl, x)
+    ref = orc.backward(g, x["q"], x["k"], x["v"], x["gate_c"], x["gate_f"], x["dout"], fwd["block_idx"], wl.topk,
+                       real="f32")
+    dev = to_dev(bits)
+    buf = run_gpu_fwd(vsa, wl, dev, block_idx=fwd["block_idx"], backward=True)
+    buf.backward(dev["q"], dev["k"], dev["v"], dev["gate_c"], dev["gate_f"], dev["dout"])
+    torch.cuda.synchronize()
+    for name_ in ("dq", "dk", "dv", "dgate_c") + (("dgate_f",) if with_gate_f else ()):
+        assert_close(bf16_to_np(getattr(buf, name_)), ref[name_], name_)
+    valid, _ = orc.valid_mask(g)
+    for name_ in ("dq", "dk", "dv", "dgate_c"):
+        assert not bf16_to_np(getattr(buf, name_))[:, :, ~valid].any(), f"{name_}: pad rows must be zero"
+
+
+def test_backward_is_deterministic(vsa):
+    import torch
+    wl = SMALL["planted_pad128"]
+    bits = tiled_bits(wl, seed=9)
+    dev = to_dev(bits)
+    runs = []
+    for _ in range(2):
+        buf = run_gpu_fwd(vsa, wl, dev, backward=True)
+        buf.backward(dev["q"], dev["k"], dev["v"], dev["gate_c"], dev["gate_f"], dev["dout"])
+        torch.cuda.synchronize()
+        runs.append(buf)
+    for name in ("dq", "dk", "dv", "dgate_c", "dgate_f"):
+        assert torch.equal(getattr(runs[0], name), getattr(runs[1], name)), name
+
+
+# ------------------------------------------------------------------------------ error paths
+def test_error_paths_return_status_and_launch_nothing(vsa):
+    import torch
+    wl = SMALL["tiny"]
+    pb = problem_of(wl)
+    dev = to_dev(tiled_bits(wl, seed=10))
+    buf = vsa.Buffers(pb, backward=False)
+    small = torch.empty(16, dtype=torch.uint8, device="cuda")
+    with pytest.raises(vsa.VsaError) as e:
+        vsa.vsa_forward(pb, dev["q"], dev["k"], dev["v"], dev["gate_c"], dev["gate_f"], buf.out, buf.block_idx,
+                        None, None, None, None, small)
+    assert e.value.status == -5
+    off = dev["q"].view(-1)[1:-7].view(-1)  # 2-byte offset: misaligned
+    with pytest.raises(vsa.VsaError) as e:
+        vsa.vsa_forward(pb, off, dev["k"], dev["v"], dev["gate_c"], dev["gate_f"], buf.out, buf.block_idx,
+                        None, None, None, None, buf.workspace)
+    assert e.value.status == -4
+    bad = vsa.Problem(wl.B, wl.H, wl.T, wl.Hh, wl.W, wl.d, 33)  # topk > Nc
+    with pytest.raises(vsa.VsaError) as e:
+        vsa.vsa_forward(bad, dev["q"], dev["k"], dev["v"], dev["gate_c"], dev["gate_f"], buf.out, buf.block_idx,
+                        None, None, None, None, buf.workspace)
+    assert e.value.status == -2
+    torch.cuda.synchronize()
