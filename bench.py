@@ -1,0 +1,191 @@
+#!/usr/bin/env python3
+"""Benchmark of the Video Sparse Attention hot path on one MI355X.
+
+One step = vsa_forward + vsa_backward (pooling, coarse attention, top-K, fine block-sparse
+attention, gated sum, and the whole backward) on the Wan-1.3B-shaped 480p workload
+(valid grid 21x30x52 padded to 24x32x52 = 39936 tokens, 12 heads, d=128, top-K 78 of 624
+cubes), inputs resident in HBM in the cube-contiguous layout.  The raster<->tiled
+permutation is hoistable out of the layer (App. B listing caption) and is timed separately.
+
+Prints ONE JSON line: effective TFLOP/s counted on the selected 64x64 blocks only
+(forward 4*Np*K*64*d*H*B, forward+backward 3.5x, App. C.4), the roofline position of the
+dominant kernel, the speedup over the same library's dense path (top-K = all cubes), and the
+CPU oracle timed on the host cores on one head of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+sys.path.insert(0, os.path.join(ROOT, "tests"))
+
+PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA peak
+
+# Algorithmic MFMA flops one launch of each fine kernel is credited with, per selected
+# (query tile, key tile) pair, in units of 2*64*64*d (one 64x64xd matmul).  Forward: S and PV.
+# Backward is 2.5x forward = 5 matmuls (S, dP, dV, dK, dQ); the two-pass backward recomputes S
+# and dP in both passes, so each pass is credited half of them: dQ pass 1 + 1, dK/dV pass 2 + 1.
+MATMULS = {"fine_fwd": 2.0, "fine_bwd_dq": 2.0, "fine_bwd_dkv": 3.0}
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="wan1.3b")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--seed", type=int, default=0)
+    return ap.parse_args()
+
+
+def device_inputs(wl, seed, torch):
+    """Seeded inputs drawn on the host in raster order, moved to HBM and tiled by the library."""
+    from paper_2505_13389_amd import synth, vsa
+    from helpers import problem_of
+    raw = synth.make_inputs(wl, seed)
+    pb = problem_of(wl)
+    Np, _ = vsa.vsa_padded_tokens(pb)
+    dev = {}
+    for n, b in raw.items():
+        src = torch.from_numpy(b.view("int16")).cuda().view(torch.bfloat16)
+        dst = torch.empty((wl.B, wl.H, Np, wl.d), dtype=torch.bfloat16, device="cuda")
+        vsa.vsa_tile_permute(pb, src, dst, inverse=False)
+        dev[n] = dst
+        dev["raster_" + n] = src
+    torch.cuda.synchronize()
+    return dev
+
+
+def time_steps(fn, steps, warmup, torch):
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        fn()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3 / steps
+
+
+def cpu_baseline(wl, seed):
+    """The oracle (fp32 build, as it stands) on one head of the same workload, forward+backward."""
+    import numpy as np
+    from oracle import vsa_oracle as orc
+    from paper_2505_13389_amd.synth import Workload
+    from helpers import grid_of, tiled_bits, widen
+    one = Workload(wl.name + "_1head", 1, 1, wl.T, wl.Hh, wl.W, wl.d, wl.topk, wl.cube, wl.planted)
+    x = widen(tiled_bits(one, seed))
+    g = grid_of(one)
+    t0 = time.perf_counter()
+    f = orc.forward(g, x["q"], x["k"], x["v"], x["gate_c"], x["gate_f"], one.topk, real="f32")
+    orc.backward(g, x["q"], x["k"], x["v"], x["gate_c"], x["gate_f"], x["dout"], f["block_idx"], one.topk, real="f32")
+    sec = time.perf_counter() - t0
+    flops = 3.5 * 4.0 * one.Np * one.topk * 64 * one.d
+    try:
+        cores = len(os.sched_getaffinity(0))
+    except AttributeError:
+        cores = os.cpu_count()
+    omp = os.environ.get("OMP_NUM_THREADS")
+    if omp:
+        cores = min(cores, int(omp))
+    return {"value": flops / sec / 1e12, "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
+            "sample": f"1 of {wl.B * wl.H} (batch,head) slices of {wl.name}, forward+backward, fp32 oracle, "
+                      f"{sec:.1f} s wall"}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus must be 1 (no multi-GPU path exists)", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2505_13389_amd import vsa
+    from paper_2505_13389_amd.synth import WORKLOADS, Workload
+    from helpers import problem_of
+
+    vsa.lib()  # fail loudly if the HIP library is missing
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    wl = WORKLOADS[args.workload]
+    dev = device_inputs(wl, args.seed, torch)
+    pb = problem_of(wl)
+    buf = vsa.Buffers(pb)
+    a = (dev["q"], dev["k"], dev["v"], dev["gate_c"], dev["gate_f"])
+
+    def step():
+        buf.forward(*a)
+        buf.backward(*a, dev["dout"])
+
+    ms = time_steps(step, args.steps, args.warmup, torch)
+    ms_fwd = time_steps(lambda: buf.forward(*a), args.steps, 1, torch)
+
+    # the same steps again with every kernel bracketed by HIP events on the launch stream
+    vsa.vsa_profile_begin(32 * args.steps)
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    per = {}
+    for name, t in vsa.vsa_profile_end():
+        per.setdefault(name, []).append(t)
+    kern = {n: sum(v) / len(v) * (len(v) / args.steps) for n, v in per.items()}  # ms per step, by kernel
+    ms_profiled = sum(kern.values())
+
+    fwd_flops = 4.0 * buf.Np * wl.topk * 64 * wl.d * wl.H * wl.B
+    flops = 3.5 * fwd_flops
+    tflops = flops / (ms * 1e-3) / 1e12
+    pair_flops = 2.0 * 64 * 64 * wl.d
+    pairs = wl.B * wl.H * buf.Nc * wl.topk
+    dom = max(MATMULS, key=lambda n: kern.get(n, 0.0))
+    achieved = MATMULS[dom] * pair_flops * pairs / (kern[dom] * 1e-3) / 1e12
+    roofline = {"kernel": dom, "bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS,
+                "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                "avg_launch_ms": round(kern[dom], 4)}
+
+    # raster <-> tiled permutation of the 6 inputs and 6 outputs of a training step, timed apart
+    def permutes():
+        for n in ("q", "k", "v", "gate_c", "gate_f", "dout"):
+            vsa.vsa_tile_permute(pb, dev["raster_" + n], dev[n], inverse=False)
+        for t in (buf.out, buf.dq, buf.dk, buf.dv, buf.dgate_c, buf.dgate_f):
+            vsa.vsa_tile_permute(pb, t, dev["raster_q"], inverse=True)
+    raster_keep = dev["raster_q"].clone()
+    ms_perm = time_steps(permutes, max(2, args.steps // 4), 1, torch)
+    dev["raster_q"].copy_(raster_keep)
+
+    speedup = None
+    if not args.no_dense:
+        dense_wl = Workload(wl.name + "_dense", wl.B, wl.H, wl.T, wl.Hh, wl.W, wl.d, buf.Nc, wl.cube, wl.planted)
+        dbuf = vsa.Buffers(problem_of(dense_wl))
+
+        def dstep():
+            dbuf.forward(*a)
+            dbuf.backward(*a, dev["dout"])
+        ms_dense = time_steps(dstep, max(2, args.steps // 8), 1, torch)
+        speedup = ms_dense / ms
+        del dbuf
+
+    line = {
+        "metric": "VSA fwd+bwd effective TFLOP/s (selected blocks only)", "value": round(tflops, 2), "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{wl.name}: B={wl.B} H={wl.H} grid={wl.T}x{wl.Hh}x{wl.W} (Np={buf.Np}, Nc={buf.Nc}) "
+                               f"d={wl.d} topk={wl.topk}, forward+backward, tiled layout resident in HBM"},
+        "pct_of_bf16_peak": round(100.0 * tflops / PEAK_BF16_TFLOPS, 2),
+        "fwd_ms": round(ms_fwd, 4), "fwd_tflops": round(fwd_flops / (ms_fwd * 1e-3) / 1e12, 2),
+        "speedup_vs_dense": None if speedup is None else round(speedup, 2),
+        "ideal_speedup_vs_dense": round(buf.Nc / wl.topk, 2),
+        "permute_ms_12_tensors": round(ms_perm, 4),
+        "ms_per_step_profiled": round(ms_profiled, 4),
+        "kernel_ms": {n: round(t, 4) for n, t in sorted(kern.items(), key=lambda kv: -kv[1])},
+        "roofline": roofline,
+    }
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(wl, args.seed)
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

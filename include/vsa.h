@@ -18,9 +18,12 @@
  *     cube multiples, Np tokens = Nc cubes x 64; each cube is 64 consecutive rows.
  *   - Pad slots (tiled rows outside the valid grid) are defined by geometry alone.  They
  *     are never keys, are excluded from pooled means, and their rows of every output and
- *     gradient are written as zero; whatever the caller stores there in an input is ignored.
+ *     gradient are written as zero; whatever finite values the caller stores there in an
+ *     input are ignored.
  *   - Results are deterministic (bit-identical across calls on the same inputs).
- *   - Return value: VSA_OK (0) or a negative vsa_status; on an error nothing was enqueued.
+ *   - Return value: VSA_OK (0) or a negative vsa_status.  Validation errors are detected
+ *     before anything is enqueued; VSA_ERR_HIP (a launch rejected by the runtime) can leave
+ *     the earlier kernels of that call enqueued.
  */
 #ifndef VSA_H_
 #define VSA_H_
@@ -104,6 +107,19 @@ int vsa_backward(const vsa_params_t* p, const void* q, const void* k, const void
                  const float* lse_fine, const float* out_coarse, const float* lse_coarse, void* dq, void* dk,
                  void* dv, void* dgate_c, void* dgate_f, void* workspace, size_t workspace_bytes,
                  void* hip_stream);
+
+/* Per-kernel timing for benchmarks (not part of the paper's method).  Between
+ * vsa_profile_begin and vsa_profile_end every kernel the other entry points enqueue is
+ * bracketed by a pair of HIP events on the caller's stream, up to max_records kernels
+ * (events are created inside vsa_profile_begin; further launches are simply not recorded).
+ * After the caller has synchronised the stream, record i (launch order) has the static
+ * kernel name vsa_profile_name(i) and took vsa_profile_ms(i) milliseconds (-1 on error).
+ * One global recorder per process; not thread-safe; host-side calls. */
+int vsa_profile_begin(int max_records);
+int vsa_profile_count(void);
+const char* vsa_profile_name(int i);
+float vsa_profile_ms(int i);
+int vsa_profile_end(void);
 
 /* Human-readable name of a status code (static string, never NULL). */
 const char* vsa_status_string(int status);

@@ -103,8 +103,34 @@ BwdWs carve_bwd(const vsa_params_t* p, const Geo& g, void* ws) {
   return w;
 }
 
-#define VSA_TRY(expr)                      \
+// Optional per-kernel timing (vsa_profile_*): events are created up front by vsa_profile_begin,
+// so a profiled call still allocates nothing.  One global recorder, not thread-safe.
+struct Profiler {
+  bool on = false;
+  int cap = 0, n = 0;
+  hipEvent_t* start = nullptr;
+  hipEvent_t* stop = nullptr;
+  const char** name = nullptr;
+} g_prof;
+
+struct Timed {
+  int slot = -1;
+  hipStream_t s;
+  Timed(const char* name, hipStream_t stream) : s(stream) {
+    if (g_prof.on && g_prof.n < g_prof.cap) {
+      slot = g_prof.n++;
+      g_prof.name[slot] = name;
+      (void)hipEventRecord(g_prof.start[slot], s);
+    }
+  }
+  ~Timed() {
+    if (slot >= 0) (void)hipEventRecord(g_prof.stop[slot], s);
+  }
+};
+
+#define VSA_TRY(name, expr)                \
   do {                                     \
+    Timed timed_(name, s);                 \
     if ((expr) != hipSuccess) return VSA_ERR_HIP; \
   } while (0)
 
@@ -133,7 +159,8 @@ int vsa_tile_permute(const vsa_params_t* p, const void* src, void* dst, int inve
   if (rc != VSA_OK) return rc;
   if (!src || !dst) return VSA_ERR_NULL;
   if (misaligned(src) || misaligned(dst)) return VSA_ERR_ALIGN;
-  VSA_TRY(vsa::launch_tile_permute(g, p->B * p->H, p->d, src, dst, inverse != 0, (hipStream_t)hip_stream));
+  hipStream_t s = (hipStream_t)hip_stream;
+  VSA_TRY("tile_permute", vsa::launch_tile_permute(g, p->B * p->H, p->d, src, dst, inverse != 0, s));
   return VSA_OK;
 }
 
@@ -160,10 +187,10 @@ int vsa_forward(const vsa_params_t* p, const void* q, const void* k, const void*
   float* lse_c = lse_coarse ? lse_coarse : w.lse_c;
   int32_t* idx = block_idx ? block_idx : w.idx;
 
-  VSA_TRY(vsa::launch_cube_masks(g, w.mask, s));
-  VSA_TRY(vsa::launch_pool(g, BH, p->d, w.mask, q, k, v, w.qc, w.kc, w.vc, s));
-  VSA_TRY(vsa::launch_coarse(BH, g.Nc, p->d, p->topk, scale, w.qc, w.kc, w.vc, oc, lse_c, idx, given ? 0 : 1, s));
-  VSA_TRY(vsa::launch_fine_fwd(BH, g.Nc, p->d, p->topk, scale, q, k, v, gate_c, gate_f, idx, oc, w.mask, out, out_fine,
+  VSA_TRY("cube_masks", vsa::launch_cube_masks(g, w.mask, s));
+  VSA_TRY("pool", vsa::launch_pool(g, BH, p->d, w.mask, q, k, v, w.qc, w.kc, w.vc, s));
+  VSA_TRY("coarse", vsa::launch_coarse(BH, g.Nc, p->d, p->topk, scale, w.qc, w.kc, w.vc, oc, lse_c, idx, given ? 0 : 1, s));
+  VSA_TRY("fine_fwd", vsa::launch_fine_fwd(BH, g.Nc, p->d, p->topk, scale, q, k, v, gate_c, gate_f, idx, oc, w.mask, out, out_fine,
                                lse_fine, s));
   return VSA_OK;
 }
@@ -193,17 +220,54 @@ int vsa_backward(const vsa_params_t* p, const void* q, const void* k, const void
   const int BH = p->B * p->H;
   const float scale = scale_of(p);
 
-  VSA_TRY(vsa::launch_cube_masks(g, w.mask, s));
-  VSA_TRY(vsa::launch_pool(g, BH, p->d, w.mask, q, k, v, w.qc, w.kc, w.vc, s));
-  VSA_TRY(vsa::launch_bwd_pre(BH, g.Nc, p->d, w.mask, dout, gate_c, gate_f, out_fine, out_coarse, dgate_c, dgate_f,
+  VSA_TRY("cube_masks", vsa::launch_cube_masks(g, w.mask, s));
+  VSA_TRY("pool", vsa::launch_pool(g, BH, p->d, w.mask, q, k, v, w.qc, w.kc, w.vc, s));
+  VSA_TRY("bwd_pre", vsa::launch_bwd_pre(BH, g.Nc, p->d, w.mask, dout, gate_c, gate_f, out_fine, out_coarse, dgate_c, dgate_f,
                               w.dof, w.delta, w.doc, s));
-  VSA_TRY(vsa::launch_coarse_bwd(BH, g.Nc, p->d, scale, w.qc, w.kc, w.vc, lse_coarse, w.doc, w.ac, w.dsc, w.dqc, w.dkc,
+  VSA_TRY("coarse_bwd", vsa::launch_coarse_bwd(BH, g.Nc, p->d, scale, w.qc, w.kc, w.vc, lse_coarse, w.doc, w.ac, w.dsc, w.dqc, w.dkc,
                                  w.dvc, s));
-  VSA_TRY(vsa::launch_transpose_map(BH, g.Nc, p->topk, block_idx, w.row_ptr, w.col, s));
-  VSA_TRY(vsa::launch_fine_bwd_dq(BH, g.Nc, p->d, p->topk, scale, q, k, v, w.dof, block_idx, lse_fine, w.delta,
+  VSA_TRY("transpose_map", vsa::launch_transpose_map(BH, g.Nc, p->topk, block_idx, w.row_ptr, w.col, s));
+  VSA_TRY("fine_bwd_dq", vsa::launch_fine_bwd_dq(BH, g.Nc, p->d, p->topk, scale, q, k, v, w.dof, block_idx, lse_fine, w.delta,
                                   w.dqc, w.mask, dq, s));
-  VSA_TRY(vsa::launch_fine_bwd_dkv(BH, g.Nc, p->d, p->topk, scale, q, k, v, w.dof, w.row_ptr, w.col, lse_fine, w.delta, w.dkc,
+  VSA_TRY("fine_bwd_dkv", vsa::launch_fine_bwd_dkv(BH, g.Nc, p->d, p->topk, scale, q, k, v, w.dof, w.row_ptr, w.col, lse_fine, w.delta, w.dkc,
                                    w.dvc, w.mask, dk, dv, s));
+  return VSA_OK;
+}
+
+int vsa_profile_begin(int max_records) {
+  if (g_prof.on || max_records < 1) return VSA_ERR_BAD_ARG;
+  g_prof.start = new hipEvent_t[max_records];
+  g_prof.stop = new hipEvent_t[max_records];
+  g_prof.name = new const char*[max_records];
+  for (int i = 0; i < max_records; ++i)
+    if (hipEventCreate(&g_prof.start[i]) != hipSuccess || hipEventCreate(&g_prof.stop[i]) != hipSuccess)
+      return VSA_ERR_HIP;
+  g_prof.cap = max_records;
+  g_prof.n = 0;
+  g_prof.on = true;
+  return VSA_OK;
+}
+
+int vsa_profile_count(void) { return g_prof.n; }
+
+const char* vsa_profile_name(int i) { return (i >= 0 && i < g_prof.n) ? g_prof.name[i] : ""; }
+
+float vsa_profile_ms(int i) {
+  float ms = -1.f;
+  if (i >= 0 && i < g_prof.n && hipEventElapsedTime(&ms, g_prof.start[i], g_prof.stop[i]) != hipSuccess) ms = -1.f;
+  return ms;
+}
+
+int vsa_profile_end(void) {
+  if (!g_prof.on) return VSA_ERR_BAD_ARG;
+  for (int i = 0; i < g_prof.cap; ++i) {
+    (void)hipEventDestroy(g_prof.start[i]);
+    (void)hipEventDestroy(g_prof.stop[i]);
+  }
+  delete[] g_prof.start;
+  delete[] g_prof.stop;
+  delete[] g_prof.name;
+  g_prof = Profiler();
   return VSA_OK;
 }
 

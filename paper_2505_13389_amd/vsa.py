@@ -17,7 +17,8 @@ VSA_FLAG_INDICES_GIVEN = 1
 STATUS = {0: "VSA_OK", -1: "VSA_ERR_NULL", -2: "VSA_ERR_BAD_ARG", -3: "VSA_ERR_UNSUPPORTED", -4: "VSA_ERR_ALIGN",
           -5: "VSA_ERR_WORKSPACE", -6: "VSA_ERR_HIP"}
 EXPORTS = ["vsa_padded_tokens", "vsa_workspace_bytes", "vsa_tile_permute", "vsa_forward", "vsa_backward",
-           "vsa_status_string"]
+           "vsa_status_string", "vsa_profile_begin", "vsa_profile_count", "vsa_profile_name", "vsa_profile_ms",
+           "vsa_profile_end"]
 
 
 class VsaParams(C.Structure):
@@ -54,6 +55,11 @@ def lib():
         L.vsa_forward.restype = C.c_int
         L.vsa_backward.argtypes = [C.POINTER(VsaParams)] + [vp] * 17 + [C.c_size_t, vp]
         L.vsa_backward.restype = C.c_int
+        L.vsa_profile_begin.argtypes = [C.c_int]
+        L.vsa_profile_name.argtypes = [C.c_int]
+        L.vsa_profile_name.restype = C.c_char_p
+        L.vsa_profile_ms.argtypes = [C.c_int]
+        L.vsa_profile_ms.restype = C.c_float
         L.vsa_status_string.argtypes = [C.c_int]
         L.vsa_status_string.restype = C.c_char_p
         _lib = L
@@ -156,3 +162,17 @@ class Buffers:
         vsa_backward(self.pb, q, k, v, gate_c, gate_f, dout, self.block_idx, self.out_fine, self.lse_fine,
                      self.out_coarse, self.lse_coarse, self.dq, self.dk, self.dv, self.dgate_c, self.dgate_f,
                      self.workspace)
+
+
+def vsa_profile_begin(max_records: int):
+    rc = lib().vsa_profile_begin(max_records)
+    if rc:
+        raise VsaError("vsa_profile_begin", rc)
+
+
+def vsa_profile_end():
+    """Synchronise first.  Returns [(kernel name, milliseconds)] in launch order and stops recording."""
+    L = lib()
+    recs = [(L.vsa_profile_name(i).decode(), float(L.vsa_profile_ms(i))) for i in range(L.vsa_profile_count())]
+    L.vsa_profile_end()
+    return recs
