@@ -21,16 +21,16 @@ template <int D>
 __global__ __launch_bounds__(256, 2) void k_fine_bwd_dq(int Nc, int K, float sl2, float scale, const uint4* __restrict__ q,
                                                         const uint4* __restrict__ k, const uint4* __restrict__ v,
                                                         const uint4* __restrict__ dof, const int32_t* __restrict__ idx,
-                                                        const float* __restrict__ lse_f, const float* __restrict__ delta,
+                                                        const float* __restrict__ lse2_f, const float* __restrict__ delta,
                                                         const float* __restrict__ dqc, const uint64_t* __restrict__ mask,
                                                         uint4* __restrict__ dq) {
   using TL = Tile<D>;
   constexpr int CPR = TL::CPR, KS = D / 16, DVB = D / 32, LPT = TL::LPT;
-  constexpr int OS = D + 4;
-  constexpr int STAGE = 2 * TL::BYTES;
-  constexpr int MERGE = 4 * 32 * OS * 4;
-  constexpr int LDS = (2 * STAGE > MERGE) ? 2 * STAGE : MERGE;
-  __shared__ __attribute__((aligned(16))) unsigned char smem[LDS];
+  constexpr int OS = D;
+  constexpr int STAGE = 2 * TL::BYTES;  // K tile + V tile
+  __shared__ __attribute__((aligned(16))) unsigned char stage0[STAGE];
+  __shared__ __attribute__((aligned(16))) unsigned char stage1[STAGE];
+  static_assert(2 * 32 * OS * 4 <= STAGE, "merge buffer must fit in one stage");
 
   const int c = blockIdx.x % Nc;
   const long long bh = blockIdx.x / Nc;
@@ -39,6 +39,10 @@ __global__ __launch_bounds__(256, 2) void k_fine_bwd_dq(int Nc, int K, float sl2
   const long long rows0 = bh * (long long)Nc * kTile;
   const int32_t* my_idx = idx + (bh * Nc + c) * (long long)K;
   const uint64_t qmask = mask[c];
+
+  int jt = my_idx[0];
+  TL::async_load(k, rows0 + (long long)jt * kTile, stage0, wave, lane);
+  TL::async_load(v, rows0 + (long long)jt * kTile, stage0 + TL::BYTES, wave, lane);
 
   const long long qrow_g = rows0 + c * kTile + qh * 32 + l32;
   bf16x8 qreg[KS], doreg[KS];
@@ -51,34 +55,27 @@ __global__ __launch_bounds__(256, 2) void k_fine_bwd_dq(int Nc, int K, float sl2
       doreg[s] = __builtin_bit_cast(bf16x8, dorow[2 * s + h]);
     }
   }
-  // pad query rows: lse = +inf makes P = 0, so they contribute nothing
-  const bool qvalid = (qmask >> (qh * 32 + l32)) & 1;
-  const float lse2 = qvalid ? lse_f[qrow_g] * kLog2e : INFINITY;
-  const float dl = qvalid ? delta[qrow_g] : 0.f;
-
-  uint4 pk[LPT], pv[LPT];
-  int jt = my_idx[0];
-  TL::gload(k, rows0 + (long long)jt * kTile, tid, pk);
-  TL::gload(v, rows0 + (long long)jt * kTile, tid, pv);
-  TL::lstore(smem, tid, pk);
-  TL::lstore(smem + TL::BYTES, tid, pv);
-  __syncthreads();
+  // lse2 = lse*log2(e), +inf on pad query rows (then P = 0 and the row contributes nothing)
+  const float lse2 = lse2_f[qrow_g];
+  const float dl = delta[qrow_g];
 
   f32x16 acc[DVB];
 #pragma unroll
   for (int x = 0; x < DVB; ++x)
 #pragma unroll
     for (int i = 0; i < 16; ++i) acc[x][i] = 0.f;
+  __syncthreads();
 
-  for (int t = 0; t < K; ++t) {
+  auto body = [&](const unsigned char* cur, unsigned char* nxt, int t) {
     const uint64_t kmask = mask[jt];
     if (t + 1 < K) {
       jt = my_idx[t + 1];
-      TL::gload(k, rows0 + (long long)jt * kTile, tid, pk);
-      TL::gload(v, rows0 + (long long)jt * kTile, tid, pv);
+      TL::async_load(k, rows0 + (long long)jt * kTile, nxt, wave, lane);
+      TL::async_load(v, rows0 + (long long)jt * kTile, nxt + TL::BYTES, wave, lane);
     }
-    const unsigned char* Ks = smem + (t & 1) * STAGE;
-    const unsigned char* Vs = Ks + TL::BYTES;
+    __builtin_amdgcn_sched_barrier(0);
+    const unsigned char* Ks = cur;
+    const unsigned char* Vs = cur + TL::BYTES;
 
     f32x16 sacc, dpacc;
 #pragma unroll
@@ -88,13 +85,14 @@ __global__ __launch_bounds__(256, 2) void k_fine_bwd_dq(int Nc, int K, float sl2
 #pragma unroll
     for (int s = 0; s < KS; ++s) dpacc = mfma32(TL::rowmajor_operand(Vs, kh * 32, s, lane), doreg[s], dpacc);
 
-    const uint32_t mh = (uint32_t)(kmask >> (kh * 32));
     float ds[16];
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      float p = fast_exp2(fmaf(sacc[i], sl2, -lse2));
-      if (!((mh >> (8 * (i / 4) + 4 * h + (i % 4))) & 1)) p = 0.f;
-      ds[i] = p * (dpacc[i] - dl);
+    for (int i = 0; i < 16; ++i) ds[i] = fast_exp2(fmaf(sacc[i], sl2, -lse2)) * (dpacc[i] - dl);
+    if (kmask != ~0ull) {
+      const uint32_t mh = (uint32_t)(kmask >> (kh * 32));
+#pragma unroll
+      for (int i = 0; i < 16; ++i)
+        if (!((mh >> (8 * (i / 4) + 4 * h + (i % 4))) & 1)) ds[i] = 0.f;
     }
     const bf16x8 b0 = acc_to_operand(ds), b1 = acc_to_operand(ds + 8);
 #pragma unroll
@@ -102,23 +100,24 @@ __global__ __launch_bounds__(256, 2) void k_fine_bwd_dq(int Nc, int K, float sl2
       acc[x] = mfma32(TL::transposed_operand(Ks, kh * 32, 0, x * 32, lane), b0, acc[x]);
       acc[x] = mfma32(TL::transposed_operand(Ks, kh * 32, 1, x * 32, lane), b1, acc[x]);
     }
-
-    if (t + 1 < K) {
-      unsigned char* nxt = smem + ((t + 1) & 1) * STAGE;
-      TL::lstore(nxt, tid, pk);
-      TL::lstore(nxt + TL::BYTES, tid, pv);
-    }
     __syncthreads();
+  };
+
+  for (int t = 0; t < K; t += 2) {
+    body(stage0, stage1, t);
+    if (t + 1 < K) body(stage1, stage0, t + 1);
   }
 
-  float* Op = (float*)smem + wave * 32 * OS;
+  {
+    float* Op = (float*)(kh == 0 ? stage0 : stage1) + qh * 32 * OS;
 #pragma unroll
-  for (int x = 0; x < DVB; ++x)
+    for (int x = 0; x < DVB; ++x)
 #pragma unroll
-    for (int g4 = 0; g4 < 4; ++g4) {
-      float4 val = make_float4(acc[x][4 * g4], acc[x][4 * g4 + 1], acc[x][4 * g4 + 2], acc[x][4 * g4 + 3]);
-      *(float4*)&Op[l32 * OS + x * 32 + 8 * g4 + 4 * h] = val;
-    }
+      for (int g4 = 0; g4 < 4; ++g4) {
+        float4 val = make_float4(acc[x][4 * g4], acc[x][4 * g4 + 1], acc[x][4 * g4 + 2], acc[x][4 * g4 + 3]);
+        *(float4*)&Op[l32 * OS + x * 32 + 8 * g4 + 4 * h] = val;
+      }
+  }
   __syncthreads();
 
   const float inv_cnt = 1.0f / (float)__popcll(qmask);
@@ -126,9 +125,8 @@ __global__ __launch_bounds__(256, 2) void k_fine_bwd_dq(int Nc, int K, float sl2
 #pragma unroll
   for (int it = 0; it < LPT; ++it) {
     const int item = it * 256 + tid, r = item / CPR, ch = item % CPR;
-    const int wa = r >> 5, wb = wa + 2, ql = r & 31;
-    const float* Oa = (const float*)smem + (wa * 32 + ql) * OS + ch * 8;
-    const float* Ob = (const float*)smem + (wb * 32 + ql) * OS + ch * 8;
+    const float* Oa = (const float*)stage0 + r * OS + ch * 8;
+    const float* Ob = (const float*)stage1 + r * OS + ch * 8;
     uint4 ov = make_uint4(0, 0, 0, 0);
     if ((qmask >> r) & 1) {
       float res[8];
@@ -159,24 +157,25 @@ hipError_t launch_fine_bwd_dq(int BH, int Nc, int d, int K, float scale, const v
 // query cubes that selected this key cube.  Wavefront (kh, qh): key rows kh*32..+31 (its output
 // rows; K and V of those rows stay in registers), query rows qh*32..+31 of each streamed tile.
 // Here S (not S^T) is formed, so a lane holds one key column and 16 query rows; lse and Delta
-// of the streamed query tile are staged in LDS next to the tiles.
+// of the streamed query tile are staged in LDS next to the tiles.  `lse2_f` is lse*log2(e) with
+// +inf on pad query rows (written by the preprocess kernel), so pad queries give P = 0.
 template <int D>
 __global__ __launch_bounds__(256, 1) void k_fine_bwd_dkv(int Nc, int K, float sl2, float scale, const uint4* __restrict__ q,
                                                          const uint4* __restrict__ k, const uint4* __restrict__ v,
                                                          const uint4* __restrict__ dof,
                                                          const int32_t* __restrict__ row_ptr,
                                                          const int32_t* __restrict__ col,
-                                                         const float* __restrict__ lse_f, const float* __restrict__ delta,
+                                                         const float* __restrict__ lse2_f, const float* __restrict__ delta,
                                                          const float* __restrict__ dkc, const float* __restrict__ dvc,
                                                          const uint64_t* __restrict__ mask, uint4* __restrict__ dk,
                                                          uint4* __restrict__ dv) {
   using TL = Tile<D>;
   constexpr int CPR = TL::CPR, KS = D / 16, DVB = D / 32, LPT = TL::LPT;
-  constexpr int OS = D + 4;
+  constexpr int OS = D;
   constexpr int STAGE = 2 * TL::BYTES + 2 * kTile * 4;  // Q tile, dOf tile, lse2[64], delta[64]
-  constexpr int MERGE = 4 * 32 * OS * 4;
-  constexpr int LDS = (2 * STAGE > MERGE) ? 2 * STAGE : MERGE;
-  __shared__ __attribute__((aligned(16))) unsigned char smem[LDS];
+  __shared__ __attribute__((aligned(16))) unsigned char stage0[STAGE];
+  __shared__ __attribute__((aligned(16))) unsigned char stage1[STAGE];
+  static_assert(2 * 32 * OS * 4 <= STAGE, "merge buffer must fit in one stage");
 
   const int j = blockIdx.x % Nc;
   const long long bh = blockIdx.x / Nc;
@@ -187,6 +186,19 @@ __global__ __launch_bounds__(256, 1) void k_fine_bwd_dkv(int Nc, int K, float sl
   const int32_t* rp = row_ptr + bh * (Nc + 1);
   const int beg = rp[j], end = rp[j + 1];
   const int32_t* my_col = col + bh * (long long)Nc * K;
+
+  // asynchronous fill of one stage: the two tiles by all waves, lse2 by wave 0, delta by wave 1
+  auto fill = [&](unsigned char* st, int cq) {
+    const long long r0 = rows0 + (long long)cq * kTile;
+    TL::async_load(q, r0, st, wave, lane);
+    TL::async_load(dof, r0, st + TL::BYTES, wave, lane);
+    if (wave == 0)
+      __builtin_amdgcn_global_load_lds((global_void_ptr)(lse2_f + r0 + lane), (lds_void_ptr)(st + 2 * TL::BYTES), 4, 0, 0);
+    if (wave == 1)
+      __builtin_amdgcn_global_load_lds((global_void_ptr)(delta + r0 + lane),
+                                       (lds_void_ptr)(st + 2 * TL::BYTES + kTile * 4), 4, 0, 0);
+  };
+  if (beg < end) fill(stage0, my_col[beg]);
 
   bf16x8 kreg[KS], vreg[KS];
   {
@@ -205,39 +217,14 @@ __global__ __launch_bounds__(256, 1) void k_fine_bwd_dkv(int Nc, int K, float sl
   for (int x = 0; x < DVB; ++x)
 #pragma unroll
     for (int i = 0; i < 16; ++i) { dka[x][i] = 0.f; dva[x][i] = 0.f; }
-
-  uint4 pq[LPT], pd[LPT];
-  float pl = 0.f, pdl = 0.f;  // threads 0..63 carry lse2 / delta of one query row
-  auto fetch = [&](int cq) {
-    TL::gload(q, rows0 + (long long)cq * kTile, tid, pq);
-    TL::gload(dof, rows0 + (long long)cq * kTile, tid, pd);
-    if (tid < kTile) {
-      const bool qv = (mask[cq] >> tid) & 1;
-      pl = qv ? lse_f[rows0 + (long long)cq * kTile + tid] * kLog2e : INFINITY;
-      pdl = qv ? delta[rows0 + (long long)cq * kTile + tid] : 0.f;
-    }
-  };
-  auto stash = [&](unsigned char* stage) {
-    TL::lstore(stage, tid, pq);
-    TL::lstore(stage + TL::BYTES, tid, pd);
-    if (tid < kTile) {
-      ((float*)(stage + 2 * TL::BYTES))[tid] = pl;
-      ((float*)(stage + 2 * TL::BYTES))[kTile + tid] = pdl;
-    }
-  };
-
-  if (beg < end) {
-    fetch(my_col[beg]);
-    stash(smem);
-  }
   __syncthreads();
 
-  for (int t = beg; t < end; ++t) {
-    if (t + 1 < end) fetch(my_col[t + 1]);
-    const unsigned char* st = smem + ((t - beg) & 1) * STAGE;
-    const unsigned char* Qs = st;
-    const unsigned char* Ds = st + TL::BYTES;
-    const float* ls = (const float*)(st + 2 * TL::BYTES);
+  auto body = [&](const unsigned char* cur, unsigned char* nxt, int t) {
+    if (t + 1 < end) fill(nxt, my_col[t + 1]);
+    __builtin_amdgcn_sched_barrier(0);
+    const unsigned char* Qs = cur;
+    const unsigned char* Ds = cur + TL::BYTES;
+    const float* ls = (const float*)(cur + 2 * TL::BYTES);
 
     f32x16 sacc, dpacc;
 #pragma unroll
@@ -271,15 +258,18 @@ __global__ __launch_bounds__(256, 1) void k_fine_bwd_dkv(int Nc, int K, float sl
       dka[x] = mfma32(TL::transposed_operand(Qs, qh * 32, 0, x * 32, lane), sb0, dka[x]);
       dka[x] = mfma32(TL::transposed_operand(Qs, qh * 32, 1, x * 32, lane), sb1, dka[x]);
     }
-
-    if (t + 1 < end) stash(smem + ((t + 1 - beg) & 1) * STAGE);
     __syncthreads();
+  };
+
+  for (int t = beg; t < end; t += 2) {
+    body(stage0, stage1, t);
+    if (t + 1 < end) body(stage1, stage0, t + 1);
   }
 
-  // merge the two query halves; dK first, then dV through the same buffer
+  // merge the two query halves; dK first, then dV through the same buffers
   const float inv_cnt = 1.0f / (float)__popcll(kmask);
   for (int pass = 0; pass < 2; ++pass) {
-    float* Op = (float*)smem + wave * 32 * OS;
+    float* Op = (float*)(qh == 0 ? stage0 : stage1) + kh * 32 * OS;
 #pragma unroll
     for (int x = 0; x < DVB; ++x)
 #pragma unroll
@@ -295,9 +285,8 @@ __global__ __launch_bounds__(256, 1) void k_fine_bwd_dkv(int Nc, int K, float sl
 #pragma unroll
     for (int it = 0; it < LPT; ++it) {
       const int item = it * 256 + tid, r = item / CPR, ch = item % CPR;
-      const int wa = r >> 5, wb = wa + 2, kl = r & 31;  // waves (kh = r/32, qh = 0) and (kh, qh = 1)
-      const float* Oa = (const float*)smem + (wa * 32 + kl) * OS + ch * 8;
-      const float* Ob = (const float*)smem + (wb * 32 + kl) * OS + ch * 8;
+      const float* Oa = (const float*)stage0 + r * OS + ch * 8;
+      const float* Ob = (const float*)stage1 + r * OS + ch * 8;
       uint4 ov = make_uint4(0, 0, 0, 0);
       if ((kmask >> r) & 1) {
         float res[8];

@@ -27,11 +27,14 @@ __global__ __launch_bounds__(256, 2) void k_fine_fwd(int Nc, int K, float sl2, c
                                                      uint4* __restrict__ out_fine, float* __restrict__ lse_f) {
   using TL = Tile<D>;
   constexpr int CPR = TL::CPR, KS = D / 16, DVB = D / 32, LPT = TL::LPT;
-  constexpr int OS = D + 4;  // fp32 row stride of the merge buffer
-  constexpr int STAGE = 2 * TL::BYTES;
-  constexpr int MERGE = 4 * 32 * OS * 4 + 4 * 32 * 2 * 4;
-  constexpr int LDS = (2 * STAGE > MERGE) ? 2 * STAGE : MERGE;
-  __shared__ __attribute__((aligned(16))) unsigned char smem[LDS];
+  constexpr int OS = D;  // fp32 row stride of the merge buffer
+  constexpr int STAGE = 2 * TL::BYTES;  // K tile + V tile
+  // Two separate LDS objects: the compiler can then tell that the asynchronous fill of one
+  // stage does not alias the reads of the other and keeps the copy in flight during the math.
+  __shared__ __attribute__((aligned(16))) unsigned char stage0[STAGE];
+  __shared__ __attribute__((aligned(16))) unsigned char stage1[STAGE];
+  __shared__ float ml[4 * 32 * 2];
+  static_assert(2 * 32 * OS * 4 <= STAGE, "merge buffer must fit in one stage");
 
   const int c = blockIdx.x % Nc;
   const long long bh = blockIdx.x / Nc;
@@ -40,6 +43,10 @@ __global__ __launch_bounds__(256, 2) void k_fine_fwd(int Nc, int K, float sl2, c
   const long long rows0 = bh * (long long)Nc * kTile;  // first row of this (b,h)
   const int32_t* my_idx = idx + (bh * Nc + c) * (long long)K;
 
+  int jt = my_idx[0];
+  TL::async_load(k, rows0 + (long long)jt * kTile, stage0, wave, lane);
+  TL::async_load(v, rows0 + (long long)jt * kTile, stage0 + TL::BYTES, wave, lane);
+
   bf16x8 qreg[KS];
   {
     const uint4* qrow = q + (rows0 + c * kTile + qh * 32 + l32) * CPR;
@@ -47,30 +54,25 @@ __global__ __launch_bounds__(256, 2) void k_fine_fwd(int Nc, int K, float sl2, c
     for (int s = 0; s < KS; ++s) qreg[s] = __builtin_bit_cast(bf16x8, qrow[2 * s + h]);
   }
 
-  uint4 pk[LPT], pv[LPT];
-  int jt = my_idx[0];
-  TL::gload(k, rows0 + (long long)jt * kTile, tid, pk);
-  TL::gload(v, rows0 + (long long)jt * kTile, tid, pv);
-  TL::lstore(smem, tid, pk);
-  TL::lstore(smem + TL::BYTES, tid, pv);
-  __syncthreads();
-
   float m2 = -INFINITY, lsum = 0.f;
   f32x16 o[DVB];
 #pragma unroll
   for (int x = 0; x < DVB; ++x)
 #pragma unroll
     for (int i = 0; i < 16; ++i) o[x][i] = 0.f;
+  __syncthreads();
 
-  for (int t = 0; t < K; ++t) {
+  // One key tile: start the copy of the next tile pair into `nxt`, do the math on `cur`.
+  auto body = [&](const unsigned char* cur, unsigned char* nxt, int t) {
     const uint64_t kmask = mask[jt];
     if (t + 1 < K) {
       jt = my_idx[t + 1];
-      TL::gload(k, rows0 + (long long)jt * kTile, tid, pk);
-      TL::gload(v, rows0 + (long long)jt * kTile, tid, pv);
+      TL::async_load(k, rows0 + (long long)jt * kTile, nxt, wave, lane);
+      TL::async_load(v, rows0 + (long long)jt * kTile, nxt + TL::BYTES, wave, lane);
     }
-    const unsigned char* Ks = smem + (t & 1) * STAGE;
-    const unsigned char* Vs = Ks + TL::BYTES;
+    __builtin_amdgcn_sched_barrier(0);
+    const unsigned char* Ks = cur;
+    const unsigned char* Vs = cur + TL::BYTES;
 
     f32x16 sacc;
 #pragma unroll
@@ -112,26 +114,27 @@ __global__ __launch_bounds__(256, 2) void k_fine_fwd(int Nc, int K, float sl2, c
       o[x] = mfma32(TL::transposed_operand(Vs, kh * 32, 0, x * 32, lane), pb0, o[x]);
       o[x] = mfma32(TL::transposed_operand(Vs, kh * 32, 1, x * 32, lane), pb1, o[x]);
     }
+    __syncthreads();  // its fence also waits for this wave's share of the asynchronous copy
+  };
 
-    if (t + 1 < K) {
-      unsigned char* nxt = smem + ((t + 1) & 1) * STAGE;
-      TL::lstore(nxt, tid, pk);
-      TL::lstore(nxt + TL::BYTES, tid, pv);
-    }
-    __syncthreads();
+  for (int t = 0; t < K; t += 2) {
+    body(stage0, stage1, t);
+    if (t + 1 < K) body(stage1, stage0, t + 1);
   }
 
   // ---- merge the two key halves, normalise, gate, store
+  // Partial O of wave (qh, kh) goes to rows qh*32.. of stage `kh` (fp32 [64][D] each).
   lsum += __shfl_xor(lsum, 32);
-  float* Op = (float*)smem + wave * 32 * OS;
-  float* ml = (float*)smem + 4 * 32 * OS;
+  {
+    float* Op = (float*)(kh == 0 ? stage0 : stage1) + qh * 32 * OS;
 #pragma unroll
-  for (int x = 0; x < DVB; ++x)
+    for (int x = 0; x < DVB; ++x)
 #pragma unroll
-    for (int g4 = 0; g4 < 4; ++g4) {
-      float4 val = make_float4(o[x][4 * g4], o[x][4 * g4 + 1], o[x][4 * g4 + 2], o[x][4 * g4 + 3]);
-      *(float4*)&Op[l32 * OS + x * 32 + 8 * g4 + 4 * h] = val;
-    }
+      for (int g4 = 0; g4 < 4; ++g4) {
+        float4 val = make_float4(o[x][4 * g4], o[x][4 * g4 + 1], o[x][4 * g4 + 2], o[x][4 * g4 + 3]);
+        *(float4*)&Op[l32 * OS + x * 32 + 8 * g4 + 4 * h] = val;
+      }
+  }
   if (h == 0) {
     ml[(wave * 32 + l32) * 2] = m2;
     ml[(wave * 32 + l32) * 2 + 1] = lsum;
@@ -150,8 +153,8 @@ __global__ __launch_bounds__(256, 2) void k_fine_fwd(int Nc, int K, float sl2, c
     float fa = fast_exp2(ma - M), fb = fast_exp2(mb - M);
     const float inv = 1.0f / (la * fa + lb * fb);
     fa *= inv; fb *= inv;
-    const float* Oa = (const float*)smem + (wa * 32 + ql) * OS + ch * 8;
-    const float* Ob = (const float*)smem + (wb * 32 + ql) * OS + ch * 8;
+    const float* Oa = (const float*)stage0 + r * OS + ch * 8;
+    const float* Ob = (const float*)stage1 + r * OS + ch * 8;
     float of[8], res[8];
     const float4 a0 = *(const float4*)Oa, a1 = *(const float4*)(Oa + 4);
     const float4 b0 = *(const float4*)Ob, b1 = *(const float4*)(Ob + 4);

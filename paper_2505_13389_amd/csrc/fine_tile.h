@@ -12,6 +12,8 @@
 namespace vsa {
 
 typedef bf16x4 __attribute__((address_space(3))) * lds_bf16x4_ptr;
+typedef __attribute__((address_space(3))) void* lds_void_ptr;
+typedef __attribute__((address_space(1))) const void* global_void_ptr;
 
 template <int D>
 struct Tile {
@@ -39,6 +41,24 @@ struct Tile {
     for (int it = 0; it < LPT; ++it) {
       int item = it * 256 + tid;
       *(uint4*)(tile + off(item / CPR, item % CPR)) = regs[it];
+    }
+  }
+
+  // Asynchronous global -> LDS copy of one tile by the 4 wavefronts of a workgroup, without
+  // passing through registers (global_load_lds_dwordx4).  One wave instruction fills 1 KiB of
+  // consecutive LDS (RPI rows); the swizzle is applied on the SOURCE side: the lane that writes
+  // physical chunk pc of row r fetches logical chunk pc ^ swz(r).  Completion is tracked by
+  // vmcnt; the caller waits (the barrier's fence does) before other waves read the tile.
+  static constexpr int RPI = 1024 / ROW_BYTES;   // rows per wave instruction
+  static constexpr int IPW = kTile / RPI / 4;    // instructions per wave and tile
+  __device__ static __forceinline__ void async_load(const uint4* __restrict__ src, long long row0, unsigned char* tile,
+                                                    int wave, int lane) {
+#pragma unroll
+    for (int i = 0; i < IPW; ++i) {
+      const int r0 = (wave * IPW + i) * RPI;
+      const int r = r0 + lane / CPR, pc = lane % CPR;
+      const uint4* g = src + (row0 + r) * CPR + (pc ^ swz(r));
+      __builtin_amdgcn_global_load_lds((global_void_ptr)g, (lds_void_ptr)(tile + r0 * ROW_BYTES), 16, 0, 0);
     }
   }
 

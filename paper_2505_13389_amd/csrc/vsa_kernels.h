@@ -18,7 +18,7 @@ hipError_t launch_fine_fwd(int BH, int Nc, int d, int K, float scale, const void
 // backward
 hipError_t launch_bwd_pre(int BH, int Nc, int d, const uint64_t* mask, const void* dout, const void* gate_c,
                           const void* gate_f, const void* out_fine, const float* oc, void* dgate_c, void* dgate_f,
-                          void* dof, float* delta, float* doc, hipStream_t s);
+                          void* dof, float* delta, float* doc, const float* lse_f, float* lse2, hipStream_t s);
 hipError_t launch_coarse_bwd(int BH, int Nc, int d, float scale, const float* qc, const float* kc, const float* vc,
                              const float* lse_c, const float* doc, float* ac, float* dsc, float* dqc, float* dkc,
                              float* dvc,
