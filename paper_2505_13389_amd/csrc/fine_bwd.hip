@@ -40,10 +40,6 @@ __global__ __launch_bounds__(256, 2) void k_fine_bwd_dq(int Nc, int K, float sl2
   const int32_t* my_idx = idx + (bh * Nc + c) * (long long)K;
   const uint64_t qmask = mask[c];
 
-  int jt = my_idx[0];
-  TL::async_load(k, rows0 + (long long)jt * kTile, stage0, wave, lane);
-  TL::async_load(v, rows0 + (long long)jt * kTile, stage0 + TL::BYTES, wave, lane);
-
   const long long qrow_g = rows0 + c * kTile + qh * 32 + l32;
   bf16x8 qreg[KS], doreg[KS];
   {
@@ -56,22 +52,36 @@ __global__ __launch_bounds__(256, 2) void k_fine_bwd_dq(int Nc, int K, float sl2
     }
   }
   // lse2 = lse*log2(e), +inf on pad query rows (then P = 0 and the row contributes nothing)
-  const float lse2 = lse2_f[qrow_g];
-  const float dl = delta[qrow_g];
+  float lse2 = lse2_f[qrow_g];
+  float dl = delta[qrow_g];
+  // Everything loaded the ordinary way must have arrived before the first hand-ordered copy is
+  // issued (the compiler cannot see those copies; see Tile::async_load).
+#pragma unroll
+  for (int s = 0; s < KS; ++s) asm volatile("" : "+v"(qreg[s]), "+v"(doreg[s]));
+  asm volatile("" : "+v"(lse2), "+v"(dl));
+
+  unsigned goff[TL::IPW];
+  TL::lane_offsets(wave, lane, goff);
+  int jt = my_idx[0];
+  TL::async_load(k, rows0 + (long long)jt * kTile, stage0, wave, goff);
+  TL::async_load(v, rows0 + (long long)jt * kTile, stage0 + TL::BYTES, wave, goff);
 
   f32x16 acc[DVB];
 #pragma unroll
   for (int x = 0; x < DVB; ++x)
 #pragma unroll
     for (int i = 0; i < 16; ++i) acc[x][i] = 0.f;
-  __syncthreads();
 
+  // Per tile: wait for this wave's share of tile t, barrier (tile t complete, and every wave is
+  // done with tile t-1), start the copy of tile t+1 into the other stage, do the math on tile t.
   auto body = [&](const unsigned char* cur, unsigned char* nxt, int t) {
     const uint64_t kmask = mask[jt];
+    wait_vmcnt<0>();
+    __builtin_amdgcn_s_barrier();
     if (t + 1 < K) {
       jt = my_idx[t + 1];
-      TL::async_load(k, rows0 + (long long)jt * kTile, nxt, wave, lane);
-      TL::async_load(v, rows0 + (long long)jt * kTile, nxt + TL::BYTES, wave, lane);
+      TL::async_load(k, rows0 + (long long)jt * kTile, nxt, wave, goff);
+      TL::async_load(v, rows0 + (long long)jt * kTile, nxt + TL::BYTES, wave, goff);
     }
     __builtin_amdgcn_sched_barrier(0);
     const unsigned char* Ks = cur;
@@ -100,13 +110,13 @@ __global__ __launch_bounds__(256, 2) void k_fine_bwd_dq(int Nc, int K, float sl2
       acc[x] = mfma32(TL::transposed_operand(Ks, kh * 32, 0, x * 32, lane), b0, acc[x]);
       acc[x] = mfma32(TL::transposed_operand(Ks, kh * 32, 1, x * 32, lane), b1, acc[x]);
     }
-    __syncthreads();
   };
 
   for (int t = 0; t < K; t += 2) {
     body(stage0, stage1, t);
     if (t + 1 < K) body(stage1, stage0, t + 1);
   }
+  __syncthreads();
 
   {
     float* Op = (float*)(kh == 0 ? stage0 : stage1) + qh * 32 * OS;
@@ -188,17 +198,16 @@ __global__ __launch_bounds__(256, 1) void k_fine_bwd_dkv(int Nc, int K, float sl
   const int32_t* my_col = col + bh * (long long)Nc * K;
 
   // asynchronous fill of one stage: the two tiles by all waves, lse2 by wave 0, delta by wave 1
+  unsigned goff[TL::IPW];
+  TL::lane_offsets(wave, lane, goff);
   auto fill = [&](unsigned char* st, int cq) {
     const long long r0 = rows0 + (long long)cq * kTile;
-    TL::async_load(q, r0, st, wave, lane);
-    TL::async_load(dof, r0, st + TL::BYTES, wave, lane);
-    if (wave == 0)
-      __builtin_amdgcn_global_load_lds((global_void_ptr)(lse2_f + r0 + lane), (lds_void_ptr)(st + 2 * TL::BYTES), 4, 0, 0);
+    TL::async_load(q, r0, st, wave, goff);
+    TL::async_load(dof, r0, st + TL::BYTES, wave, goff);
+    if (wave == 0) lds_dma4(lse2_f + r0, lane * 4u, __builtin_amdgcn_readfirstlane(lds_address(st) + 2 * TL::BYTES));
     if (wave == 1)
-      __builtin_amdgcn_global_load_lds((global_void_ptr)(delta + r0 + lane),
-                                       (lds_void_ptr)(st + 2 * TL::BYTES + kTile * 4), 4, 0, 0);
+      lds_dma4(delta + r0, lane * 4u, __builtin_amdgcn_readfirstlane(lds_address(st) + 2 * TL::BYTES + kTile * 4));
   };
-  if (beg < end) fill(stage0, my_col[beg]);
 
   bf16x8 kreg[KS], vreg[KS];
   {
@@ -211,15 +220,20 @@ __global__ __launch_bounds__(256, 1) void k_fine_bwd_dkv(int Nc, int K, float sl
     }
   }
   const bool kvalid = (kmask >> (kh * 32 + l32)) & 1;
+  // ordinary loads done before the first hand-ordered copy (see Tile::async_load)
+#pragma unroll
+  for (int s = 0; s < KS; ++s) asm volatile("" : "+v"(kreg[s]), "+v"(vreg[s]));
+  if (beg < end) fill(stage0, my_col[beg]);
 
   f32x16 dka[DVB], dva[DVB];
 #pragma unroll
   for (int x = 0; x < DVB; ++x)
 #pragma unroll
     for (int i = 0; i < 16; ++i) { dka[x][i] = 0.f; dva[x][i] = 0.f; }
-  __syncthreads();
 
   auto body = [&](const unsigned char* cur, unsigned char* nxt, int t) {
+    wait_vmcnt<0>();
+    __builtin_amdgcn_s_barrier();
     if (t + 1 < end) fill(nxt, my_col[t + 1]);
     __builtin_amdgcn_sched_barrier(0);
     const unsigned char* Qs = cur;
@@ -258,13 +272,13 @@ __global__ __launch_bounds__(256, 1) void k_fine_bwd_dkv(int Nc, int K, float sl
       dka[x] = mfma32(TL::transposed_operand(Qs, qh * 32, 0, x * 32, lane), sb0, dka[x]);
       dka[x] = mfma32(TL::transposed_operand(Qs, qh * 32, 1, x * 32, lane), sb1, dka[x]);
     }
-    __syncthreads();
   };
 
   for (int t = beg; t < end; t += 2) {
     body(stage0, stage1, t);
     if (t + 1 < end) body(stage1, stage0, t + 1);
   }
+  __syncthreads();
 
   // merge the two query halves; dK first, then dV through the same buffers
   const float inv_cnt = 1.0f / (float)__popcll(kmask);

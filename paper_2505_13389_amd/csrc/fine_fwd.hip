@@ -18,6 +18,9 @@
 
 namespace vsa {
 
+constexpr float kMaskBias = -30000.f;  // added to the raw logits of pad keys (|q.k| is assumed < 15000)
+constexpr float kTau = 8.f;             // lazy-rescale threshold, log2 units
+
 template <int D>
 __global__ __launch_bounds__(256, 2) void k_fine_fwd(int Nc, int K, float sl2, const uint4* __restrict__ q,
                                                      const uint4* __restrict__ k, const uint4* __restrict__ v,
@@ -43,84 +46,130 @@ __global__ __launch_bounds__(256, 2) void k_fine_fwd(int Nc, int K, float sl2, c
   const long long rows0 = bh * (long long)Nc * kTile;  // first row of this (b,h)
   const int32_t* my_idx = idx + (bh * Nc + c) * (long long)K;
 
-  int jt = my_idx[0];
-  TL::async_load(k, rows0 + (long long)jt * kTile, stage0, wave, lane);
-  TL::async_load(v, rows0 + (long long)jt * kTile, stage0 + TL::BYTES, wave, lane);
-
   bf16x8 qreg[KS];
   {
     const uint4* qrow = q + (rows0 + c * kTile + qh * 32 + l32) * CPR;
 #pragma unroll
     for (int s = 0; s < KS; ++s) qreg[s] = __builtin_bit_cast(bf16x8, qrow[2 * s + h]);
   }
+  // Q must have arrived before the first hand-ordered copy is issued: afterwards the compiler's
+  // own vmcnt bookkeeping (which cannot see those copies) has nothing left to wait for in the loop.
+  // The empty asm consumes the registers, so the compiler has to place its wait right here.
+#pragma unroll
+  for (int s = 0; s < KS; ++s) asm volatile("" : "+v"(qreg[s]));
 
-  float m2 = -INFINITY, lsum = 0.f;
+  // Software pipeline of the K/V stream.  Two LDS stages; at the top of iteration t the whole
+  // tile pair t is pulled from its stage into registers (MFMA operands), which frees the stage
+  // at once for tile t+2, so two tile pairs per workgroup are in flight behind the math of one.
+  //   wait(own share of tile t landed) ; barrier ; LDS -> registers ; barrier ; refill ; math
+  // The barriers are raw s_barrier (no fence): a fence would drain the copies still in flight.
+  // vmcnt is waited by hand: copies complete in issue order, NL = copies per wave and tile pair.
+  constexpr int NL = 2 * TL::IPW;
+  unsigned goff[TL::IPW];
+  TL::lane_offsets(wave, lane, goff);
+  auto issue = [&](unsigned char* st, int j) {
+    TL::async_load(k, rows0 + (long long)j * kTile, st, wave, goff);
+    TL::async_load(v, rows0 + (long long)j * kTile, st + TL::BYTES, wave, goff);
+  };
+  // Every iteration issues exactly NL copies, also past the end of the list (the last tile is
+  // simply fetched again): the number of copies younger than the tile being waited for is then
+  // always NL, which both the hand-written waits and the compiler's own bookkeeping rely on.
+  int j0 = my_idx[0], j1 = my_idx[min(1, K - 1)];
+  issue(stage0, j0);
+  issue(stage1, j1);
+
+  float mref = -INFINITY, lsum = 0.f;
+  const bf16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
+  bf16x8 ones_b = zero8;
+  ones_b[0] = (h == 0) ? (__bf16)1.f : (__bf16)0.f;
   f32x16 o[DVB];
 #pragma unroll
   for (int x = 0; x < DVB; ++x)
 #pragma unroll
     for (int i = 0; i < 16; ++i) o[x][i] = 0.f;
-  __syncthreads();
 
-  // One key tile: start the copy of the next tile pair into `nxt`, do the math on `cur`.
-  auto body = [&](const unsigned char* cur, unsigned char* nxt, int t) {
-    const uint64_t kmask = mask[jt];
-    if (t + 1 < K) {
-      jt = my_idx[t + 1];
-      TL::async_load(k, rows0 + (long long)jt * kTile, nxt, wave, lane);
-      TL::async_load(v, rows0 + (long long)jt * kTile, nxt + TL::BYTES, wave, lane);
-    }
-    __builtin_amdgcn_sched_barrier(0);
+  // j0 = tile of this iteration, j1 = tile of the next one (already in flight)
+  auto body = [&](unsigned char* cur, int t) {
+    const uint64_t kmask = mask[j0];
+    wait_vmcnt<NL>();  // this wave's share of tile pair t has landed (only the NL copies of t+1 may be pending)
+    __builtin_amdgcn_s_barrier();
     const unsigned char* Ks = cur;
     const unsigned char* Vs = cur + TL::BYTES;
+    bf16x8 ka[KS], va[DVB][2];
+#pragma unroll
+    for (int s = 0; s < KS; ++s) ka[s] = TL::rowmajor_operand(Ks, kh * 32, s, lane);
+#pragma unroll
+    for (int x = 0; x < DVB; ++x) {
+      va[x][0] = TL::transposed_operand(Vs, kh * 32, 0, x * 32, lane);
+      va[x][1] = TL::transposed_operand(Vs, kh * 32, 1, x * 32, lane);
+    }
+    wait_lgkmcnt0();  // this wave's LDS reads of the stage are done
+    __builtin_amdgcn_s_barrier();
+    j0 = j1;
+    j1 = my_idx[min(t + 2, K - 1)];
+    issue(cur, j1);
+    __builtin_amdgcn_sched_barrier(0);
 
     f32x16 sacc;
 #pragma unroll
     for (int i = 0; i < 16; ++i) sacc[i] = 0.f;
 #pragma unroll
-    for (int s = 0; s < KS; ++s) sacc = mfma32(TL::rowmajor_operand(Ks, kh * 32, s, lane), qreg[s], sacc);
+    for (int s = 0; s < KS; ++s) sacc = mfma32(ka[s], qreg[s], sacc);
 
-    if (kmask != ~0ull) {  // pad keys of a partially filled cube never take part
-      const uint32_t mh = (uint32_t)(kmask >> (kh * 32));
-#pragma unroll
-      for (int i = 0; i < 16; ++i)
-        if (!((mh >> (8 * (i / 4) + 4 * h + (i % 4))) & 1)) sacc[i] = -INFINITY;
+    // Pad keys of a partially filled cube never take part: one extra MFMA adds a large negative
+    // bias to their rows of S^T (A = bias of key l%32 in contraction slot 0, B = ones in slot 0).
+    const bool partial = kmask != ~0ull;
+    if (partial) {
+      const bool dead = !((kmask >> (kh * 32 + l32)) & 1);
+      bf16x8 ab = zero8;
+      ab[0] = (h == 0 && dead) ? (__bf16)kMaskBias : (__bf16)0.f;
+      sacc = mfma32(ab, ones_b, sacc);
     }
 
-    float mx = sacc[0];
+    // Online softmax with a lazily updated reference maximum: mref only moves when the running
+    // maximum exceeds it by more than kTau (log2 units), so exp2(s - mref) stays below 2^kTau and
+    // the O / l rescale is skipped for almost every tile.  The result is exact either way.
+    float mx = fmaxf(fmaxf(sacc[0], sacc[1]), sacc[2]);
 #pragma unroll
-    for (int i = 1; i < 16; ++i) mx = fmaxf(mx, sacc[i]);
+    for (int i = 3; i < 15; i += 2) mx = fmaxf(fmaxf(mx, sacc[i]), sacc[i + 1]);
+    mx = fmaxf(mx, sacc[15]);
     mx = fmaxf(mx, __shfl_xor(mx, 32));
-    const float m2new = fmaxf(m2, mx * sl2);
-    const float muse = (m2new == -INFINITY) ? 0.f : m2new;
-    const float alpha = fast_exp2(m2 - muse);
-    float p[16], rs = 0.f;
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      p[i] = fast_exp2(fmaf(sacc[i], sl2, -muse));
-      rs += p[i];
-    }
-    lsum = lsum * alpha + rs;
-    m2 = m2new;
-    if (__any(alpha != 1.0f)) {
+    if (partial && mx < 0.5f * kMaskBias) mx = -INFINITY;  // every key of this half is a pad
+    const float mx2 = mx * sl2;
+    if (__any(mx2 > mref + kTau)) {
+      // only the lanes over the threshold move their reference: a lane's arithmetic then never
+      // depends on what other query columns (pad rows included) hold
+      const float mnew = (mx2 > mref + kTau) ? mx2 : mref;
+      // mref = -inf: nothing accumulated yet, the factor is irrelevant but must not be NaN
+      const float alpha = (mnew == -INFINITY) ? 1.f : fast_exp2(mref - mnew);
+      lsum *= alpha;
 #pragma unroll
       for (int x = 0; x < DVB; ++x)
 #pragma unroll
         for (int i = 0; i < 16; ++i) o[x][i] *= alpha;
+      mref = mnew;
+    }
+    const float muse = (mref == -INFINITY) ? 0.f : mref;
+    float p[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      p[i] = fast_exp2(fmaf(sacc[i], sl2, -muse));
+      lsum += p[i];
     }
     const bf16x8 pb0 = acc_to_operand(p), pb1 = acc_to_operand(p + 8);
 #pragma unroll
     for (int x = 0; x < DVB; ++x) {
-      o[x] = mfma32(TL::transposed_operand(Vs, kh * 32, 0, x * 32, lane), pb0, o[x]);
-      o[x] = mfma32(TL::transposed_operand(Vs, kh * 32, 1, x * 32, lane), pb1, o[x]);
+      o[x] = mfma32(va[x][0], pb0, o[x]);
+      o[x] = mfma32(va[x][1], pb1, o[x]);
     }
-    __syncthreads();  // its fence also waits for this wave's share of the asynchronous copy
   };
 
   for (int t = 0; t < K; t += 2) {
-    body(stage0, stage1, t);
-    if (t + 1 < K) body(stage1, stage0, t + 1);
+    body(stage0, t);
+    if (t + 1 < K) body(stage1, t + 1);
   }
+  wait_vmcnt<0>();  // the two refetches issued past the end of the list
+  __syncthreads();
 
   // ---- merge the two key halves, normalise, gate, store
   // Partial O of wave (qh, kh) goes to rows qh*32.. of stage `kh` (fp32 [64][D] each).
@@ -136,7 +185,7 @@ __global__ __launch_bounds__(256, 2) void k_fine_fwd(int Nc, int K, float sl2, c
       }
   }
   if (h == 0) {
-    ml[(wave * 32 + l32) * 2] = m2;
+    ml[(wave * 32 + l32) * 2] = mref;
     ml[(wave * 32 + l32) * 2 + 1] = lsum;
   }
   __syncthreads();

@@ -15,6 +15,36 @@ typedef bf16x4 __attribute__((address_space(3))) * lds_bf16x4_ptr;
 typedef __attribute__((address_space(3))) void* lds_void_ptr;
 typedef __attribute__((address_space(1))) const void* global_void_ptr;
 
+// Byte address of an LDS object inside the workgroup's LDS allocation.
+__device__ __forceinline__ unsigned lds_address(const void* p) {
+  return (unsigned)(size_t)(__attribute__((address_space(3))) const unsigned char*)p;
+}
+
+// 64 lanes x 16 bytes, global -> LDS at lds_addr + lane*16; `base` and `lds_addr` wave-uniform.
+// M0 carries the LDS base of the instruction; it is written right before and named as clobbered.
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
+__device__ __forceinline__ void lds_dma16(const void* base, unsigned voff, unsigned lds_addr) {
+  asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1"
+               :
+               : "v"(voff), "s"(base), "s"(lds_addr)
+               : "memory", "m0");
+}
+__device__ __forceinline__ void lds_dma4(const void* base, unsigned voff, unsigned lds_addr) {
+  asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dword %0, %1"
+               :
+               : "v"(voff), "s"(base), "s"(lds_addr)
+               : "memory", "m0");
+}
+#pragma clang diagnostic pop
+
+// s_waitcnt immediates (gfx9 encoding: vmcnt in bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8).
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
+}
+__device__ __forceinline__ void wait_lgkmcnt0() { __builtin_amdgcn_s_waitcnt(0xC07F); }
+
 template <int D>
 struct Tile {
   static constexpr int CPR = D / 8;               // 16-byte chunks per row
@@ -47,19 +77,29 @@ struct Tile {
   // Asynchronous global -> LDS copy of one tile by the 4 wavefronts of a workgroup, without
   // passing through registers (global_load_lds_dwordx4).  One wave instruction fills 1 KiB of
   // consecutive LDS (RPI rows); the swizzle is applied on the SOURCE side: the lane that writes
-  // physical chunk pc of row r fetches logical chunk pc ^ swz(r).  Completion is tracked by
-  // vmcnt; the caller waits (the barrier's fence does) before other waves read the tile.
+  // physical chunk pc of row r fetches logical chunk pc ^ swz(r).  The per-lane source offsets
+  // do not depend on the tile and are computed once (lane_offsets); per tile the address is a
+  // wave-uniform tile pointer (scalar registers) plus that 32-bit offset.
+  //
+  // The copy is issued from inline assembly on purpose: the compiler then keeps no record of it,
+  // so it never drains it early, and the kernels order it by hand -- completion is counted by
+  // vmcnt in issue order, every wave waits for its own share (s_waitcnt) and a workgroup barrier
+  // then makes the whole tile visible.
   static constexpr int RPI = 1024 / ROW_BYTES;   // rows per wave instruction
   static constexpr int IPW = kTile / RPI / 4;    // instructions per wave and tile
-  __device__ static __forceinline__ void async_load(const uint4* __restrict__ src, long long row0, unsigned char* tile,
-                                                    int wave, int lane) {
+  __device__ static __forceinline__ void lane_offsets(int wave, int lane, unsigned* off) {
 #pragma unroll
     for (int i = 0; i < IPW; ++i) {
-      const int r0 = (wave * IPW + i) * RPI;
-      const int r = r0 + lane / CPR, pc = lane % CPR;
-      const uint4* g = src + (row0 + r) * CPR + (pc ^ swz(r));
-      __builtin_amdgcn_global_load_lds((global_void_ptr)g, (lds_void_ptr)(tile + r0 * ROW_BYTES), 16, 0, 0);
+      const int r = (wave * IPW + i) * RPI + lane / CPR, pc = lane % CPR;
+      off[i] = (unsigned)((r * CPR + (pc ^ swz(r))) * 16);
     }
+  }
+  __device__ static __forceinline__ void async_load(const uint4* __restrict__ src, long long row0, unsigned char* tile,
+                                                    int wave, const unsigned* off) {
+    const uint4* g = src + row0 * CPR;  // wave-uniform
+    const unsigned lds0 = __builtin_amdgcn_readfirstlane(lds_address(tile) + (unsigned)(wave * IPW) * 1024u);
+#pragma unroll
+    for (int i = 0; i < IPW; ++i) lds_dma16(g, off[i], lds0 + (unsigned)i * 1024u);
   }
 
   // MFMA 32x32x16 operand whose 32-index is the tile ROW and whose contraction index runs

@@ -132,3 +132,23 @@ def make_inputs(wl: Workload, seed: int = 0, with_gate_f: bool = True):
     if wl.planted:
         return planted_inputs(wl, seed, with_gate_f=with_gate_f)
     return iid_inputs(wl, seed, with_gate_f=with_gate_f)
+
+
+def device_iid_inputs(wl: Workload, seed: int = 0, with_gate_f: bool = True, tiled_rows: int = None):
+    """Same recipe as iid_inputs, drawn on the GPU with torch's seeded generator (for the large
+    workloads, where drawing ~10^9 normals on the host would dominate a test).  Returns bf16
+    tensors [B,H,rows,d] on the current device; rows = L (raster) unless `tiled_rows` is given
+    (then the draw is directly in the padded tiled layout; pad rows hold ordinary draws, which
+    the library must ignore)."""
+    import torch
+    g = torch.Generator(device="cuda")
+    g.manual_seed(BASE_SEED + 5000 + seed)
+    rows = wl.L if tiled_rows is None else tiled_rows
+    shape = (wl.B, wl.H, rows, wl.d)
+    out = {}
+    for name in ("q", "k", "v", "dout"):
+        out[name] = torch.randn(shape, generator=g, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    out["gate_c"] = torch.rand(shape, generator=g, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    out["gate_f"] = (torch.rand(shape, generator=g, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+                     if with_gate_f else None)
+    return out

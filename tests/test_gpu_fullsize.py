@@ -1,0 +1,162 @@
+"""GPU parity at the full benchmark sizes, in the launch configuration bench.py times.
+
+The oracle cannot run these sizes whole in seconds, so it is run on sampled (batch, head)
+slices (every (b,h) is independent through the whole path) and, for the largest workload, on
+sampled query cubes of a slice; properties that hold at any size cover the rest.
+"""
+import numpy as np
+import pytest
+
+from oracle import vsa_oracle as orc
+from paper_2505_13389_amd import synth
+from paper_2505_13389_amd.synth import WORKLOADS, Workload
+
+from helpers import GAP, assert_close, bf16_to_np, check_index_sets, grid_of, problem_of
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def vsa():
+    import torch
+    assert torch.cuda.is_available()
+    from paper_2505_13389_amd import vsa as m
+    m.lib()
+    return m
+
+
+def head_to_oracle(dev, b, h):
+    """One (b,h) slice of the device tensors as float32 numpy arrays [1,1,Np,d]."""
+    out = {}
+    for n, t in dev.items():
+        out[n] = None if t is None else bf16_to_np(t[b:b + 1, h:h + 1].contiguous())
+    return out
+
+
+def run(vsa, wl, dev, backward):
+    import torch
+    buf = vsa.Buffers(problem_of(wl), backward=backward)
+    a = (dev["q"], dev["k"], dev["v"], dev["gate_c"], dev["gate_f"])
+    buf.forward(*a)
+    if backward:
+        buf.backward(*a, dev["dout"])
+    torch.cuda.synchronize()
+    return buf
+
+
+def check_head(vsa, wl, dev, buf, b, h, backward, cubes=None):
+    one = Workload("slice", 1, 1, wl.T, wl.Hh, wl.W, wl.d, wl.topk, wl.cube)
+    g = grid_of(one)
+    x = head_to_oracle(dev, b, h)
+    ref = orc.forward(g, x["q"], x["k"], x["v"], x["gate_c"], x["gate_f"], wl.topk, real="f32", want_sc=True,
+                      cubes=cubes)
+    sl = (slice(b, b + 1), slice(h, h + 1))
+    gi = buf.block_idx[sl].cpu().numpy()
+    rows = np.arange(g.Nc) if cubes is None else np.asarray(cubes)
+    differ = check_index_sets(gi[:, :, rows], ref["block_idx"][:, :, rows], ref["sc"][:, :, rows])
+    assert len(differ) <= max(2, len(rows) // 20), f"{len(differ)} of {len(rows)} rows differ"
+    assert_close(buf.out_coarse[sl].cpu().numpy()[:, :, rows], ref["out_coarse"][:, :, rows], "out_coarse", 1e-4, 1e-4)
+    # values: the oracle on the GPU's own selection would need GPU data as oracle input, which
+    # is not allowed; instead compare the rows whose selection is identical (almost all).
+    same_c = np.zeros(g.Nc, bool)
+    same_c[rows] = (gi[0, 0, rows] == ref["block_idx"][0, 0, rows]).all(-1)
+    same = np.repeat(same_c, 64)
+    assert same_c[rows].mean() > 0.9
+    assert_close(bf16_to_np(buf.out[sl])[0, 0, same], ref["out"][0, 0, same], "out")
+    assert np.abs(buf.lse_fine[sl].cpu().numpy()[0, 0, same] - ref["lse_fine"][0, 0, same]).max() < 2e-3
+    if backward:
+        # backward parity needs identical selections everywhere in the slice (dK/dV sum over all
+        # query cubes): re-run this slice on the oracle's selection through the same entry points
+        import torch
+        pb1 = problem_of(one)
+        b1 = vsa.Buffers(pb1)
+        d1 = {n: (None if t is None else t[b:b + 1, h:h + 1].contiguous()) for n, t in dev.items()}
+        b1.block_idx.copy_(torch.from_numpy(ref["block_idx"]))
+        a = (d1["q"], d1["k"], d1["v"], d1["gate_c"], d1["gate_f"])
+        b1.forward(*a, indices_given=True)
+        b1.backward(*a, d1["dout"])
+        torch.cuda.synchronize()
+        gref = orc.backward(g, x["q"], x["k"], x["v"], x["gate_c"], x["gate_f"], x["dout"], ref["block_idx"], wl.topk,
+                            real="f32")
+        for n in ("dq", "dk", "dv", "dgate_c", "dgate_f"):
+            assert_close(bf16_to_np(getattr(b1, n)), gref[n], n)
+        # and the full-size launch must agree with the single-slice launch wherever the
+        # selections coincide: dQ and the gate gradients are row-local
+        for n in ("dq", "dgate_c", "dgate_f"):
+            full = bf16_to_np(getattr(buf, n)[sl])[0, 0, same]
+            assert_close(full, gref[n][0, 0, same], n + " (full launch)")
+
+
+def invariants(buf, dev, wl, backward):
+    """Properties that hold at any size, checked on the whole output."""
+    import torch
+    Np, Nc = buf.Np, buf.Nc
+    idx = buf.block_idx
+    assert int(idx.min()) >= 0 and int(idx.max()) < Nc
+    assert bool((idx[..., 1:] > idx[..., :-1]).all()), "index lists must be strictly ascending"
+    assert bool(torch.isfinite(buf.out.float()).all())
+    valid, _ = orc.valid_mask(grid_of(wl))
+    pad = torch.from_numpy(~valid).cuda()
+    assert not bool(buf.out[:, :, pad].any())
+    # constant-V identity: O_f is a convex combination of V rows -> |O_f| <= max |V| per (b,h,dim)
+    vmax = dev["v"].float().abs().amax(dim=2, keepdim=True)
+    assert bool((buf.out_fine.float().abs() <= vmax * 1.01 + 1e-3).all())
+    if backward:
+        for n in ("dq", "dk", "dv", "dgate_c", "dgate_f"):
+            t = getattr(buf, n)
+            assert bool(torch.isfinite(t.float()).all()), n
+            assert not bool(t[:, :, pad].any()), n
+        # sum_j dV_j = sum_i dOf_i + (pooled path) is checked per slice by the oracle comparison;
+        # here: dGf = dO * Of exactly (one rounding)
+        ref = (dev["dout"].float() * buf.out_fine.float()).to(torch.bfloat16)
+        ref[:, :, pad] = 0
+        assert torch.equal(ref, buf.dgate_f)
+
+
+def test_mid_forward_backward(vsa):
+    wl = WORKLOADS["mid"]
+    dev = {n: t for n, t in synth.device_iid_inputs(wl, seed=1, tiled_rows=wl.Np).items()}
+    buf = run(vsa, wl, dev, backward=True)
+    invariants(buf, dev, wl, True)
+    for (b, h) in [(0, 0), (0, 7)]:
+        check_head(vsa, wl, dev, buf, b, h, backward=True)
+
+
+def test_wan13b_forward_backward(vsa):
+    wl = WORKLOADS["wan1.3b"]
+    dev = synth.device_iid_inputs(wl, seed=2, tiled_rows=wl.Np)
+    buf = run(vsa, wl, dev, backward=True)
+    invariants(buf, dev, wl, True)
+    check_head(vsa, wl, dev, buf, 0, 5, backward=True)
+
+
+def test_wan14b_forward_sampled_cubes(vsa):
+    wl = WORKLOADS["wan14b"]
+    dev = synth.device_iid_inputs(wl, seed=3, tiled_rows=wl.Np)
+    buf = run(vsa, wl, dev, backward=False)
+    invariants(buf, dev, wl, False)
+    rng = np.random.default_rng(5)
+    for h in (3, 38):
+        cubes = np.sort(rng.choice(wl.Nc, 24, replace=False)).astype(np.int32)
+        check_head(vsa, wl, dev, buf, 0, h, backward=False, cubes=cubes)
+
+
+def test_wan14b_dense_path_equals_dense_attention_on_sampled_rows(vsa):
+    """top-K = all 1440 cubes on the Wan-14B shape: sampled query rows against brute-force attention."""
+    import torch
+    base = WORKLOADS["wan14b"]
+    wl = Workload("wan14b_dense", 1, 4, base.T, base.Hh, base.W, base.d, base.Nc)  # 4 of the 40 heads: same kernels, grid scaled
+    dev = synth.device_iid_inputs(wl, seed=4, tiled_rows=wl.Np, with_gate_f=False)
+    dev["gate_c"].zero_()
+    buf = run(vsa, wl, dev, backward=False)
+    valid, _ = orc.valid_mask(grid_of(wl))
+    vrows = np.flatnonzero(valid)
+    rows = np.random.default_rng(6).choice(vrows, 16, replace=False)
+    q = bf16_to_np(dev["q"][0, 1, torch.from_numpy(rows).cuda()]).astype(np.float64)
+    k = bf16_to_np(dev["k"][0, 1]).astype(np.float64)[valid]
+    v = bf16_to_np(dev["v"][0, 1]).astype(np.float64)[valid]
+    s = q @ k.T / np.sqrt(wl.d)
+    p = np.exp(s - s.max(-1, keepdims=True)); p /= p.sum(-1, keepdims=True)
+    ref = p @ v
+    got = bf16_to_np(buf.out[0, 1, torch.from_numpy(rows).cuda()])
+    assert_close(got, ref, "dense path rows")
