@@ -9,16 +9,16 @@ namespace vsa {
 // Preprocess.  Per token i of cube c (pad rows produce zeros):
 //   dGc_i = dO_i * Oc[c]      dGf_i = dO_i * Of_i      dOf_i = dO_i * Gf_i  (bf16, feeds the MFMAs)
 //   Delta_i = sum_d dOf_i * Of_i                       dOc[c] = sum_i dO_i * Gc_i
-//   lse2_i = lse_i * log2(e), +inf on pad rows (makes P = 0 there in the fine backward kernels)
+//   ld_i = (lse_i * log2(e), Delta_i) as one pair per row, lse = +inf on pad rows (makes P = 0
+//          there in the fine backward kernels)
 // One workgroup per (b*h, cube); thread layout as in the pooling kernel.
 template <int D>
 __global__ __launch_bounds__(256) void k_bwd_pre(int Nc, const uint64_t* __restrict__ mask, const uint4* __restrict__ dout,
                                                  const uint4* __restrict__ gc, const uint4* __restrict__ gf,
                                                  const uint4* __restrict__ of, const float* __restrict__ oc,
                                                  uint4* __restrict__ dgc, uint4* __restrict__ dgf,
-                                                 uint4* __restrict__ dof, float* __restrict__ delta,
-                                                 float* __restrict__ doc, const float* __restrict__ lse_f,
-                                                 float* __restrict__ lse2) {
+                                                 uint4* __restrict__ dof, float* __restrict__ ld,
+                                                 float* __restrict__ doc, const float* __restrict__ lse_f) {
   constexpr int CPR = D / 8, RG = 256 / CPR, RPT = kTile / RG;
   __shared__ float part[RG][D + 4];
   const int c = blockIdx.x % Nc;
@@ -68,10 +68,7 @@ __global__ __launch_bounds__(256) void k_bwd_pre(int Nc, const uint64_t* __restr
     dof[g] = o_dof;
 #pragma unroll
     for (int o = CPR / 2; o > 0; o >>= 1) dsum += __shfl_xor(dsum, o);
-    if (ch == 0) {
-      delta[row0 + r] = dsum;
-      lse2[row0 + r] = valid ? lse_f[row0 + r] * kLog2e : INFINITY;
-    }
+    if (ch == 0) *(float2*)&ld[2 * (row0 + r)] = make_float2(valid ? lse_f[row0 + r] * kLog2e : INFINITY, dsum);
   }
 #pragma unroll
   for (int e = 0; e < 8; ++e) part[rg][ch * 8 + e] = acc[e];
@@ -85,16 +82,16 @@ __global__ __launch_bounds__(256) void k_bwd_pre(int Nc, const uint64_t* __restr
 
 hipError_t launch_bwd_pre(int BH, int Nc, int d, const uint64_t* mask, const void* dout, const void* gate_c,
                           const void* gate_f, const void* out_fine, const float* oc, void* dgate_c, void* dgate_f,
-                          void* dof, float* delta, float* doc, const float* lse_f, float* lse2, hipStream_t s) {
+                          void* dof, float* ld, float* doc, const float* lse_f, hipStream_t s) {
   const unsigned grid = (unsigned)(BH * Nc);
   if (d == 128)
     k_bwd_pre<128><<<grid, 256, 0, s>>>(Nc, mask, (const uint4*)dout, (const uint4*)gate_c, (const uint4*)gate_f,
-                                        (const uint4*)out_fine, oc, (uint4*)dgate_c, (uint4*)dgate_f, (uint4*)dof, delta,
-                                        doc, lse_f, lse2);
+                                        (const uint4*)out_fine, oc, (uint4*)dgate_c, (uint4*)dgate_f, (uint4*)dof, ld,
+                                        doc, lse_f);
   else
     k_bwd_pre<64><<<grid, 256, 0, s>>>(Nc, mask, (const uint4*)dout, (const uint4*)gate_c, (const uint4*)gate_f,
-                                       (const uint4*)out_fine, oc, (uint4*)dgate_c, (uint4*)dgate_f, (uint4*)dof, delta,
-                                       doc, lse_f, lse2);
+                                       (const uint4*)out_fine, oc, (uint4*)dgate_c, (uint4*)dgate_f, (uint4*)dof, ld,
+                                       doc, lse_f);
   return hipGetLastError();
 }
 

@@ -9,6 +9,8 @@
 // products are computed transposed, the streamed tiles sit in a double-buffered LDS stage, the
 // resident tile sits in registers, and each wavefront pair owning the same output rows is
 // merged once at the end.
+#include <type_traits>
+
 #include "fine_tile.h"
 #include "vsa_kernels.h"
 
@@ -21,7 +23,7 @@ template <int D>
 __global__ __launch_bounds__(256, 2) void k_fine_bwd_dq(int Nc, int K, float sl2, float scale, const uint4* __restrict__ q,
                                                         const uint4* __restrict__ k, const uint4* __restrict__ v,
                                                         const uint4* __restrict__ dof, const int32_t* __restrict__ idx,
-                                                        const float* __restrict__ lse2_f, const float* __restrict__ delta,
+                                                        const float* __restrict__ ld,
                                                         const float* __restrict__ dqc, const uint64_t* __restrict__ mask,
                                                         uint4* __restrict__ dq) {
   using TL = Tile<D>;
@@ -52,8 +54,8 @@ __global__ __launch_bounds__(256, 2) void k_fine_bwd_dq(int Nc, int K, float sl2
     }
   }
   // lse2 = lse*log2(e), +inf on pad query rows (then P = 0 and the row contributes nothing)
-  float lse2 = lse2_f[qrow_g];
-  float dl = delta[qrow_g];
+  float lse2 = ld[2 * qrow_g];
+  float dl = ld[2 * qrow_g + 1];
   // Everything loaded the ordinary way must have arrived before the first hand-ordered copy is
   // issued (the compiler cannot see those copies; see Tile::async_load).
 #pragma unroll
@@ -149,16 +151,16 @@ __global__ __launch_bounds__(256, 2) void k_fine_bwd_dq(int Nc, int K, float sl2
 }
 
 hipError_t launch_fine_bwd_dq(int BH, int Nc, int d, int K, float scale, const void* q, const void* k, const void* v,
-                              const void* dof, const int32_t* idx, const float* lse_f, const float* delta,
+                              const void* dof, const int32_t* idx, const float* ld,
                               const float* dqc, const uint64_t* mask, void* dq, hipStream_t s) {
   const float sl2 = scale * kLog2e;
   const unsigned grid = (unsigned)(BH * Nc);
   if (d == 128)
     k_fine_bwd_dq<128><<<grid, 256, 0, s>>>(Nc, K, sl2, scale, (const uint4*)q, (const uint4*)k, (const uint4*)v,
-                                            (const uint4*)dof, idx, lse_f, delta, dqc, mask, (uint4*)dq);
+                                            (const uint4*)dof, idx, ld, dqc, mask, (uint4*)dq);
   else
     k_fine_bwd_dq<64><<<grid, 256, 0, s>>>(Nc, K, sl2, scale, (const uint4*)q, (const uint4*)k, (const uint4*)v,
-                                           (const uint4*)dof, idx, lse_f, delta, dqc, mask, (uint4*)dq);
+                                           (const uint4*)dof, idx, ld, dqc, mask, (uint4*)dq);
   return hipGetLastError();
 }
 
@@ -166,26 +168,34 @@ hipError_t launch_fine_bwd_dq(int BH, int Nc, int d, int K, float scale, const v
 // dK/dV pass: one workgroup per (b, h, key cube); streams the (Q tile, dOf tile) pairs of the
 // query cubes that selected this key cube.  Wavefront (kh, qh): key rows kh*32..+31 (its output
 // rows; K and V of those rows stay in registers), query rows qh*32..+31 of each streamed tile.
-// Here S (not S^T) is formed, so a lane holds one key column and 16 query rows; lse and Delta
-// of the streamed query tile are staged in LDS next to the tiles.  `lse2_f` is lse*log2(e) with
-// +inf on pad query rows (written by the preprocess kernel), so pad queries give P = 0.
+// Here S (not S^T) is formed, so a lane holds one key column and 16 query rows; the per-row pair
+// (lse*log2 e, Delta) of the streamed query tile -- `ld`, written by the preprocess kernel with
+// lse = +inf on pad rows so that pad queries give P = 0 -- is staged in LDS next to the tiles.
+//
+// One workgroup per CU (the whole register file for 4 wavefronts), four LDS stages, and the
+// loop is software-pipelined inside each wavefront: iteration t forms S and dP of tile t+1
+// (MFMA) while the exponentials of tile t run (VALU), then feeds P and dS of tile t to the
+// dV / dK MFMAs.  Copies run three tiles ahead.  Per iteration: wait for this wave's share of
+// tile t+1, one barrier (tile t+1 complete; every wave done with tile t-1), refill the stage of
+// tile t-1 with tile t+3.  Past the end of the list the last tile is fetched again, so the
+// number of copies in flight is the same in every iteration.
 template <int D>
 __global__ __launch_bounds__(256, 1) void k_fine_bwd_dkv(int Nc, int K, float sl2, float scale, const uint4* __restrict__ q,
                                                          const uint4* __restrict__ k, const uint4* __restrict__ v,
                                                          const uint4* __restrict__ dof,
                                                          const int32_t* __restrict__ row_ptr,
                                                          const int32_t* __restrict__ col,
-                                                         const float* __restrict__ lse2_f, const float* __restrict__ delta,
+                                                         const float* __restrict__ ld,
                                                          const float* __restrict__ dkc, const float* __restrict__ dvc,
                                                          const uint64_t* __restrict__ mask, uint4* __restrict__ dk,
                                                          uint4* __restrict__ dv) {
   using TL = Tile<D>;
   constexpr int CPR = TL::CPR, KS = D / 16, DVB = D / 32, LPT = TL::LPT;
   constexpr int OS = D;
-  constexpr int STAGE = 2 * TL::BYTES + 2 * kTile * 4;  // Q tile, dOf tile, lse2[64], delta[64]
-  __shared__ __attribute__((aligned(16))) unsigned char stage0[STAGE];
-  __shared__ __attribute__((aligned(16))) unsigned char stage1[STAGE];
-  static_assert(2 * 32 * OS * 4 <= STAGE, "merge buffer must fit in one stage");
+  constexpr int STAGE = 2 * TL::BYTES + 2 * kTile * 4;  // Q tile, dOf tile, (lse2, delta)[64]
+  constexpr int NLP = 2 * TL::IPW + 1;                  // copies per wave and stage
+  __shared__ __attribute__((aligned(16))) unsigned char smem[4 * STAGE];
+  static_assert(2 * 64 * OS * 4 <= 4 * STAGE, "merge buffers must fit");
 
   const int j = blockIdx.x % Nc;
   const long long bh = blockIdx.x / Nc;
@@ -196,18 +206,6 @@ __global__ __launch_bounds__(256, 1) void k_fine_bwd_dkv(int Nc, int K, float sl
   const int32_t* rp = row_ptr + bh * (Nc + 1);
   const int beg = rp[j], end = rp[j + 1];
   const int32_t* my_col = col + bh * (long long)Nc * K;
-
-  // asynchronous fill of one stage: the two tiles by all waves, lse2 by wave 0, delta by wave 1
-  unsigned goff[TL::IPW];
-  TL::lane_offsets(wave, lane, goff);
-  auto fill = [&](unsigned char* st, int cq) {
-    const long long r0 = rows0 + (long long)cq * kTile;
-    TL::async_load(q, r0, st, wave, goff);
-    TL::async_load(dof, r0, st + TL::BYTES, wave, goff);
-    if (wave == 0) lds_dma4(lse2_f + r0, lane * 4u, __builtin_amdgcn_readfirstlane(lds_address(st) + 2 * TL::BYTES));
-    if (wave == 1)
-      lds_dma4(delta + r0, lane * 4u, __builtin_amdgcn_readfirstlane(lds_address(st) + 2 * TL::BYTES + kTile * 4));
-  };
 
   bf16x8 kreg[KS], vreg[KS];
   {
@@ -223,7 +221,6 @@ __global__ __launch_bounds__(256, 1) void k_fine_bwd_dkv(int Nc, int K, float sl
   // ordinary loads done before the first hand-ordered copy (see Tile::async_load)
 #pragma unroll
   for (int s = 0; s < KS; ++s) asm volatile("" : "+v"(kreg[s]), "+v"(vreg[s]));
-  if (beg < end) fill(stage0, my_col[beg]);
 
   f32x16 dka[DVB], dva[DVB];
 #pragma unroll
@@ -231,59 +228,100 @@ __global__ __launch_bounds__(256, 1) void k_fine_bwd_dkv(int Nc, int K, float sl
 #pragma unroll
     for (int i = 0; i < 16; ++i) { dka[x][i] = 0.f; dva[x][i] = 0.f; }
 
-  auto body = [&](const unsigned char* cur, unsigned char* nxt, int t) {
-    wait_vmcnt<0>();
+  if (beg < end) {
+    unsigned goff[TL::IPW];
+    TL::lane_offsets(wave, lane, goff);
+    const unsigned lds0 = lds_address(smem);
+    // fill stage `st` with the tiles of list entry min(t, end-1); every wave issues NLP copies
+    auto fill = [&](int st, int t) {
+      const int cq = my_col[min(t, end - 1)];
+      const long long r0 = rows0 + (long long)cq * kTile;
+      unsigned char* sp = smem + st * STAGE;
+      TL::async_load(q, r0, sp, wave, goff);
+      TL::async_load(dof, r0, sp + TL::BYTES, wave, goff);
+      if (lane < 8)  // 16 rows x (lse2, delta) = 128 bytes per wave
+        lds_dma16(ld + 2 * r0, (unsigned)(wave * 128 + lane * 16),
+                  __builtin_amdgcn_readfirstlane(lds0 + st * STAGE + 2 * TL::BYTES + wave * 128));
+    };
+    auto s_dp = [&](int st, f32x16& sacc, f32x16& dpacc) {  // S and dP of the tile in stage st
+      const unsigned char* Qs = smem + st * STAGE;
+      const unsigned char* Ds = Qs + TL::BYTES;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) { sacc[i] = 0.f; dpacc[i] = 0.f; }
+#pragma unroll
+      for (int s = 0; s < KS; ++s) sacc = mfma32(TL::rowmajor_operand(Qs, qh * 32, s, lane), kreg[s], sacc);
+#pragma unroll
+      for (int s = 0; s < KS; ++s) dpacc = mfma32(TL::rowmajor_operand(Ds, qh * 32, s, lane), vreg[s], dpacc);
+    };
+
+    fill(0, beg);
+    fill(1, beg + 1);
+    fill(2, beg + 2);
+    wait_vmcnt<2 * NLP>();
     __builtin_amdgcn_s_barrier();
-    if (t + 1 < end) fill(nxt, my_col[t + 1]);
-    __builtin_amdgcn_sched_barrier(0);
-    const unsigned char* Qs = cur;
-    const unsigned char* Ds = cur + TL::BYTES;
-    const float* ls = (const float*)(cur + 2 * TL::BYTES);
-
     f32x16 sacc, dpacc;
-#pragma unroll
-    for (int i = 0; i < 16; ++i) { sacc[i] = 0.f; dpacc[i] = 0.f; }
-#pragma unroll
-    for (int s = 0; s < KS; ++s) sacc = mfma32(TL::rowmajor_operand(Qs, qh * 32, s, lane), kreg[s], sacc);
-#pragma unroll
-    for (int s = 0; s < KS; ++s) dpacc = mfma32(TL::rowmajor_operand(Ds, qh * 32, s, lane), vreg[s], dpacc);
+    s_dp(0, sacc, dpacc);
 
-    float p[16], ds[16];
+    // ST = stage of tile t (tile t+1 sits in ST+1, tile t+3 goes where tile t-1 was)
+    auto body = [&](auto st_tag, int t) {
+      constexpr int ST = decltype(st_tag)::value;
+      wait_vmcnt<NLP>();
+      __builtin_amdgcn_s_barrier();
+      fill((ST + 3) & 3, t + 3);
+      __builtin_amdgcn_sched_barrier(0);
+      const unsigned char* Qs = smem + ST * STAGE;
+      const unsigned char* Ds = Qs + TL::BYTES;
+      const float* ls = (const float*)(Qs + 2 * TL::BYTES);
+
+      // tile t+1: S, dP (independent of the arithmetic below, the scheduler interleaves them)
+      f32x16 sn, dpn;
+      s_dp((ST + 1) & 3, sn, dpn);
+
+      // tile t: P = exp2(S*sl2 - lse2), dS = P * (dP - Delta)
+      float p[16], ds[16];
 #pragma unroll
-    for (int g4 = 0; g4 < 4; ++g4) {
-      const float4 l4 = *(const float4*)&ls[qh * 32 + 8 * g4 + 4 * h];
-      const float4 d4 = *(const float4*)&ls[kTile + qh * 32 + 8 * g4 + 4 * h];
-      const float lv[4] = {l4.x, l4.y, l4.z, l4.w}, dvv[4] = {d4.x, d4.y, d4.z, d4.w};
+      for (int g4 = 0; g4 < 4; ++g4) {
+        const float4 a = *(const float4*)&ls[2 * (qh * 32 + 8 * g4 + 4 * h)];
+        const float4 b = *(const float4*)&ls[2 * (qh * 32 + 8 * g4 + 4 * h) + 4];
+        const float lv[4] = {a.x, a.z, b.x, b.z}, dvv[4] = {a.y, a.w, b.y, b.w};
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const int i = 4 * g4 + e;
-        float pi = fast_exp2(fmaf(sacc[i], sl2, -lv[e]));
-        if (!kvalid) pi = 0.f;
-        p[i] = pi;
-        ds[i] = pi * (dpacc[i] - dvv[e]);
+        for (int e = 0; e < 4; ++e) {
+          const int i = 4 * g4 + e;
+          float pi = fast_exp2(fmaf(sacc[i], sl2, -lv[e]));
+          if (!kvalid) pi = 0.f;
+          p[i] = pi;
+          ds[i] = pi * (dpacc[i] - dvv[e]);
+        }
       }
-    }
-    const bf16x8 pb0 = acc_to_operand(p), pb1 = acc_to_operand(p + 8);
-    const bf16x8 sb0 = acc_to_operand(ds), sb1 = acc_to_operand(ds + 8);
+      const bf16x8 pb0 = acc_to_operand(p), pb1 = acc_to_operand(p + 8);
+      const bf16x8 sb0 = acc_to_operand(ds), sb1 = acc_to_operand(ds + 8);
 #pragma unroll
-    for (int x = 0; x < DVB; ++x) {
-      dva[x] = mfma32(TL::transposed_operand(Ds, qh * 32, 0, x * 32, lane), pb0, dva[x]);
-      dva[x] = mfma32(TL::transposed_operand(Ds, qh * 32, 1, x * 32, lane), pb1, dva[x]);
-      dka[x] = mfma32(TL::transposed_operand(Qs, qh * 32, 0, x * 32, lane), sb0, dka[x]);
-      dka[x] = mfma32(TL::transposed_operand(Qs, qh * 32, 1, x * 32, lane), sb1, dka[x]);
-    }
-  };
+      for (int x = 0; x < DVB; ++x) {
+        dva[x] = mfma32(TL::transposed_operand(Ds, qh * 32, 0, x * 32, lane), pb0, dva[x]);
+        dva[x] = mfma32(TL::transposed_operand(Ds, qh * 32, 1, x * 32, lane), pb1, dva[x]);
+        dka[x] = mfma32(TL::transposed_operand(Qs, qh * 32, 0, x * 32, lane), sb0, dka[x]);
+        dka[x] = mfma32(TL::transposed_operand(Qs, qh * 32, 1, x * 32, lane), sb1, dka[x]);
+      }
+      sacc = sn;
+      dpacc = dpn;
+    };
 
-  for (int t = beg; t < end; t += 2) {
-    body(stage0, stage1, t);
-    if (t + 1 < end) body(stage1, stage0, t + 1);
+    for (int t = beg; t < end; t += 4) {
+      body(std::integral_constant<int, 0>{}, t);
+      if (t + 1 < end) body(std::integral_constant<int, 1>{}, t + 1);
+      if (t + 2 < end) body(std::integral_constant<int, 2>{}, t + 2);
+      if (t + 3 < end) body(std::integral_constant<int, 3>{}, t + 3);
+    }
+    wait_vmcnt<0>();  // the refetches issued past the end of the list
   }
   __syncthreads();
 
   // merge the two query halves; dK first, then dV through the same buffers
   const float inv_cnt = 1.0f / (float)__popcll(kmask);
+  float* part0 = (float*)smem;
+  float* part1 = (float*)smem + 64 * OS;
   for (int pass = 0; pass < 2; ++pass) {
-    float* Op = (float*)(qh == 0 ? stage0 : stage1) + kh * 32 * OS;
+    float* Op = (qh == 0 ? part0 : part1) + kh * 32 * OS;
 #pragma unroll
     for (int x = 0; x < DVB; ++x)
 #pragma unroll
@@ -299,8 +337,8 @@ __global__ __launch_bounds__(256, 1) void k_fine_bwd_dkv(int Nc, int K, float sl
 #pragma unroll
     for (int it = 0; it < LPT; ++it) {
       const int item = it * 256 + tid, r = item / CPR, ch = item % CPR;
-      const float* Oa = (const float*)stage0 + r * OS + ch * 8;
-      const float* Ob = (const float*)stage1 + r * OS + ch * 8;
+      const float* Oa = part0 + r * OS + ch * 8;
+      const float* Ob = part1 + r * OS + ch * 8;
       uint4 ov = make_uint4(0, 0, 0, 0);
       if ((kmask >> r) & 1) {
         float res[8];
@@ -315,18 +353,18 @@ __global__ __launch_bounds__(256, 1) void k_fine_bwd_dkv(int Nc, int K, float sl
 }
 
 hipError_t launch_fine_bwd_dkv(int BH, int Nc, int d, int K, float scale, const void* q, const void* k, const void* v,
-                               const void* dof, const int32_t* row_ptr, const int32_t* col, const float* lse_f,
-                               const float* delta, const float* dkc, const float* dvc, const uint64_t* mask, void* dk,
+                               const void* dof, const int32_t* row_ptr, const int32_t* col, const float* ld,
+                               const float* dkc, const float* dvc, const uint64_t* mask, void* dk,
                                void* dv, hipStream_t s) {
   const float sl2 = scale * kLog2e;
   const unsigned grid = (unsigned)(BH * Nc);
   if (d == 128)
     k_fine_bwd_dkv<128><<<grid, 256, 0, s>>>(Nc, K, sl2, scale, (const uint4*)q, (const uint4*)k, (const uint4*)v,
-                                             (const uint4*)dof, row_ptr, col, lse_f, delta, dkc, dvc, mask, (uint4*)dk,
+                                             (const uint4*)dof, row_ptr, col, ld, dkc, dvc, mask, (uint4*)dk,
                                              (uint4*)dv);
   else
     k_fine_bwd_dkv<64><<<grid, 256, 0, s>>>(Nc, K, sl2, scale, (const uint4*)q, (const uint4*)k, (const uint4*)v,
-                                            (const uint4*)dof, row_ptr, col, lse_f, delta, dkc, dvc, mask, (uint4*)dk,
+                                            (const uint4*)dof, row_ptr, col, ld, dkc, dvc, mask, (uint4*)dk,
                                             (uint4*)dv);
   return hipGetLastError();
 }
