@@ -234,13 +234,13 @@ __global__ __launch_bounds__(256, 1) void k_fine_bwd_dkv(int Nc, int K, float sl
     const unsigned lds0 = lds_address(smem);
     // fill stage `st` with the tiles of list entry min(t, end-1); every wave issues NLP copies
     auto fill = [&](int st, int t) {
-      const int cq = my_col[min(t, end - 1)];
+      const int cq = __builtin_amdgcn_readfirstlane(my_col[min(t, end - 1)]);
       const long long r0 = rows0 + (long long)cq * kTile;
       unsigned char* sp = smem + st * STAGE;
       TL::async_load(q, r0, sp, wave, goff);
       TL::async_load(dof, r0, sp + TL::BYTES, wave, goff);
       if (lane < 8)  // 16 rows x (lse2, delta) = 128 bytes per wave
-        lds_dma16(ld + 2 * r0, (unsigned)(wave * 128 + lane * 16),
+        lds_dma16(uniform_ptr(ld + 2 * r0), (unsigned)(wave * 128 + lane * 16),
                   __builtin_amdgcn_readfirstlane(lds0 + st * STAGE + 2 * TL::BYTES + wave * 128));
     };
     auto s_dp = [&](int st, f32x16& sacc, f32x16& dpacc) {  // S and dP of the tile in stage st
@@ -272,17 +272,48 @@ __global__ __launch_bounds__(256, 1) void k_fine_bwd_dkv(int Nc, int K, float sl
       const unsigned char* Qs = smem + ST * STAGE;
       const unsigned char* Ds = Qs + TL::BYTES;
       const float* ls = (const float*)(Qs + 2 * TL::BYTES);
+      const unsigned char* Qn = smem + ((ST + 1) & 3) * STAGE;
+      const unsigned char* Dn = Qn + TL::BYTES;
+
+      // With one wavefront per SIMD nothing hides an LDS round trip, so every operand of the
+      // iteration is requested up front, in the order it is consumed.
+      bf16x8 qa[KS], da[KS], dt[DVB][2], qt[DVB][2];
+      float4 la[4], lb[4];
+#pragma unroll
+      for (int s = 0; s < KS; ++s) qa[s] = TL::rowmajor_operand(Qn, qh * 32, s, lane);
+#pragma unroll
+      for (int s = 0; s < KS; ++s) da[s] = TL::rowmajor_operand(Dn, qh * 32, s, lane);
+#pragma unroll
+      for (int g4 = 0; g4 < 4; ++g4) {
+        la[g4] = *(const float4*)&ls[2 * (qh * 32 + 8 * g4 + 4 * h)];
+        lb[g4] = *(const float4*)&ls[2 * (qh * 32 + 8 * g4 + 4 * h) + 4];
+      }
+#pragma unroll
+      for (int x = 0; x < DVB; ++x) {
+        dt[x][0] = TL::transposed_operand(Ds, qh * 32, 0, x * 32, lane);
+        dt[x][1] = TL::transposed_operand(Ds, qh * 32, 1, x * 32, lane);
+      }
+#pragma unroll
+      for (int x = 0; x < DVB; ++x) {
+        qt[x][0] = TL::transposed_operand(Qs, qh * 32, 0, x * 32, lane);
+        qt[x][1] = TL::transposed_operand(Qs, qh * 32, 1, x * 32, lane);
+      }
+      __builtin_amdgcn_sched_barrier(0);
 
       // tile t+1: S, dP (independent of the arithmetic below, the scheduler interleaves them)
       f32x16 sn, dpn;
-      s_dp((ST + 1) & 3, sn, dpn);
+#pragma unroll
+      for (int i = 0; i < 16; ++i) { sn[i] = 0.f; dpn[i] = 0.f; }
+#pragma unroll
+      for (int s = 0; s < KS; ++s) sn = mfma32(qa[s], kreg[s], sn);
+#pragma unroll
+      for (int s = 0; s < KS; ++s) dpn = mfma32(da[s], vreg[s], dpn);
 
       // tile t: P = exp2(S*sl2 - lse2), dS = P * (dP - Delta)
       float p[16], ds[16];
 #pragma unroll
       for (int g4 = 0; g4 < 4; ++g4) {
-        const float4 a = *(const float4*)&ls[2 * (qh * 32 + 8 * g4 + 4 * h)];
-        const float4 b = *(const float4*)&ls[2 * (qh * 32 + 8 * g4 + 4 * h) + 4];
+        const float4 a = la[g4], b = lb[g4];
         const float lv[4] = {a.x, a.z, b.x, b.z}, dvv[4] = {a.y, a.w, b.y, b.w};
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
@@ -297,10 +328,10 @@ __global__ __launch_bounds__(256, 1) void k_fine_bwd_dkv(int Nc, int K, float sl
       const bf16x8 sb0 = acc_to_operand(ds), sb1 = acc_to_operand(ds + 8);
 #pragma unroll
       for (int x = 0; x < DVB; ++x) {
-        dva[x] = mfma32(TL::transposed_operand(Ds, qh * 32, 0, x * 32, lane), pb0, dva[x]);
-        dva[x] = mfma32(TL::transposed_operand(Ds, qh * 32, 1, x * 32, lane), pb1, dva[x]);
-        dka[x] = mfma32(TL::transposed_operand(Qs, qh * 32, 0, x * 32, lane), sb0, dka[x]);
-        dka[x] = mfma32(TL::transposed_operand(Qs, qh * 32, 1, x * 32, lane), sb1, dka[x]);
+        dva[x] = mfma32(dt[x][0], pb0, dva[x]);
+        dva[x] = mfma32(dt[x][1], pb1, dva[x]);
+        dka[x] = mfma32(qt[x][0], sb0, dka[x]);
+        dka[x] = mfma32(qt[x][1], sb1, dka[x]);
       }
       sacc = sn;
       dpacc = dpn;

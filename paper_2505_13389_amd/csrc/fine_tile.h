@@ -39,6 +39,13 @@ __device__ __forceinline__ void lds_dma4(const void* base, unsigned voff, unsign
 #pragma clang diagnostic pop
 
 // s_waitcnt immediates (gfx9 encoding: vmcnt in bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8).
+// A pointer the caller knows to be wave-uniform, forced into scalar registers.
+__device__ __forceinline__ const void* uniform_ptr(const void* p) {
+  const unsigned long long a = (unsigned long long)p;
+  const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)a), hi = __builtin_amdgcn_readfirstlane((unsigned)(a >> 32));
+  return (const void*)(((unsigned long long)hi << 32) | lo);
+}
+
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {
   __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
@@ -86,20 +93,25 @@ struct Tile {
   // vmcnt in issue order, every wave waits for its own share (s_waitcnt) and a workgroup barrier
   // then makes the whole tile visible.
   static constexpr int RPI = 1024 / ROW_BYTES;   // rows per wave instruction
-  static constexpr int IPW = kTile / RPI / 4;    // instructions per wave and tile
-  __device__ static __forceinline__ void lane_offsets(int wave, int lane, unsigned* off) {
+  static constexpr int IPW = kTile / RPI / 4;    // instructions per wave and tile, 4 waves copying
+  // NW wavefronts share the copy of one tile; `part` in [0, NW) is this wave's share.
+  template <int NW = 4>
+  __device__ static __forceinline__ void lane_offsets(int part, int lane, unsigned* off) {
+    constexpr int N = kTile / RPI / NW;
 #pragma unroll
-    for (int i = 0; i < IPW; ++i) {
-      const int r = (wave * IPW + i) * RPI + lane / CPR, pc = lane % CPR;
+    for (int i = 0; i < N; ++i) {
+      const int r = (part * N + i) * RPI + lane / CPR, pc = lane % CPR;
       off[i] = (unsigned)((r * CPR + (pc ^ swz(r))) * 16);
     }
   }
+  template <int NW = 4>
   __device__ static __forceinline__ void async_load(const uint4* __restrict__ src, long long row0, unsigned char* tile,
-                                                    int wave, const unsigned* off) {
-    const uint4* g = src + row0 * CPR;  // wave-uniform
-    const unsigned lds0 = __builtin_amdgcn_readfirstlane(lds_address(tile) + (unsigned)(wave * IPW) * 1024u);
+                                                    int part, const unsigned* off) {
+    constexpr int N = kTile / RPI / NW;
+    const void* g = uniform_ptr(src + row0 * CPR);
+    const unsigned lds0 = __builtin_amdgcn_readfirstlane(lds_address(tile) + (unsigned)(part * N) * 1024u);
 #pragma unroll
-    for (int i = 0; i < IPW; ++i) lds_dma16(g, off[i], lds0 + (unsigned)i * 1024u);
+    for (int i = 0; i < N; ++i) lds_dma16(g, off[i], lds0 + (unsigned)i * 1024u);
   }
 
   // MFMA 32x32x16 operand whose 32-index is the tile ROW and whose contraction index runs
