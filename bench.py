@@ -141,8 +141,16 @@ def main():
     pairs = wl.B * wl.H * buf.Nc * wl.topk
     dom = max(MATMULS, key=lambda n: kern.get(n, 0.0))
     achieved = MATMULS[dom] * pair_flops * pairs / (kern[dom] * 1e-3) / 1e12
+    # HBM-side bytes per launch of that kernel, from committed rocprofv3 --pmc runs (FETCH_SIZE and
+    # WRITE_SIZE, each scaled by what the same counter reads for a copy kernel of known size)
+    traffic = None
+    tpath = os.path.join(ROOT, "paper_2505_13389_amd", "traffic.json")
+    if os.path.exists(tpath):
+        tj = json.load(open(tpath))
+        if tj.get("workload") == wl.name and dom in tj.get("kernels", {}):
+            traffic = tj["kernels"][dom]["total_bytes"]
     roofline = {"kernel": dom, "bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS,
-                "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": traffic,
                 "avg_launch_ms": round(kern[dom], 4)}
 
     # raster <-> tiled permutation of the 6 inputs and 6 outputs of a training step, timed apart

@@ -96,68 +96,87 @@ hipError_t launch_bwd_pre(int BH, int Nc, int d, const uint64_t* mask, const voi
 }
 
 // ---------------------------------------------------------------------------------------------
-// Batched fp32 GEMM with arbitrary strides: C[b][m][n] = alpha * sum_k A(b,m,k) * B(b,k,n),
-// A(b,m,k) = a[b*sab + m*sam + k*sak], B(b,k,n) = bm[b*sbb + k*sbk + n*sbn], C row-major.
-// 64x64 output tile per workgroup, 16-deep k slices through LDS, 4x4 outputs per thread.
+// Batched fp32 GEMM on the matrix cores (v_mfma_f32_32x32x2_f32: full fp32 products and sums),
+// arbitrary strides:  C[b][m][n] = alpha * sum_k A(b,m,k) * B(b,k,n),
+//   A(b,m,k) = a[b*sab + m*sam + k*sak],  B(b,k,n) = bm[b*sbb + k*sbk + n*sbn],  C row-major.
+// Each operand must have one unit stride (k or the other axis).  64x64 output tile per workgroup,
+// one 32x32 block per wavefront, 32-deep k slices staged in LDS as [row][k] (k contiguous) so a
+// lane fetches 4 consecutive k of its row with one 16-byte read and feeds 4 MFMAs with it; the
+// contraction index a lane half works on is k = 8j + 4h + e, the same for both operands.
 // The summation order over k is fixed, so results are deterministic.
-__global__ __launch_bounds__(256) void k_sgemm(int M, int N, int Kd, float alpha, const float* __restrict__ a,
-                                               long long sab, int sam, int sak, const float* __restrict__ bm,
-                                               long long sbb, int sbk, int sbn, float* __restrict__ cm, long long scb) {
-  __shared__ float As[16][68];
-  __shared__ float Bs[16][68];
-  const int b = blockIdx.z, m0 = blockIdx.y * 64, n0 = blockIdx.x * 64;
-  const float* ab = a + b * sab;
-  const float* bb = bm + b * sbb;
-  const int tid = threadIdx.x, tm = tid / 16, tn = tid % 16;
-  float acc[4][4];
+typedef float f32x16g __attribute__((ext_vector_type(16)));
+
+__device__ __forceinline__ void gemm_stage(float (*T)[36], const float* __restrict__ base, int rows_valid, int k_valid,
+                                           long long srow, long long sk, int tid) {
+  // T[r][kk] = base[r*srow + kk*sk] for r < rows_valid, kk < k_valid, else 0 (64 rows x 32 k)
+  if (sk == 1) {
+    const int r = tid >> 2, kq = (tid & 3) * 8;
+    const float* p = base + r * srow + kq;
+    const bool vec = (r < rows_valid) && (kq + 8 <= k_valid) && ((srow & 3) == 0) && ((((uintptr_t)base) & 15) == 0);
+    float v[8];
+    if (vec) {
+      const float4 x = *(const float4*)p, y = *(const float4*)(p + 4);
+      v[0] = x.x; v[1] = x.y; v[2] = x.z; v[3] = x.w; v[4] = y.x; v[5] = y.y; v[6] = y.z; v[7] = y.w;
+    } else {
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
-#pragma unroll
-    for (int j = 0; j < 4; ++j) acc[i][j] = 0.f;
-  for (int k0 = 0; k0 < Kd; k0 += 16) {
-#pragma unroll
-    for (int it = 0; it < 4; ++it) {
-      const int e = it * 256 + tid;
-      // keep the unit-stride axis on consecutive threads
-      int mm, kk;
-      if (sak == 1) { kk = e % 16; mm = e / 16; } else { mm = e % 64; kk = e / 64; }
-      float va = 0.f;
-      if (m0 + mm < M && k0 + kk < Kd) va = ab[(long long)(m0 + mm) * sam + (long long)(k0 + kk) * sak];
-      As[kk][mm] = va;
-      int nn, kb;
-      if (sbk == 1) { kb = e % 16; nn = e / 16; } else { nn = e % 64; kb = e / 64; }
-      float vb = 0.f;
-      if (n0 + nn < N && k0 + kb < Kd) vb = bb[(long long)(k0 + kb) * sbk + (long long)(n0 + nn) * sbn];
-      Bs[kb][nn] = vb;
+      for (int i = 0; i < 8; ++i) v[i] = (r < rows_valid && kq + i < k_valid) ? p[i] : 0.f;
     }
+    *(float4*)&T[r][kq] = make_float4(v[0], v[1], v[2], v[3]);
+    *(float4*)&T[r][kq + 4] = make_float4(v[4], v[5], v[6], v[7]);
+  } else {  // rows contiguous in memory: coalesced reads along the row axis, transposing LDS writes
+    const int kk = tid >> 3, rq = (tid & 7) * 8;
+    const float* p = base + (long long)kk * sk + (long long)rq * srow;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) T[rq + i][kk] = (rq + i < rows_valid && kk < k_valid) ? p[i * srow] : 0.f;
+  }
+}
+
+__global__ __launch_bounds__(256) void k_gemm32(int M, int N, int Kd, float alpha, const float* __restrict__ a,
+                                                long long sab, int sam, int sak, const float* __restrict__ bm,
+                                                long long sbb, int sbk, int sbn, float* __restrict__ cm, long long scb) {
+  __shared__ __attribute__((aligned(16))) float As[64][36];
+  __shared__ __attribute__((aligned(16))) float Bs[64][36];
+  const int b = blockIdx.z, m0 = blockIdx.y * 64, n0 = blockIdx.x * 64;
+  const float* ab = a + b * sab + (long long)m0 * sam;
+  const float* bb = bm + b * sbb + (long long)n0 * sbn;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave & 1, wn = wave >> 1, l32 = lane & 31, h = lane >> 5;
+  f32x16g acc;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+  for (int k0 = 0; k0 < Kd; k0 += 32) {
+    gemm_stage(As, ab + (long long)k0 * sak, M - m0, Kd - k0, sam, sak, tid);
+    gemm_stage(Bs, bb + (long long)k0 * sbk, N - n0, Kd - k0, sbn, sbk, tid);
     __syncthreads();
 #pragma unroll
-    for (int kk = 0; kk < 16; ++kk) {
-      const float4 av = *(const float4*)&As[kk][tm * 4];
-      const float4 bv = *(const float4*)&Bs[kk][tn * 4];
-      const float ar[4] = {av.x, av.y, av.z, av.w}, br[4] = {bv.x, bv.y, bv.z, bv.w};
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(ar[i], br[j], acc[i][j]);
+    for (int j = 0; j < 4; ++j) {
+      const float4 av = *(const float4*)&As[wm * 32 + l32][8 * j + 4 * h];
+      const float4 bv = *(const float4*)&Bs[wn * 32 + l32][8 * j + 4 * h];
+      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av.x, bv.x, acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av.y, bv.y, acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av.z, bv.z, acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av.w, bv.w, acc, 0, 0, 0);
     }
     __syncthreads();
   }
   float* cb = cm + b * scb;
+  const int n = n0 + wn * 32 + l32;
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int m = m0 + tm * 4 + i, n = n0 + tn * 4 + j;
-      if (m < M && n < N) cb[(long long)m * N + n] = alpha * acc[i][j];
-    }
+  for (int i = 0; i < 16; ++i) {
+    const int m = m0 + wm * 32 + 8 * (i / 4) + 4 * h + (i % 4);
+    if (m < M && n < N) cb[(long long)m * N + n] = alpha * acc[i];
+  }
 }
 
+hipError_t gemm32(int batch, int M, int N, int Kd, float alpha, const float* a, long long sab, int sam, int sak,
+                  const float* b, long long sbb, int sbk, int sbn, float* c, long long scb, hipStream_t s) {
+  dim3 grid((N + 63) / 64, (M + 63) / 64, batch);
+  k_gemm32<<<grid, 256, 0, s>>>(M, N, Kd, alpha, a, sab, sam, sak, b, sbb, sbk, sbn, c, scb);
+  return hipGetLastError();
+}
 static hipError_t sgemm(int batch, int M, int N, int Kd, float alpha, const float* a, long long sab, int sam, int sak,
                         const float* b, long long sbb, int sbk, int sbn, float* c, long long scb, hipStream_t s) {
-  dim3 grid((N + 63) / 64, (M + 63) / 64, batch);
-  k_sgemm<<<grid, 256, 0, s>>>(M, N, Kd, alpha, a, sab, sam, sak, b, sbb, sbk, sbn, c, scb);
-  return hipGetLastError();
+  return gemm32(batch, M, N, Kd, alpha, a, sab, sam, sak, b, sbb, sbk, sbn, c, scb, s);
 }
 
 // Row-wise softmax backward on the coarse score matrix, in place:

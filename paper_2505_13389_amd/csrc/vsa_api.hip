@@ -55,7 +55,7 @@ struct Carver {
 
 struct FwdWs {
   uint64_t* mask;
-  float *qc, *kc, *vc, *oc, *lse_c;
+  float *qc, *kc, *vc, *oc, *lse_c, *sc;
   int32_t* idx;
   size_t bytes;
 };
@@ -70,6 +70,7 @@ FwdWs carve_fwd(const vsa_params_t* p, const Geo& g, void* ws) {
   w.oc = c.take<float>(bh * g.Nc * p->d);
   w.lse_c = c.take<float>(bh * g.Nc);
   w.idx = c.take<int32_t>(bh * g.Nc * p->topk);
+  w.sc = c.take<float>(bh * g.Nc * g.Nc);
   w.bytes = c.used;
   return w;
 }
@@ -189,7 +190,7 @@ int vsa_forward(const vsa_params_t* p, const void* q, const void* k, const void*
 
   VSA_TRY("cube_masks", vsa::launch_cube_masks(g, w.mask, s));
   VSA_TRY("pool", vsa::launch_pool(g, BH, p->d, w.mask, q, k, v, w.qc, w.kc, w.vc, s));
-  VSA_TRY("coarse", vsa::launch_coarse(BH, g.Nc, p->d, p->topk, scale, w.qc, w.kc, w.vc, oc, lse_c, idx, given ? 0 : 1, s));
+  VSA_TRY("coarse", vsa::launch_coarse(BH, g.Nc, p->d, p->topk, scale, w.qc, w.kc, w.vc, w.sc, oc, lse_c, idx, given ? 0 : 1, s));
   VSA_TRY("fine_fwd", vsa::launch_fine_fwd(BH, g.Nc, p->d, p->topk, scale, q, k, v, gate_c, gate_f, idx, oc, w.mask, out, out_fine,
                                lse_fine, s));
   return VSA_OK;
