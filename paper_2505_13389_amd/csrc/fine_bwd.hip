@@ -168,17 +168,23 @@ hipError_t launch_fine_bwd_dq(int BH, int Nc, int d, int K, float scale, const v
 // dK/dV pass: one workgroup per (b, h, key cube); streams the (Q tile, dOf tile) pairs of the
 // query cubes that selected this key cube.  Wavefront (kh, qh): key rows kh*32..+31 (its output
 // rows; K and V of those rows stay in registers), query rows qh*32..+31 of each streamed tile.
-// Here S (not S^T) is formed, so a lane holds one key column and 16 query rows; the per-row pair
+// Here S (not S^T) is formed, so a lane holds one key column and 16 query rows.  The per-row pair
 // (lse*log2 e, Delta) of the streamed query tile -- `ld`, written by the preprocess kernel with
-// lse = +inf on pad rows so that pad queries give P = 0 -- is staged in LDS next to the tiles.
+// lse = +inf on pad rows so that pad queries give P = 0 -- is staged in LDS next to the tiles and
+// enters S and dP through one extra MFMA step each (split into three bf16 parts), as does the
+// large negative bias of pad keys.
 //
-// One workgroup per CU (the whole register file for 4 wavefronts), four LDS stages, and the
-// loop is software-pipelined inside each wavefront: iteration t forms S and dP of tile t+1
-// (MFMA) while the exponentials of tile t run (VALU), then feeds P and dS of tile t to the
-// dV / dK MFMAs.  Copies run three tiles ahead.  Per iteration: wait for this wave's share of
-// tile t+1, one barrier (tile t+1 complete; every wave done with tile t-1), refill the stage of
-// tile t-1 with tile t+3.  Past the end of the list the last tile is fetched again, so the
-// number of copies in flight is the same in every iteration.
+// One workgroup per CU (the whole register file for 4 wavefronts) and four LDS stages.  With a
+// single wavefront per SIMD nothing but the wavefront's own instruction order overlaps the matrix
+// pipe with LDS reads, copies and vector arithmetic, so the loop body is one basic block whose
+// order is pinned by scheduling barriers: every step is one MFMA plus its share of the other
+// work.  The loop is software-pipelined over three tiles: iteration t issues dV, dK of tile t,
+// turns S', dP' of tile t+1 into P, dS, and forms S', dP' of tile t+2; the LDS operands of each
+// phase are read during the phase before it.  Copies run four tiles ahead (two iterations of
+// flight).  Per iteration: wait for this wave's share of tile t+2, one barrier (tile t+2
+// complete; every wave done reading tile t), refill the stage of tile t with tile t+4.  Past the
+// end of the list the last tile is fetched again, so the number of copies in flight is the same
+// in every iteration.
 template <int D>
 __global__ __launch_bounds__(256, 1) void k_fine_bwd_dkv(int Nc, int K, float sl2, float scale, const uint4* __restrict__ q,
                                                          const uint4* __restrict__ k, const uint4* __restrict__ v,
@@ -232,109 +238,205 @@ __global__ __launch_bounds__(256, 1) void k_fine_bwd_dkv(int Nc, int K, float sl
     unsigned goff[TL::IPW];
     TL::lane_offsets(wave, lane, goff);
     const unsigned lds0 = lds_address(smem);
+    const int n = end - beg;
+    // The list of streamed query cubes sits in a register, 64 entries at a time (lane e holds
+    // entry e of the current chunk), so that the loop reads an index with v_readlane and issues
+    // no scalar or vector memory load of its own.
+    int chunk = 0;
+    int col_v = my_col[beg + min(lane, n - 1)];
+    asm volatile("" : "+v"(col_v));
+    auto entry = [&](int t) {  // cube of list entry min(t, end - 1)
+      const int e = min(t, end - 1) - beg;
+      if ((e >> 6) != chunk) {
+        chunk = e >> 6;
+        col_v = my_col[beg + min((chunk << 6) + lane, n - 1)];
+        asm volatile("" : "+v"(col_v));  // its wait stays inside this branch
+      }
+      return __builtin_amdgcn_readlane(col_v, e & 63);
+    };
     // fill stage `st` with the tiles of list entry min(t, end-1); every wave issues NLP copies
     auto fill = [&](int st, int t) {
-      const int cq = __builtin_amdgcn_readfirstlane(my_col[min(t, end - 1)]);
-      const long long r0 = rows0 + (long long)cq * kTile;
+      const long long r0 = rows0 + (long long)entry(t) * kTile;
       unsigned char* sp = smem + st * STAGE;
       TL::async_load(q, r0, sp, wave, goff);
       TL::async_load(dof, r0, sp + TL::BYTES, wave, goff);
-      if (lane < 8)  // 16 rows x (lse2, delta) = 128 bytes per wave
-        lds_dma16(uniform_ptr(ld + 2 * r0), (unsigned)(wave * 128 + lane * 16),
-                  __builtin_amdgcn_readfirstlane(lds0 + st * STAGE + 2 * TL::BYTES + wave * 128));
+      // (lse2, delta) of the 64 rows = 128 floats: every wave copies one half, all lanes active
+      // (waves 2 and 3 repeat the copies of waves 0 and 1, so that each wave issues NLP copies
+      // and none of them runs under a lane mask)
+      lds_dma4(uniform_ptr(ld + 2 * r0), (unsigned)((wave & 1) * 256 + lane * 4),
+               __builtin_amdgcn_readfirstlane(lds0 + st * STAGE + 2 * TL::BYTES + (wave & 1) * 256));
     };
-    auto s_dp = [&](int st, f32x16& sacc, f32x16& dpacc) {  // S and dP of the tile in stage st
+    // Per-row terms folded into the matrix products: one extra MFMA step on S adds
+    // -lse2[q]/sl2 (so that P = exp2(S' * sl2)) and a large negative bias on pad keys; one extra
+    // step on dP subtracts Delta[q].  The fp32 row values are split into three bf16 parts
+    // (exact to fp32 precision) in contraction slots 0..2 of the lane half h = 0; slot 3 carries
+    // the key bias (the dP step has a zero there).
+    const float inv_sl2 = 1.0f / sl2;
+    bf16x8 bias_b = {0, 0, 0, 0, 0, 0, 0, 0};
+    if (h == 0) {
+      bias_b[0] = bias_b[1] = bias_b[2] = (__bf16)1.f;
+      bias_b[3] = kvalid ? (__bf16)0.f : (__bf16)-30000.f;
+    }
+    auto split3 = [&](float x, bf16x8& out, float slot3) {  // x -> bf16 hi + mid + lo in slots 0..2 (h == 0 lanes)
+      const __bf16 hi = (__bf16)x;
+      const float r1 = (x == -INFINITY || x == INFINITY) ? 0.f : x - (float)hi;
+      const __bf16 mid = (__bf16)r1;
+      const __bf16 lo = (__bf16)(r1 - (float)mid);
+      const uint32_t w0 = (uint32_t)__builtin_bit_cast(unsigned short, hi) | ((uint32_t)__builtin_bit_cast(unsigned short, mid) << 16);
+      const uint32_t w1 = (uint32_t)__builtin_bit_cast(unsigned short, lo) |
+                          ((uint32_t)__builtin_bit_cast(unsigned short, (__bf16)slot3) << 16);
+      const uint4 u = make_uint4(h == 0 ? w0 : 0u, h == 0 ? w1 : 0u, 0u, 0u);  // selects, no branch
+      out = __builtin_bit_cast(bf16x8, u);
+    };
+    const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    // S' and dP' of the tile in stage st (prologue only; the loop interleaves the same steps)
+    auto s_dp = [&](int st, f32x16& sacc, f32x16& dpacc) {
       const unsigned char* Qs = smem + st * STAGE;
       const unsigned char* Ds = Qs + TL::BYTES;
-#pragma unroll
-      for (int i = 0; i < 16; ++i) { sacc[i] = 0.f; dpacc[i] = 0.f; }
+      const float2 row = ((const float2*)(Qs + 2 * TL::BYTES))[qh * 32 + l32];
+      bf16x8 la, da;
+      split3(-row.x * inv_sl2, la, 1.f);
+      split3(-row.y, da, 0.f);
+      sacc = zero;
+      dpacc = zero;
 #pragma unroll
       for (int s = 0; s < KS; ++s) sacc = mfma32(TL::rowmajor_operand(Qs, qh * 32, s, lane), kreg[s], sacc);
+      sacc = mfma32(la, bias_b, sacc);
 #pragma unroll
       for (int s = 0; s < KS; ++s) dpacc = mfma32(TL::rowmajor_operand(Ds, qh * 32, s, lane), vreg[s], dpacc);
+      dpacc = mfma32(da, bias_b, dpacc);
     };
+
+    // State carried from one iteration to the next (t = tile whose dV/dK products come next):
+    //   sA, dpA        S' and dP' of tile t+1
+    //   pb*, sb*       P and dS of tile t as bf16 operands
+    //   dt, qt         transposed dOf and Q operands of tile t
+    f32x16 sA, dpA;
+    bf16x8 pb0, pb1, sb0, sb1, dt[DVB][2], qt[DVB][2];
 
     fill(0, beg);
     fill(1, beg + 1);
     fill(2, beg + 2);
+    fill(3, beg + 3);
     wait_vmcnt<2 * NLP>();
     __builtin_amdgcn_s_barrier();
-    f32x16 sacc, dpacc;
-    s_dp(0, sacc, dpacc);
-
-    // ST = stage of tile t (tile t+1 sits in ST+1, tile t+3 goes where tile t-1 was)
-    auto body = [&](auto st_tag, int t) {
-      constexpr int ST = decltype(st_tag)::value;
-      wait_vmcnt<NLP>();
-      __builtin_amdgcn_s_barrier();
-      fill((ST + 3) & 3, t + 3);
-      __builtin_amdgcn_sched_barrier(0);
-      const unsigned char* Qs = smem + ST * STAGE;
-      const unsigned char* Ds = Qs + TL::BYTES;
-      const float* ls = (const float*)(Qs + 2 * TL::BYTES);
-      const unsigned char* Qn = smem + ((ST + 1) & 3) * STAGE;
-      const unsigned char* Dn = Qn + TL::BYTES;
-
-      // With one wavefront per SIMD nothing hides an LDS round trip, so every operand of the
-      // iteration is requested up front, in the order it is consumed.
-      bf16x8 qa[KS], da[KS], dt[DVB][2], qt[DVB][2];
-      float4 la[4], lb[4];
-#pragma unroll
-      for (int s = 0; s < KS; ++s) qa[s] = TL::rowmajor_operand(Qn, qh * 32, s, lane);
-#pragma unroll
-      for (int s = 0; s < KS; ++s) da[s] = TL::rowmajor_operand(Dn, qh * 32, s, lane);
-#pragma unroll
-      for (int g4 = 0; g4 < 4; ++g4) {
-        la[g4] = *(const float4*)&ls[2 * (qh * 32 + 8 * g4 + 4 * h)];
-        lb[g4] = *(const float4*)&ls[2 * (qh * 32 + 8 * g4 + 4 * h) + 4];
-      }
-#pragma unroll
-      for (int x = 0; x < DVB; ++x) {
-        dt[x][0] = TL::transposed_operand(Ds, qh * 32, 0, x * 32, lane);
-        dt[x][1] = TL::transposed_operand(Ds, qh * 32, 1, x * 32, lane);
-      }
-#pragma unroll
-      for (int x = 0; x < DVB; ++x) {
-        qt[x][0] = TL::transposed_operand(Qs, qh * 32, 0, x * 32, lane);
-        qt[x][1] = TL::transposed_operand(Qs, qh * 32, 1, x * 32, lane);
-      }
-      __builtin_amdgcn_sched_barrier(0);
-
-      // tile t+1: S, dP (independent of the arithmetic below, the scheduler interleaves them)
-      f32x16 sn, dpn;
-#pragma unroll
-      for (int i = 0; i < 16; ++i) { sn[i] = 0.f; dpn[i] = 0.f; }
-#pragma unroll
-      for (int s = 0; s < KS; ++s) sn = mfma32(qa[s], kreg[s], sn);
-#pragma unroll
-      for (int s = 0; s < KS; ++s) dpn = mfma32(da[s], vreg[s], dpn);
-
-      // tile t: P = exp2(S*sl2 - lse2), dS = P * (dP - Delta)
+    {
+      f32x16 s0, dp0;
+      s_dp(0, s0, dp0);
       float p[16], ds[16];
 #pragma unroll
-      for (int g4 = 0; g4 < 4; ++g4) {
-        const float4 a = la[g4], b = lb[g4];
-        const float lv[4] = {a.x, a.z, b.x, b.z}, dvv[4] = {a.y, a.w, b.y, b.w};
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const int i = 4 * g4 + e;
-          float pi = fast_exp2(fmaf(sacc[i], sl2, -lv[e]));
-          if (!kvalid) pi = 0.f;
-          p[i] = pi;
-          ds[i] = pi * (dpacc[i] - dvv[e]);
-        }
+      for (int i = 0; i < 16; ++i) {
+        p[i] = fast_exp2(s0[i] * sl2);
+        ds[i] = p[i] * dp0[i];
       }
-      const bf16x8 pb0 = acc_to_operand(p), pb1 = acc_to_operand(p + 8);
-      const bf16x8 sb0 = acc_to_operand(ds), sb1 = acc_to_operand(ds + 8);
+      pb0 = acc_to_operand(p), pb1 = acc_to_operand(p + 8);
+      sb0 = acc_to_operand(ds), sb1 = acc_to_operand(ds + 8);
 #pragma unroll
       for (int x = 0; x < DVB; ++x) {
-        dva[x] = mfma32(dt[x][0], pb0, dva[x]);
-        dva[x] = mfma32(dt[x][1], pb1, dva[x]);
-        dka[x] = mfma32(qt[x][0], sb0, dka[x]);
-        dka[x] = mfma32(qt[x][1], sb1, dka[x]);
+        dt[x][0] = TL::transposed_operand(smem + TL::BYTES, qh * 32, 0, x * 32, lane);
+        dt[x][1] = TL::transposed_operand(smem + TL::BYTES, qh * 32, 1, x * 32, lane);
+        qt[x][0] = TL::transposed_operand(smem, qh * 32, 0, x * 32, lane);
+        qt[x][1] = TL::transposed_operand(smem, qh * 32, 1, x * 32, lane);
       }
-      sacc = sn;
-      dpacc = dpn;
+      s_dp(1, sA, dpA);
+    }
+
+    // One iteration, ST = stage of tile t.  Tile t+1 sits in ST+1, tile t+2 in ST+2, tile t+3 is
+    // in flight and tile t+4 goes where tile t was.  Two phases, each a fixed interleave of one
+    // matrix instruction with a few LDS reads, copy instructions and vector operations, so that
+    // the single wavefront of a SIMD keeps the matrix pipe fed while it issues everything else:
+    //   A: dV, dK of tile t          | row-major reads of tile t+2, the copies of tile t+4,
+    //                                | P, dS of tile t+1
+    //   B: S', dP' of tile t+2       | transposed reads of tile t+1
+    const int lane_a = TL::rowmajor_lane(qh * 32, lane);
+    int lane_b0, lane_b1;
+    TL::transposed_lane(qh * 32, lane, lane_b0, lane_b1);
+    constexpr int NA = 4 * DVB, NB = 2 * (KS + 1);
+    static_assert(NA == 2 * KS && NLP <= NA && 16 % NA == 0, "phase interleave");
+    auto body = [&](auto st_tag, int t) {
+      constexpr int ST = decltype(st_tag)::value;
+      constexpr int S1 = (ST + 1) & 3, S2 = (ST + 2) & 3;
+      wait_lgkmcnt0();   // this wave's reads of tile t have landed: its stage may be overwritten
+      wait_vmcnt<NLP>();  // this wave's share of tile t+2 has landed
+      __builtin_amdgcn_s_barrier();
+      __builtin_amdgcn_sched_barrier(0);
+      const long long r0 = rows0 + (long long)entry(t + 4) * kTile;
+      const void* gq = uniform_ptr(q + r0 * CPR);
+      const void* gd = uniform_ptr(dof + r0 * CPR);
+      const void* gl = uniform_ptr(ld + 2 * r0);
+      const unsigned lq = __builtin_amdgcn_readfirstlane(lds0 + ST * STAGE + (unsigned)(wave * TL::IPW) * 1024u);
+      const unsigned ll = __builtin_amdgcn_readfirstlane(lds0 + ST * STAGE + 2 * TL::BYTES + (wave & 1) * 256);
+      // operand addresses are rebuilt from three lane-dependent values in every iteration (one
+      // XOR per read) instead of being held in registers across the loop
+      int la_n = lane_a, lb0_n = lane_b0, lb1_n = lane_b1;
+      asm volatile("" : "+v"(la_n), "+v"(lb0_n), "+v"(lb1_n));
+      constexpr int FAR = 2 * STAGE;  // constant offsets of LDS reads stop at 64 KiB
+      const int la_2 = la_n + (S2 >= 2 ? FAR : 0), lb0_1 = lb0_n + (S1 >= 2 ? FAR : 0), lb1_1 = lb1_n + (S1 >= 2 ? FAR : 0);
+      const unsigned char* Q1 = smem + (S1 & 1) * STAGE;
+      const unsigned char* D1 = Q1 + TL::BYTES;
+      const unsigned char* Q2 = smem + (S2 & 1) * STAGE;
+      const unsigned char* D2 = Q2 + TL::BYTES;
+      bf16x8 qa[KS], da[KS], la, dla, pbn0, pbn1, sbn0, sbn1;
+      float pn[16], dsn[16];
+      uint4 pu0, pu1, su0, su1;
+      float2 row;
+      auto value = [&](int i) {
+        pn[i] = fast_exp2(sA[i] * sl2);
+        dsn[i] = pn[i] * dpA[i];
+      };
+
+#pragma unroll
+      for (int i = 0; i < NA; ++i) {
+        const int x = i >> 2, sub = i & 3;
+        if (sub == 0) dva[x] = mfma32(dt[x][0], pb0, dva[x]);
+        if (sub == 1) dva[x] = mfma32(dt[x][1], pb1, dva[x]);
+        if (sub == 2) dka[x] = mfma32(qt[x][0], sb0, dka[x]);
+        if (sub == 3) dka[x] = mfma32(qt[x][1], sb1, dka[x]);
+        if (i < KS) qa[i] = TL::rowmajor_at(Q2, la_2, i);
+        else da[i - KS] = TL::rowmajor_at(D2, la_2, i - KS);
+        if (i == 0) row = ((const float2*)(smem + S2 * STAGE + 2 * TL::BYTES))[qh * 32 + l32];
+        if (i < TL::IPW) lds_dma16(gq, goff[i], lq + (unsigned)i * 1024u);
+        else if (i < 2 * TL::IPW) lds_dma16(gd, goff[i - TL::IPW], lq + TL::BYTES + (unsigned)(i - TL::IPW) * 1024u);
+        else if (i == 2 * TL::IPW) lds_dma4(gl, (unsigned)((wave & 1) * 256 + lane * 4), ll);
+        constexpr int VPC = 16 / NA;  // P, dS values per step (all of tile t+1: S', dP' of it die here)
+#pragma unroll
+        for (int u = 0; u < VPC; ++u) {
+          const int e = i * VPC + u;
+          value(e);
+          if (e & 1) {  // pack each pair at once: few fp32 values stay live
+            const uint32_t pp = pack_bf16(pn[e - 1], pn[e]), ss = pack_bf16(dsn[e - 1], dsn[e]);
+            uint4& pu = e < 8 ? pu0 : pu1;
+            uint4& su = e < 8 ? su0 : su1;
+            const int w = (e >> 1) & 3;
+            if (w == 0) pu.x = pp, su.x = ss;
+            if (w == 1) pu.y = pp, su.y = ss;
+            if (w == 2) pu.z = pp, su.z = ss;
+            if (w == 3) pu.w = pp, su.w = ss;
+          }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      pbn0 = __builtin_bit_cast(bf16x8, pu0), pbn1 = __builtin_bit_cast(bf16x8, pu1);
+      sbn0 = __builtin_bit_cast(bf16x8, su0), sbn1 = __builtin_bit_cast(bf16x8, su1);
+
+      f32x16 sN, dpN;
+#pragma unroll
+      for (int i = 0; i < NB; ++i) {
+        const int s = i >> 1;
+        if (!(i & 1)) sN = mfma32(s < KS ? qa[s < KS ? s : 0] : la, s < KS ? kreg[s < KS ? s : 0] : bias_b, i < 2 ? zero : sN);
+        else dpN = mfma32(s < KS ? da[s < KS ? s : 0] : dla, s < KS ? vreg[s < KS ? s : 0] : bias_b, i < 2 ? zero : dpN);
+        if (i < 4 * DVB) {
+          const int x = i >> 2, which = i & 3;
+          if (which < 2) dt[x][which] = TL::transposed_at(D1, lb0_1, lb1_1, which, x);
+          else qt[x][which - 2] = TL::transposed_at(Q1, lb0_1, lb1_1, which - 2, x);
+        }
+        if (i == 0) split3(-row.x * inv_sl2, la, 1.f);
+        if (i == 2) split3(-row.y, dla, 0.f);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      sA = sN;
+      dpA = dpN;
+      pb0 = pbn0, pb1 = pbn1, sb0 = sbn0, sb1 = sbn1;
     };
 
     for (int t = beg; t < end; t += 4) {

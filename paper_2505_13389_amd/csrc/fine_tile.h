@@ -135,6 +135,29 @@ struct Tile {
     bf16x4 a1 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4_ptr)(tile + off(r1 + 8, ch) + sub));
     return __builtin_shufflevector(a0, a1, 0, 1, 2, 3, 4, 5, 6, 7);
   }
+
+  // The same two operand reads with the lane-dependent part of the address split off, for loops
+  // that cannot afford one address register per read: the swizzle is an XOR on the chunk bits, so
+  // the k-step s of a row-major operand and the column block x of a transposed operand enter as
+  // an XOR with a constant, everything else as a constant byte offset.
+  __device__ static __forceinline__ int rowmajor_lane(int row0, int lane) { return off(row0 + (lane & 31), lane >> 5); }
+  __device__ static __forceinline__ bf16x8 rowmajor_at(const unsigned char* tile, int lane_part, int s) {
+    return *(const bf16x8*)(tile + (lane_part ^ (s << 5)));
+  }
+  // valid for row0 a multiple of 32 (swz(r + 8) == swz(r) ^ 2 and swz(r + 16) == swz(r) then hold)
+  __device__ static __forceinline__ void transposed_lane(int row0, int lane, int& b0, int& b1) {
+    const int L = lane & 15;
+    const int r1 = row0 + 4 * (lane >> 5) + (L >> 2);
+    const int col = ((lane >> 4) & 1) * 16 + 4 * (L & 3);
+    b0 = off(r1, col >> 3) + (col & 7) * 2;
+    b1 = off(r1 + 8, col >> 3) + (col & 7) * 2;
+  }
+  __device__ static __forceinline__ bf16x8 transposed_at(const unsigned char* tile, int b0, int b1, int s, int x) {
+    const unsigned char* p = tile + s * 16 * ROW_BYTES;
+    bf16x4 a0 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4_ptr)(p + (b0 ^ (x << 6))));
+    bf16x4 a1 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4_ptr)(p + (b1 ^ (x << 6))));
+    return __builtin_shufflevector(a0, a1, 0, 1, 2, 3, 4, 5, 6, 7);
+  }
 };
 
 // fp32 accumulator values [8s .. 8s+7] -> bf16 operand of k-step s (see transposed_operand).
