@@ -64,9 +64,15 @@ __global__ __launch_bounds__(256, 2) void k_fine_bwd_dq(int Nc, int K, float sl2
 
   unsigned goff[TL::IPW];
   TL::lane_offsets(wave, lane, goff);
-  int jt = my_idx[0];
-  TL::async_load(k, rows0 + (long long)jt * kTile, stage0, wave, goff);
-  TL::async_load(v, rows0 + (long long)jt * kTile, stage0 + TL::BYTES, wave, goff);
+  CubeList cubes;
+  cubes.init(my_idx, mask, K, kh, lane);
+  uint32_t km_cur;  // valid-key mask (this wave's key half) of the tile of this iteration
+  {
+    int jt;
+    cubes.get(0, jt, km_cur);
+    TL::async_load(k, rows0 + (long long)jt * kTile, stage0, wave, goff);
+    TL::async_load(v, rows0 + (long long)jt * kTile, stage0 + TL::BYTES, wave, goff);
+  }
 
   f32x16 acc[DVB];
 #pragma unroll
@@ -77,11 +83,12 @@ __global__ __launch_bounds__(256, 2) void k_fine_bwd_dq(int Nc, int K, float sl2
   // Per tile: wait for this wave's share of tile t, barrier (tile t complete, and every wave is
   // done with tile t-1), start the copy of tile t+1 into the other stage, do the math on tile t.
   auto body = [&](const unsigned char* cur, unsigned char* nxt, int t) {
-    const uint64_t kmask = mask[jt];
+    const uint32_t mh = km_cur;
     wait_vmcnt<0>();
     __builtin_amdgcn_s_barrier();
     if (t + 1 < K) {
-      jt = my_idx[t + 1];
+      int jt;
+      cubes.get(t + 1, jt, km_cur);
       TL::async_load(k, rows0 + (long long)jt * kTile, nxt, wave, goff);
       TL::async_load(v, rows0 + (long long)jt * kTile, nxt + TL::BYTES, wave, goff);
     }
@@ -100,8 +107,7 @@ __global__ __launch_bounds__(256, 2) void k_fine_bwd_dq(int Nc, int K, float sl2
     float ds[16];
 #pragma unroll
     for (int i = 0; i < 16; ++i) ds[i] = fast_exp2(fmaf(sacc[i], sl2, -lse2)) * (dpacc[i] - dl);
-    if (kmask != ~0ull) {
-      const uint32_t mh = (uint32_t)(kmask >> (kh * 32));
+    if (mh != 0xffffffffu) {
 #pragma unroll
       for (int i = 0; i < 16; ++i)
         if (!((mh >> (8 * (i / 4) + 4 * h + (i % 4))) & 1)) ds[i] = 0.f;

@@ -74,9 +74,17 @@ __global__ __launch_bounds__(256, 2) void k_fine_fwd(int Nc, int K, float sl2, c
   // Every iteration issues exactly NL copies, also past the end of the list (the last tile is
   // simply fetched again): the number of copies younger than the tile being waited for is then
   // always NL, which both the hand-written waits and the compiler's own bookkeeping rely on.
-  int j0 = my_idx[0], j1 = my_idx[min(1, K - 1)];
-  issue(stage0, j0);
-  issue(stage1, j1);
+  // km0 / km1: valid-key masks (this wave's key half) of the tile of this iteration / the next
+  CubeList cubes;
+  cubes.init(my_idx, mask, K, kh, lane);
+  uint32_t km0, km1;
+  {
+    int j0, j1;
+    cubes.get(0, j0, km0);
+    cubes.get(min(1, K - 1), j1, km1);
+    issue(stage0, j0);
+    issue(stage1, j1);
+  }
 
   float mref = -INFINITY, lsum = 0.f;
   const bf16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
@@ -88,9 +96,8 @@ __global__ __launch_bounds__(256, 2) void k_fine_fwd(int Nc, int K, float sl2, c
 #pragma unroll
     for (int i = 0; i < 16; ++i) o[x][i] = 0.f;
 
-  // j0 = tile of this iteration, j1 = tile of the next one (already in flight)
   auto body = [&](unsigned char* cur, int t) {
-    const uint64_t kmask = mask[j0];
+    const uint32_t kmask = km0;
     wait_vmcnt<NL>();  // this wave's share of tile pair t has landed (only the NL copies of t+1 may be pending)
     __builtin_amdgcn_s_barrier();
     const unsigned char* Ks = cur;
@@ -105,9 +112,14 @@ __global__ __launch_bounds__(256, 2) void k_fine_fwd(int Nc, int K, float sl2, c
     }
     wait_lgkmcnt0();  // this wave's LDS reads of the stage are done
     __builtin_amdgcn_s_barrier();
-    j0 = j1;
-    j1 = my_idx[min(t + 2, K - 1)];
-    issue(cur, j1);
+    {
+      int j2;
+      uint32_t km2;
+      cubes.get(min(t + 2, K - 1), j2, km2);
+      issue(cur, j2);
+      km0 = km1;
+      km1 = km2;
+    }
     __builtin_amdgcn_sched_barrier(0);
 
     f32x16 sacc;
@@ -118,9 +130,9 @@ __global__ __launch_bounds__(256, 2) void k_fine_fwd(int Nc, int K, float sl2, c
 
     // Pad keys of a partially filled cube never take part: one extra MFMA adds a large negative
     // bias to their rows of S^T (A = bias of key l%32 in contraction slot 0, B = ones in slot 0).
-    const bool partial = kmask != ~0ull;
+    const bool partial = kmask != 0xffffffffu;
     if (partial) {
-      const bool dead = !((kmask >> (kh * 32 + l32)) & 1);
+      const bool dead = !((kmask >> l32) & 1);
       bf16x8 ab = zero8;
       ab[0] = (h == 0 && dead) ? (__bf16)kMaskBias : (__bf16)0.f;
       sacc = mfma32(ab, ones_b, sacc);

@@ -52,6 +52,35 @@ __device__ __forceinline__ void wait_vmcnt() {
 }
 __device__ __forceinline__ void wait_lgkmcnt0() { __builtin_amdgcn_s_waitcnt(0xC07F); }
 
+// The list of key cubes a workgroup streams, with the valid-key mask of one 32-key half of each
+// cube, held in registers 64 entries at a time (lane e holds entry e of the current chunk).  The
+// loops read an entry with v_readlane: no scalar or vector load, and so no wait on one, sits
+// between a barrier and the copies issued after it.  Entries must be visited in ascending order.
+struct CubeList {
+  const int32_t* list;
+  const uint64_t* mask;
+  int n, half, lane, chunk, idx_v;
+  uint32_t km_v;
+  __device__ __forceinline__ void load_chunk(int c) {
+    chunk = c;
+    idx_v = list[min((c << 6) + lane, n - 1)];
+    const uint64_t m = mask[idx_v];
+    km_v = half ? (uint32_t)(m >> 32) : (uint32_t)m;
+    // consumed at once: the compiler's wait for these loads is placed right here
+    asm volatile("" : "+v"(idx_v), "+v"(km_v));
+  }
+  __device__ __forceinline__ void init(const int32_t* list_, const uint64_t* mask_, int n_, int half_, int lane_) {
+    list = list_, mask = mask_, n = n_, half = half_, lane = lane_;
+    load_chunk(0);
+  }
+  // cube index and key mask of entry e (wave-uniform, 0 <= e < n)
+  __device__ __forceinline__ void get(int e, int& cube, uint32_t& km) {
+    if ((e >> 6) != chunk) load_chunk(e >> 6);
+    cube = __builtin_amdgcn_readlane(idx_v, e & 63);
+    km = (uint32_t)__builtin_amdgcn_readlane((int)km_v, e & 63);
+  }
+};
+
 template <int D>
 struct Tile {
   static constexpr int CPR = D / 8;               // 16-byte chunks per row
