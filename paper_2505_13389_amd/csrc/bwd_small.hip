@@ -12,13 +12,24 @@ namespace vsa {
 //   ld_i = (lse_i * log2(e), Delta_i) as one pair per row, lse = +inf on pad rows (makes P = 0
 //          there in the fine backward kernels)
 // One workgroup per (b*h, cube); thread layout as in the pooling kernel.
+// x as bf16 hi + mid + lo (slots 0..2) and `slot3` as bf16 in slot 3 of an MFMA operand
+__device__ __forceinline__ uint2 split3_bf16(float x, float slot3) {
+  const __bf16 hi = (__bf16)x;
+  const float r1 = x - (float)hi;
+  const __bf16 mid = (__bf16)r1;
+  const __bf16 lo = (__bf16)(r1 - (float)mid);
+  auto bits = [](__bf16 v) { return (uint32_t)__builtin_bit_cast(unsigned short, v); };
+  return make_uint2(bits(hi) | (bits(mid) << 16), bits(lo) | (bits((__bf16)slot3) << 16));
+}
+
 template <int D>
 __global__ __launch_bounds__(256) void k_bwd_pre(int Nc, const uint64_t* __restrict__ mask, const uint4* __restrict__ dout,
                                                  const uint4* __restrict__ gc, const uint4* __restrict__ gf,
                                                  const uint4* __restrict__ of, const float* __restrict__ oc,
                                                  uint4* __restrict__ dgc, uint4* __restrict__ dgf,
                                                  uint4* __restrict__ dof, float* __restrict__ ld,
-                                                 float* __restrict__ doc, const float* __restrict__ lse_f) {
+                                                 uint4* __restrict__ ldb, float inv_sl2, float* __restrict__ doc,
+                                                 const float* __restrict__ lse_f) {
   constexpr int CPR = D / 8, RG = 256 / CPR, RPT = kTile / RG;
   __shared__ float part[RG][D + 4];
   const int c = blockIdx.x % Nc;
@@ -68,7 +79,16 @@ __global__ __launch_bounds__(256) void k_bwd_pre(int Nc, const uint64_t* __restr
     dof[g] = o_dof;
 #pragma unroll
     for (int o = CPR / 2; o > 0; o >>= 1) dsum += __shfl_xor(dsum, o);
-    if (ch == 0) *(float2*)&ld[2 * (row0 + r)] = make_float2(valid ? lse_f[row0 + r] * kLog2e : INFINITY, dsum);
+    if (ch == 0) {
+      const float lse2 = valid ? lse_f[row0 + r] * kLog2e : INFINITY;
+      *(float2*)&ld[2 * (row0 + r)] = make_float2(lse2, dsum);
+      // the same pair as two rows of bf16 MFMA operand slots: -lse2/sl2 and -Delta, each split into
+      // three bf16 parts that add up to the fp32 value, then a constant slot (1 for the first, 0
+      // for the second).  Pad rows carry a large finite negative number instead of -inf.
+      const uint2 a = split3_bf16(valid ? -lse2 * inv_sl2 : -30000.f, 1.f);
+      const uint2 b = split3_bf16(-dsum, 0.f);
+      ldb[row0 + r] = make_uint4(a.x, a.y, b.x, b.y);
+    }
   }
 #pragma unroll
   for (int e = 0; e < 8; ++e) part[rg][ch * 8 + e] = acc[e];
@@ -82,16 +102,18 @@ __global__ __launch_bounds__(256) void k_bwd_pre(int Nc, const uint64_t* __restr
 
 hipError_t launch_bwd_pre(int BH, int Nc, int d, const uint64_t* mask, const void* dout, const void* gate_c,
                           const void* gate_f, const void* out_fine, const float* oc, void* dgate_c, void* dgate_f,
-                          void* dof, float* ld, float* doc, const float* lse_f, hipStream_t s) {
+                          void* dof, float* ld, void* ldb, float scale, float* doc, const float* lse_f,
+                          hipStream_t s) {
   const unsigned grid = (unsigned)(BH * Nc);
+  const float inv_sl2 = 1.0f / (scale * kLog2e);
   if (d == 128)
     k_bwd_pre<128><<<grid, 256, 0, s>>>(Nc, mask, (const uint4*)dout, (const uint4*)gate_c, (const uint4*)gate_f,
                                         (const uint4*)out_fine, oc, (uint4*)dgate_c, (uint4*)dgate_f, (uint4*)dof, ld,
-                                        doc, lse_f);
+                                        (uint4*)ldb, inv_sl2, doc, lse_f);
   else
     k_bwd_pre<64><<<grid, 256, 0, s>>>(Nc, mask, (const uint4*)dout, (const uint4*)gate_c, (const uint4*)gate_f,
                                        (const uint4*)out_fine, oc, (uint4*)dgate_c, (uint4*)dgate_f, (uint4*)dof, ld,
-                                       doc, lse_f);
+                                       (uint4*)ldb, inv_sl2, doc, lse_f);
   return hipGetLastError();
 }
 

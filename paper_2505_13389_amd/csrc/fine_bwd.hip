@@ -197,14 +197,14 @@ __global__ __launch_bounds__(256, 1) void k_fine_bwd_dkv(int Nc, int K, float sl
                                                          const uint4* __restrict__ dof,
                                                          const int32_t* __restrict__ row_ptr,
                                                          const int32_t* __restrict__ col,
-                                                         const float* __restrict__ ld,
+                                                         const uint4* __restrict__ ldb,
                                                          const float* __restrict__ dkc, const float* __restrict__ dvc,
                                                          const uint64_t* __restrict__ mask, uint4* __restrict__ dk,
                                                          uint4* __restrict__ dv) {
   using TL = Tile<D>;
   constexpr int CPR = TL::CPR, KS = D / 16, DVB = D / 32, LPT = TL::LPT;
   constexpr int OS = D;
-  constexpr int STAGE = 2 * TL::BYTES + 2 * kTile * 4;  // Q tile, dOf tile, (lse2, delta)[64]
+  constexpr int STAGE = 2 * TL::BYTES + kTile * 16;  // Q tile, dOf tile, 16 bytes of (lse2, Delta) operand slots per row
   constexpr int NLP = 2 * TL::IPW + 1;                  // copies per wave and stage
   __shared__ __attribute__((aligned(16))) unsigned char smem[4 * STAGE];
   static_assert(2 * 64 * OS * 4 <= 4 * STAGE, "merge buffers must fit");
@@ -266,43 +266,35 @@ __global__ __launch_bounds__(256, 1) void k_fine_bwd_dkv(int Nc, int K, float sl
       unsigned char* sp = smem + st * STAGE;
       TL::async_load(q, r0, sp, wave, goff);
       TL::async_load(dof, r0, sp + TL::BYTES, wave, goff);
-      // (lse2, delta) of the 64 rows = 128 floats: every wave copies one half, all lanes active
-      // (waves 2 and 3 repeat the copies of waves 0 and 1, so that each wave issues NLP copies
-      // and none of them runs under a lane mask)
-      lds_dma4(uniform_ptr(ld + 2 * r0), (unsigned)((wave & 1) * 256 + lane * 4),
-               __builtin_amdgcn_readfirstlane(lds0 + st * STAGE + 2 * TL::BYTES + (wave & 1) * 256));
+      // the (lse2, Delta) operand slots of the 64 rows, 1 KiB: a quarter per wave
+      lds_dma4(uniform_ptr(ldb + r0), (unsigned)(wave * 256 + lane * 4),
+               __builtin_amdgcn_readfirstlane(lds0 + st * STAGE + 2 * TL::BYTES + wave * 256));
     };
     // Per-row terms folded into the matrix products: one extra MFMA step on S adds
     // -lse2[q]/sl2 (so that P = exp2(S' * sl2)) and a large negative bias on pad keys; one extra
-    // step on dP subtracts Delta[q].  The fp32 row values are split into three bf16 parts
-    // (exact to fp32 precision) in contraction slots 0..2 of the lane half h = 0; slot 3 carries
-    // the key bias (the dP step has a zero there).
-    const float inv_sl2 = 1.0f / sl2;
+    // step on dP subtracts Delta[q].  The preprocess kernel has split both fp32 row values into
+    // three bf16 parts (exact to fp32 precision) for contraction slots 0..2; slot 3 is 1 for the S
+    // step (it multiplies the key bias) and 0 for the dP step.  Only the lane half h = 0 of the
+    // other operand is non-zero, so both lane halves may load the same row slots.
     bf16x8 bias_b = {0, 0, 0, 0, 0, 0, 0, 0};
     if (h == 0) {
       bias_b[0] = bias_b[1] = bias_b[2] = (__bf16)1.f;
       bias_b[3] = kvalid ? (__bf16)0.f : (__bf16)-30000.f;
     }
-    auto split3 = [&](float x, bf16x8& out, float slot3) {  // x -> bf16 hi + mid + lo in slots 0..2 (h == 0 lanes)
-      const __bf16 hi = (__bf16)x;
-      const float r1 = (x == -INFINITY || x == INFINITY) ? 0.f : x - (float)hi;
-      const __bf16 mid = (__bf16)r1;
-      const __bf16 lo = (__bf16)(r1 - (float)mid);
-      const uint32_t w0 = (uint32_t)__builtin_bit_cast(unsigned short, hi) | ((uint32_t)__builtin_bit_cast(unsigned short, mid) << 16);
-      const uint32_t w1 = (uint32_t)__builtin_bit_cast(unsigned short, lo) |
-                          ((uint32_t)__builtin_bit_cast(unsigned short, (__bf16)slot3) << 16);
-      const uint4 u = make_uint4(h == 0 ? w0 : 0u, h == 0 ? w1 : 0u, 0u, 0u);  // selects, no branch
-      out = __builtin_bit_cast(bf16x8, u);
+    auto row_read = [&](const unsigned char* stage) {
+      return *(const uint4*)(stage + 2 * TL::BYTES + (qh * 32 + l32) * 16);
+    };
+    auto row_slots = [&](const uint4& r, bf16x8& la, bf16x8& da) {
+      la = __builtin_bit_cast(bf16x8, make_uint4(r.x, r.y, 0u, 0u));
+      da = __builtin_bit_cast(bf16x8, make_uint4(r.z, r.w, 0u, 0u));
     };
     const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     // S' and dP' of the tile in stage st (prologue only; the loop interleaves the same steps)
     auto s_dp = [&](int st, f32x16& sacc, f32x16& dpacc) {
       const unsigned char* Qs = smem + st * STAGE;
       const unsigned char* Ds = Qs + TL::BYTES;
-      const float2 row = ((const float2*)(Qs + 2 * TL::BYTES))[qh * 32 + l32];
       bf16x8 la, da;
-      split3(-row.x * inv_sl2, la, 1.f);
-      split3(-row.y, da, 0.f);
+      row_slots(row_read(Qs), la, da);
       sacc = zero;
       dpacc = zero;
 #pragma unroll
@@ -354,6 +346,9 @@ __global__ __launch_bounds__(256, 1) void k_fine_bwd_dkv(int Nc, int K, float sl
     //   A: dV, dK of tile t          | row-major reads of tile t+2, the copies of tile t+4,
     //                                | P, dS of tile t+1
     //   B: S', dP' of tile t+2       | transposed reads of tile t+1
+    unsigned goff_im[TL::IPW];  // per-lane source offsets less the instruction offset of copy i
+#pragma unroll
+    for (int i = 0; i < TL::IPW; ++i) goff_im[i] = goff[i] - (unsigned)i * 1024u;
     const int lane_a = TL::rowmajor_lane(qh * 32, lane);
     int lane_b0, lane_b1;
     TL::transposed_lane(qh * 32, lane, lane_b0, lane_b1);
@@ -369,9 +364,9 @@ __global__ __launch_bounds__(256, 1) void k_fine_bwd_dkv(int Nc, int K, float sl
       const long long r0 = rows0 + (long long)entry(t + 4) * kTile;
       const void* gq = uniform_ptr(q + r0 * CPR);
       const void* gd = uniform_ptr(dof + r0 * CPR);
-      const void* gl = uniform_ptr(ld + 2 * r0);
+      const void* gl = uniform_ptr(ldb + r0);
       const unsigned lq = __builtin_amdgcn_readfirstlane(lds0 + ST * STAGE + (unsigned)(wave * TL::IPW) * 1024u);
-      const unsigned ll = __builtin_amdgcn_readfirstlane(lds0 + ST * STAGE + 2 * TL::BYTES + (wave & 1) * 256);
+      const unsigned ll = __builtin_amdgcn_readfirstlane(lds0 + ST * STAGE + 2 * TL::BYTES + wave * 256);
       // operand addresses are rebuilt from three lane-dependent values in every iteration (one
       // XOR per read) instead of being held in registers across the loop
       int la_n = lane_a, lb0_n = lane_b0, lb1_n = lane_b1;
@@ -382,13 +377,31 @@ __global__ __launch_bounds__(256, 1) void k_fine_bwd_dkv(int Nc, int K, float sl
       const unsigned char* D1 = Q1 + TL::BYTES;
       const unsigned char* Q2 = smem + (S2 & 1) * STAGE;
       const unsigned char* D2 = Q2 + TL::BYTES;
-      bf16x8 qa[KS], da[KS], la, dla, pbn0, pbn1, sbn0, sbn1;
+      bf16x8 qa[KS], da[KS], la, dla;
       float pn[16], dsn[16];
-      uint4 pu0, pu1, su0, su1;
-      float2 row;
+      uint4 pu0, pu1, su0, su1, rowv;
       auto value = [&](int i) {
         pn[i] = fast_exp2(sA[i] * sl2);
         dsn[i] = pn[i] * dpA[i];
+      };
+      // values [lo, hi) of P, dS; each finished pair is packed at once (few fp32 values stay live)
+      auto value_step = [&](int lo, int hi) {
+#pragma unroll
+        for (int e = lo; e < hi; ++e) {
+          value(e);
+          if (e & 1) {
+            const uint32_t pp = pack_bf16(pn[e - 1], pn[e]), ss = pack_bf16(dsn[e - 1], dsn[e]);
+            uint4& pu = e < 8 ? pu0 : pu1;
+            uint4& su = e < 8 ? su0 : su1;
+            const int w = (e >> 1) & 3;
+            if (w == 0) pu.x = pp, su.x = ss;
+            if (w == 1) pu.y = pp, su.y = ss;
+            if (w == 2) pu.z = pp, su.z = ss;
+            if (w == 3) pu.w = pp, su.w = ss;
+            // pure arithmetic has no place of its own in the instruction order: tie it to this step
+            asm volatile("" : : "v"(pp), "v"(ss));
+          }
+        }
       };
 
 #pragma unroll
@@ -400,31 +413,21 @@ __global__ __launch_bounds__(256, 1) void k_fine_bwd_dkv(int Nc, int K, float sl
         if (sub == 3) dka[x] = mfma32(qt[x][1], sb1, dka[x]);
         if (i < KS) qa[i] = TL::rowmajor_at(Q2, la_2, i);
         else da[i - KS] = TL::rowmajor_at(D2, la_2, i - KS);
-        if (i == 0) row = ((const float2*)(smem + S2 * STAGE + 2 * TL::BYTES))[qh * 32 + l32];
-        if (i < TL::IPW) lds_dma16(gq, goff[i], lq + (unsigned)i * 1024u);
-        else if (i < 2 * TL::IPW) lds_dma16(gd, goff[i - TL::IPW], lq + TL::BYTES + (unsigned)(i - TL::IPW) * 1024u);
-        else if (i == 2 * TL::IPW) lds_dma4(gl, (unsigned)((wave & 1) * 256 + lane * 4), ll);
-        constexpr int VPC = 16 / NA;  // P, dS values per step (all of tile t+1: S', dP' of it die here)
-#pragma unroll
-        for (int u = 0; u < VPC; ++u) {
-          const int e = i * VPC + u;
-          value(e);
-          if (e & 1) {  // pack each pair at once: few fp32 values stay live
-            const uint32_t pp = pack_bf16(pn[e - 1], pn[e]), ss = pack_bf16(dsn[e - 1], dsn[e]);
-            uint4& pu = e < 8 ? pu0 : pu1;
-            uint4& su = e < 8 ? su0 : su1;
-            const int w = (e >> 1) & 3;
-            if (w == 0) pu.x = pp, su.x = ss;
-            if (w == 1) pu.y = pp, su.y = ss;
-            if (w == 2) pu.z = pp, su.z = ss;
-            if (w == 3) pu.w = pp, su.w = ss;
-          }
-        }
+        if (i == 0) rowv = row_read(smem + S2 * STAGE);
+        // copies of tile t+4: one M0 value per tensor, the 1 KiB steps ride in the instruction offset
+        if (i == 0) set_m0(lq);
+        if (i == TL::IPW) set_m0(lq + TL::BYTES);
+        if (i < 2 * TL::IPW) {
+          const void* g = i < TL::IPW ? gq : gd;
+          const int r = i % TL::IPW;
+          if (r == 0) lds_dma16_at<0>(g, goff_im[0]);
+          if (r == 1) lds_dma16_at<1024>(g, goff_im[1 % TL::IPW]);
+          if (r == 2) lds_dma16_at<2048>(g, goff_im[2 % TL::IPW]);
+          if (r == 3) lds_dma16_at<3072>(g, goff_im[3 % TL::IPW]);
+        } else if (i == 2 * TL::IPW) lds_dma4(gl, (unsigned)(wave * 256 + lane * 4), ll);
+        value_step(i * 16 / NA, (i + 1) * 16 / NA);  // P, dS of tile t+1 (S', dP' of it die here)
         __builtin_amdgcn_sched_barrier(0);
       }
-      pbn0 = __builtin_bit_cast(bf16x8, pu0), pbn1 = __builtin_bit_cast(bf16x8, pu1);
-      sbn0 = __builtin_bit_cast(bf16x8, su0), sbn1 = __builtin_bit_cast(bf16x8, su1);
-
       f32x16 sN, dpN;
 #pragma unroll
       for (int i = 0; i < NB; ++i) {
@@ -436,13 +439,16 @@ __global__ __launch_bounds__(256, 1) void k_fine_bwd_dkv(int Nc, int K, float sl
           if (which < 2) dt[x][which] = TL::transposed_at(D1, lb0_1, lb1_1, which, x);
           else qt[x][which - 2] = TL::transposed_at(Q1, lb0_1, lb1_1, which - 2, x);
         }
-        if (i == 0) split3(-row.x * inv_sl2, la, 1.f);
-        if (i == 2) split3(-row.y, dla, 0.f);
+        if (i == NB - 4) {  // the operands of the two bias steps are put together here, not earlier
+          asm volatile("" : "+v"(rowv.x), "+v"(rowv.y), "+v"(rowv.z), "+v"(rowv.w));
+          row_slots(rowv, la, dla);
+        }
         __builtin_amdgcn_sched_barrier(0);
       }
       sA = sN;
       dpA = dpN;
-      pb0 = pbn0, pb1 = pbn1, sb0 = sbn0, sb1 = sbn1;
+      pb0 = __builtin_bit_cast(bf16x8, pu0), pb1 = __builtin_bit_cast(bf16x8, pu1);
+      sb0 = __builtin_bit_cast(bf16x8, su0), sb1 = __builtin_bit_cast(bf16x8, su1);
     };
 
     for (int t = beg; t < end; t += 4) {
@@ -492,18 +498,18 @@ __global__ __launch_bounds__(256, 1) void k_fine_bwd_dkv(int Nc, int K, float sl
 }
 
 hipError_t launch_fine_bwd_dkv(int BH, int Nc, int d, int K, float scale, const void* q, const void* k, const void* v,
-                               const void* dof, const int32_t* row_ptr, const int32_t* col, const float* ld,
+                               const void* dof, const int32_t* row_ptr, const int32_t* col, const void* ldb,
                                const float* dkc, const float* dvc, const uint64_t* mask, void* dk,
                                void* dv, hipStream_t s) {
   const float sl2 = scale * kLog2e;
   const unsigned grid = (unsigned)(BH * Nc);
   if (d == 128)
     k_fine_bwd_dkv<128><<<grid, 256, 0, s>>>(Nc, K, sl2, scale, (const uint4*)q, (const uint4*)k, (const uint4*)v,
-                                             (const uint4*)dof, row_ptr, col, ld, dkc, dvc, mask, (uint4*)dk,
+                                             (const uint4*)dof, row_ptr, col, (const uint4*)ldb, dkc, dvc, mask, (uint4*)dk,
                                              (uint4*)dv);
   else
     k_fine_bwd_dkv<64><<<grid, 256, 0, s>>>(Nc, K, sl2, scale, (const uint4*)q, (const uint4*)k, (const uint4*)v,
-                                            (const uint4*)dof, row_ptr, col, ld, dkc, dvc, mask, (uint4*)dk,
+                                            (const uint4*)dof, row_ptr, col, (const uint4*)ldb, dkc, dvc, mask, (uint4*)dk,
                                             (uint4*)dv);
   return hipGetLastError();
 }

@@ -30,6 +30,15 @@ __device__ __forceinline__ void lds_dma16(const void* base, unsigned voff, unsig
                : "v"(voff), "s"(base), "s"(lds_addr)
                : "memory", "m0");
 }
+// The same with an immediate byte offset, which the instruction adds to BOTH addresses (global and
+// LDS): a run of copies whose LDS targets are IMM apart then shares one M0 value, the callers
+// compensating in the per-lane global offsets.  0 <= IMM < 4096.
+template <int IMM>
+__device__ __forceinline__ void lds_dma16_at(const void* base, unsigned voff) {
+  static_assert(IMM >= 0 && IMM < 4096, "13-bit signed instruction offset");
+  asm volatile("global_load_lds_dwordx4 %0, %1 offset:%2" : : "v"(voff), "s"(base), "n"(IMM) : "memory");
+}
+__device__ __forceinline__ void set_m0(unsigned lds_addr) { asm volatile("s_mov_b32 m0, %0" : : "s"(lds_addr) : "m0", "memory"); }
 __device__ __forceinline__ void lds_dma4(const void* base, unsigned voff, unsigned lds_addr) {
   asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dword %0, %1"
                :

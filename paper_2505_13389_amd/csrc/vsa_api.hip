@@ -78,7 +78,7 @@ FwdWs carve_fwd(const vsa_params_t* p, const Geo& g, void* ws) {
 struct BwdWs {
   uint64_t* mask;
   float *qc, *kc, *vc, *ld, *doc, *ac, *dsc, *dqc, *dkc, *dvc;
-  void* dof;
+  void *dof, *ldb;
   int32_t *row_ptr, *col;
   size_t bytes;
 };
@@ -91,6 +91,7 @@ BwdWs carve_bwd(const vsa_params_t* p, const Geo& g, void* ws) {
   w.kc = c.take<float>(bh * g.Nc * p->d);
   w.vc = c.take<float>(bh * g.Nc * p->d);
   w.ld = c.take<float>(2 * bh * g.Np);
+  w.ldb = c.take<uint32_t>(4 * bh * g.Np);
   w.doc = c.take<float>(bh * g.Nc * p->d);
   w.ac = c.take<float>(bh * g.Nc * g.Nc);
   w.dsc = c.take<float>(bh * g.Nc * g.Nc);
@@ -224,13 +225,13 @@ int vsa_backward(const vsa_params_t* p, const void* q, const void* k, const void
   VSA_TRY("cube_masks", vsa::launch_cube_masks(g, w.mask, s));
   VSA_TRY("pool", vsa::launch_pool(g, BH, p->d, w.mask, q, k, v, w.qc, w.kc, w.vc, s));
   VSA_TRY("bwd_pre", vsa::launch_bwd_pre(BH, g.Nc, p->d, w.mask, dout, gate_c, gate_f, out_fine, out_coarse, dgate_c, dgate_f,
-                              w.dof, w.ld, w.doc, lse_fine, s));
+                              w.dof, w.ld, w.ldb, scale, w.doc, lse_fine, s));
   VSA_TRY("coarse_bwd", vsa::launch_coarse_bwd(BH, g.Nc, p->d, scale, w.qc, w.kc, w.vc, lse_coarse, w.doc, w.ac, w.dsc, w.dqc, w.dkc,
                                  w.dvc, s));
   VSA_TRY("transpose_map", vsa::launch_transpose_map(BH, g.Nc, p->topk, block_idx, w.row_ptr, w.col, s));
   VSA_TRY("fine_bwd_dq", vsa::launch_fine_bwd_dq(BH, g.Nc, p->d, p->topk, scale, q, k, v, w.dof, block_idx, w.ld,
                                   w.dqc, w.mask, dq, s));
-  VSA_TRY("fine_bwd_dkv", vsa::launch_fine_bwd_dkv(BH, g.Nc, p->d, p->topk, scale, q, k, v, w.dof, w.row_ptr, w.col, w.ld, w.dkc,
+  VSA_TRY("fine_bwd_dkv", vsa::launch_fine_bwd_dkv(BH, g.Nc, p->d, p->topk, scale, q, k, v, w.dof, w.row_ptr, w.col, w.ldb, w.dkc,
                                    w.dvc, w.mask, dk, dv, s));
   return VSA_OK;
 }

@@ -18,7 +18,7 @@ hipError_t launch_fine_fwd(int BH, int Nc, int d, int K, float scale, const void
 // backward
 hipError_t launch_bwd_pre(int BH, int Nc, int d, const uint64_t* mask, const void* dout, const void* gate_c,
                           const void* gate_f, const void* out_fine, const float* oc, void* dgate_c, void* dgate_f,
-                          void* dof, float* ld, float* doc, const float* lse_f, hipStream_t s);
+                          void* dof, float* ld, void* ldb, float scale, float* doc, const float* lse_f, hipStream_t s);
 hipError_t launch_coarse_bwd(int BH, int Nc, int d, float scale, const float* qc, const float* kc, const float* vc,
                              const float* lse_c, const float* doc, float* ac, float* dsc, float* dqc, float* dkc,
                              float* dvc,
@@ -29,7 +29,7 @@ hipError_t launch_fine_bwd_dq(int BH, int Nc, int d, int K, float scale, const v
                               const void* dof, const int32_t* idx, const float* ld,
                               const float* dqc, const uint64_t* mask, void* dq, hipStream_t s);
 hipError_t launch_fine_bwd_dkv(int BH, int Nc, int d, int K, float scale, const void* q, const void* k, const void* v,
-                               const void* dof, const int32_t* row_ptr, const int32_t* col, const float* ld,
+                               const void* dof, const int32_t* row_ptr, const int32_t* col, const void* ldb,
                                const float* dkc, const float* dvc, const uint64_t* mask, void* dk,
                                void* dv, hipStream_t s);
 
