@@ -19,7 +19,9 @@
  *   - Pad slots (tiled rows outside the valid grid) are defined by geometry alone.  They
  *     are never keys, are excluded from pooled means, and their rows of every output and
  *     gradient are written as zero; whatever finite values the caller stores there in an
- *     input are ignored.
+ *     input are ignored (NaN or Inf there is not allowed).
+ *   - Value range: raw dot products |q . k| of token pairs must stay below 15000 (the pad
+ *     keys of a partially filled cube are removed by adding -30000 to their raw logits).
  *   - Results are deterministic (bit-identical across calls on the same inputs).
  *   - Return value: VSA_OK (0) or a negative vsa_status.  Validation errors are detected
  *     before anything is enqueued; VSA_ERR_HIP (a launch rejected by the runtime) can leave
