@@ -21,6 +21,13 @@ namespace vsa {
 constexpr float kMaskBias = -30000.f;  // added to the raw logits of pad keys (|q.k| is assumed < 15000)
 constexpr float kTau = 8.f;             // lazy-rescale threshold, log2 units
 
+// max over both lane halves (lanes l and l^32) with one cross-lane VALU instruction instead of a
+// round trip through the LDS permute path
+__device__ __forceinline__ float max_across_halves(float x) {
+  auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+
 template <int D>
 __global__ __launch_bounds__(256, 2) void k_fine_fwd(int Nc, int K, float sl2, const uint4* __restrict__ q,
                                                      const uint4* __restrict__ k, const uint4* __restrict__ v,
@@ -145,7 +152,7 @@ __global__ __launch_bounds__(256, 2) void k_fine_fwd(int Nc, int K, float sl2, c
 #pragma unroll
     for (int i = 3; i < 15; i += 2) mx = fmaxf(fmaxf(mx, sacc[i]), sacc[i + 1]);
     mx = fmaxf(mx, sacc[15]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    mx = max_across_halves(mx);
     if (partial && mx < 0.5f * kMaskBias) mx = -INFINITY;  // every key of this half is a pad
     const float mx2 = mx * sl2;
     if (__any(mx2 > mref + kTau)) {
