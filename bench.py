@@ -72,6 +72,34 @@ def time_steps(fn, steps, warmup, torch):
     return (time.perf_counter() - t0) * 1e3 / steps
 
 
+def event_times(fn, n, torch, before=None):
+    """n calls of fn, each bracketed by a pair of events on the current stream; ms per call."""
+    out = []
+    for _ in range(n):
+        if before is not None:
+            before()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        fn()
+        b.record()
+        b.synchronize()
+        out.append(a.elapsed_time(b))
+    return out
+
+
+def mfma_rate(torch, vsa):
+    """Sustained v_mfma_f32_32x32x16_bf16 rate of this chip on N(0,1) operands, TFLOP/s."""
+    g = torch.Generator(device="cuda")
+    g.manual_seed(1)
+    ops = torch.randn(32768, generator=g, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    wgs, iters = 1024, 4000
+    sink = torch.empty(wgs * 256, device="cuda", dtype=torch.float32)
+    fl = vsa.vsa_bench_mfma_rate(ops, sink, wgs, iters)  # warm-up
+    torch.cuda.synchronize()
+    ms = min(event_times(lambda: vsa.vsa_bench_mfma_rate(ops, sink, wgs, iters), 3, torch))
+    return fl / (ms * 1e-3) / 1e12
+
+
 def cpu_baseline(wl, seed):
     """The oracle (fp32 build, as it stands) on a few heads of the same workload, forward+backward."""
     import numpy as np
@@ -123,6 +151,11 @@ def main():
 
     ms = time_steps(step, args.steps, args.warmup, torch)
     ms_fwd = time_steps(lambda: buf.forward(*a), args.steps, 1, torch)
+    # the same step timed one by one (events), warm and with L2 / Infinity Cache swept before each
+    per_step = sorted(event_times(step, args.steps, torch))
+    sweep = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+    cold = sorted(event_times(step, max(3, args.steps // 4), torch, before=lambda: sweep.fill_(1)))
+    del sweep
 
     # the same steps again with every kernel bracketed by HIP events on the launch stream
     vsa.vsa_profile_begin(32 * args.steps)
@@ -164,6 +197,8 @@ def main():
     ms_perm = time_steps(permutes, max(2, args.steps // 4), 1, torch)
     dev["raster_q"].copy_(raster_keep)
 
+    rate = mfma_rate(torch, vsa)
+
     speedup = None
     if not args.no_dense:
         dense_wl = Workload(wl.name + "_dense", wl.B, wl.H, wl.T, wl.Hh, wl.W, wl.d, buf.Nc, wl.cube, wl.planted)
@@ -183,6 +218,11 @@ def main():
         "config": {"workload": f"{wl.name}: B={wl.B} H={wl.H} grid={wl.T}x{wl.Hh}x{wl.W} (Np={buf.Np}, Nc={buf.Nc}) "
                                f"d={wl.d} topk={wl.topk}, forward+backward, tiled layout resident in HBM"},
         "pct_of_bf16_peak": round(100.0 * tflops / PEAK_BF16_TFLOPS, 2),
+        "measured_mfma_tflops_random_operands": round(rate, 1),
+        "pct_of_measured_mfma_rate": round(100.0 * tflops / rate, 2),
+        "value_valid_tokens_only": round(tflops * (wl.L / buf.Np) ** 2, 2),
+        "ms_per_step_median": round(per_step[len(per_step) // 2], 4), "ms_per_step_min": round(per_step[0], 4),
+        "ms_per_step_cold_cache_median": round(cold[len(cold) // 2], 4),
         "fwd_ms": round(ms_fwd, 4), "fwd_tflops": round(fwd_flops / (ms_fwd * 1e-3) / 1e12, 2),
         "speedup_vs_dense": None if speedup is None else round(speedup, 2),
         "ideal_speedup_vs_dense": round(buf.Nc / wl.topk, 2),

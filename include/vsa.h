@@ -123,6 +123,17 @@ const char* vsa_profile_name(int i);
 float vsa_profile_ms(int i);
 int vsa_profile_end(void);
 
+/* Sustained matrix-core rate of the chip, for benchmarks (not part of the paper's method):
+ * enqueues ONE kernel that does nothing but v_mfma_f32_32x32x16_bf16 on operands taken from
+ * `operands` (DEVICE, 16-byte aligned, at least 65536 bytes of bf16 values; their statistics
+ * matter: the clock the chip holds depends on the operand bits), 4 wavefronts per workgroup,
+ * `workgroups` workgroups, `iters` x 32 instructions per wavefront, and writes one float per
+ * thread to `sink` (DEVICE, workgroups*256 floats).  *flops receives the number of floating
+ * point operations of that launch (HOST pointer).  The caller times the launch.
+ * Errors: VSA_ERR_NULL, VSA_ERR_BAD_ARG (non-positive counts), VSA_ERR_ALIGN, VSA_ERR_HIP. */
+int vsa_bench_mfma_rate(const void* operands, float* sink, int workgroups, int iters, double* flops,
+                        void* hip_stream);
+
 /* Human-readable name of a status code (static string, never NULL). */
 const char* vsa_status_string(int status);
 

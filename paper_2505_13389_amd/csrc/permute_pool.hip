@@ -110,4 +110,42 @@ hipError_t launch_pool(const Geo& g, int BH, int d, const uint64_t* mask, const 
   return hipGetLastError();
 }
 
+// ---------------------------------------------------------------------------------------------
+// Matrix-core rate probe for benchmarks: 4 wavefronts per workgroup, each running `iters` x 32
+// v_mfma_f32_32x32x16_bf16 on 8 + 8 operands fetched once from `operands` (4 accumulators, 8-deep
+// dependent chains, which the pipe runs at full rate).  No memory traffic inside the loop.
+typedef __bf16 rate_bf16x8 __attribute__((ext_vector_type(8)));
+typedef float rate_f32x16 __attribute__((ext_vector_type(16)));
+__global__ __launch_bounds__(256) void k_mfma_rate(const uint4* __restrict__ operands, float* __restrict__ sink,
+                                                   int iters) {
+  rate_bf16x8 a[8], b[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    a[j] = __builtin_bit_cast(rate_bf16x8, operands[(threadIdx.x * 16 + j) & 4095]);
+    b[j] = __builtin_bit_cast(rate_bf16x8, operands[(threadIdx.x * 16 + 8 + j) & 4095]);
+  }
+  rate_f32x16 c[4];
+#pragma unroll
+  for (int x = 0; x < 4; ++x)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) c[x][i] = 0.f;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int x = 0; x < 4; ++x)
+#pragma unroll
+      for (int j = 0; j < 8; ++j) c[x] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[j], b[(j + x) & 7], c[x], 0, 0, 0);
+  }
+  float s = 0.f;
+#pragma unroll
+  for (int x = 0; x < 4; ++x)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) s += c[x][i];
+  sink[blockIdx.x * 256 + threadIdx.x] = s;
+}
+
+hipError_t launch_mfma_rate(const void* operands, float* sink, int workgroups, int iters, hipStream_t s) {
+  k_mfma_rate<<<(unsigned)workgroups, 256, 0, s>>>((const uint4*)operands, sink, iters);
+  return hipGetLastError();
+}
+
 }  // namespace vsa

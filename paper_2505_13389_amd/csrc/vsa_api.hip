@@ -273,6 +273,14 @@ int vsa_profile_end(void) {
   return VSA_OK;
 }
 
+int vsa_bench_mfma_rate(const void* operands, float* sink, int workgroups, int iters, double* flops, void* hip_stream) {
+  if (!operands || !sink || !flops) return VSA_ERR_NULL;
+  if (workgroups < 1 || iters < 1 || workgroups > (1 << 20) || iters > (1 << 24)) return VSA_ERR_BAD_ARG;
+  if (misaligned(operands) || misaligned(sink)) return VSA_ERR_ALIGN;
+  *flops = (double)workgroups * 4.0 * (double)iters * 32.0 * (2.0 * 32 * 32 * 16);
+  return vsa::launch_mfma_rate(operands, sink, workgroups, iters, (hipStream_t)hip_stream) == hipSuccess ? VSA_OK : VSA_ERR_HIP;
+}
+
 const char* vsa_status_string(int status) {
   switch (status) {
     case VSA_OK: return "ok";

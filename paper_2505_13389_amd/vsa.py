@@ -18,7 +18,7 @@ STATUS = {0: "VSA_OK", -1: "VSA_ERR_NULL", -2: "VSA_ERR_BAD_ARG", -3: "VSA_ERR_U
           -5: "VSA_ERR_WORKSPACE", -6: "VSA_ERR_HIP"}
 EXPORTS = ["vsa_padded_tokens", "vsa_workspace_bytes", "vsa_tile_permute", "vsa_forward", "vsa_backward",
            "vsa_status_string", "vsa_profile_begin", "vsa_profile_count", "vsa_profile_name", "vsa_profile_ms",
-           "vsa_profile_end"]
+           "vsa_profile_end", "vsa_bench_mfma_rate"]
 
 
 class VsaParams(C.Structure):
@@ -55,6 +55,7 @@ def lib():
         L.vsa_forward.restype = C.c_int
         L.vsa_backward.argtypes = [C.POINTER(VsaParams)] + [vp] * 17 + [C.c_size_t, vp]
         L.vsa_backward.restype = C.c_int
+        L.vsa_bench_mfma_rate.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.POINTER(C.c_double), C.c_void_p]
         L.vsa_profile_begin.argtypes = [C.c_int]
         L.vsa_profile_name.argtypes = [C.c_int]
         L.vsa_profile_name.restype = C.c_char_p
@@ -162,6 +163,16 @@ class Buffers:
         vsa_backward(self.pb, q, k, v, gate_c, gate_f, dout, self.block_idx, self.out_fine, self.lse_fine,
                      self.out_coarse, self.lse_coarse, self.dq, self.dk, self.dv, self.dgate_c, self.dgate_f,
                      self.workspace)
+
+
+def vsa_bench_mfma_rate(operands: torch.Tensor, sink: torch.Tensor, workgroups: int, iters: int) -> float:
+    """Enqueues the matrix-core rate probe on the current stream; returns the flops of the launch."""
+    assert operands.numel() * operands.element_size() >= 65536 and sink.numel() >= workgroups * 256
+    fl = C.c_double(0.0)
+    rc = lib().vsa_bench_mfma_rate(_p(operands), _p(sink), workgroups, iters, C.byref(fl), _stream())
+    if rc:
+        raise VsaError("vsa_bench_mfma_rate", rc)
+    return fl.value
 
 
 def vsa_profile_begin(max_records: int):
