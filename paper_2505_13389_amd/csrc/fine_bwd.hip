@@ -80,6 +80,10 @@ __global__ __launch_bounds__(256, 2) void k_fine_bwd_dq(int Nc, int K, float sl2
 #pragma unroll
     for (int i = 0; i < 16; ++i) acc[x][i] = 0.f;
 
+  const int lane_a = TL::rowmajor_lane(kh * 32, lane);
+  int lane_b0, lane_b1;
+  TL::transposed_lane(kh * 32, lane, lane_b0, lane_b1);
+
   // Per tile: wait for this wave's share of tile t, barrier (tile t complete, and every wave is
   // done with tile t-1), start the copy of tile t+1 into the other stage, do the math on tile t.
   auto body = [&](const unsigned char* cur, unsigned char* nxt, int t) {
@@ -96,13 +100,34 @@ __global__ __launch_bounds__(256, 2) void k_fine_bwd_dq(int Nc, int K, float sl2
     const unsigned char* Ks = cur;
     const unsigned char* Vs = cur + TL::BYTES;
 
+    // The LDS operands are requested a fixed number of matrix instructions ahead of their use, in
+    // a pinned order (left to itself the compiler reads, waits and multiplies one operand at a
+    // time).  Operand i: K rows (S^T steps), then V rows (dP^T steps), then transposed K (dQ^T
+    // steps).  Operand addresses are rebuilt from three lane-dependent values (one XOR per read)
+    // rather than held in registers across the loop: the register file is the scarce resource.
+    int la = lane_a, lb0 = lane_b0, lb1 = lane_b1;
+    asm volatile("" : "+v"(la), "+v"(lb0), "+v"(lb1));
+    constexpr int NOP = 2 * KS + 2 * DVB, AHEAD = 4;
+    bf16x8 op[NOP];
+    auto read_op = [&](int i) {
+      if (i < KS) return TL::rowmajor_at(Ks, la, i);
+      if (i < 2 * KS) return TL::rowmajor_at(Vs, la, i - KS);
+      const int j = i - 2 * KS;
+      return TL::transposed_at(Ks, lb0, lb1, j & 1, j >> 1);
+    };
+#pragma unroll
+    for (int i = 0; i < AHEAD; ++i) op[i] = read_op(i);
+    __builtin_amdgcn_sched_barrier(0);
     f32x16 sacc, dpacc;
 #pragma unroll
     for (int i = 0; i < 16; ++i) { sacc[i] = 0.f; dpacc[i] = 0.f; }
 #pragma unroll
-    for (int s = 0; s < KS; ++s) sacc = mfma32(TL::rowmajor_operand(Ks, kh * 32, s, lane), qreg[s], sacc);
-#pragma unroll
-    for (int s = 0; s < KS; ++s) dpacc = mfma32(TL::rowmajor_operand(Vs, kh * 32, s, lane), doreg[s], dpacc);
+    for (int i = 0; i < 2 * KS; ++i) {
+      if (i < KS) sacc = mfma32(op[i], qreg[i < KS ? i : 0], sacc);
+      else dpacc = mfma32(op[i], doreg[i < KS ? 0 : i - KS], dpacc);
+      if (i + AHEAD < NOP) op[i + AHEAD] = read_op(i + AHEAD);
+      __builtin_amdgcn_sched_barrier(0);
+    }
 
     float ds[16];
 #pragma unroll
@@ -114,9 +139,11 @@ __global__ __launch_bounds__(256, 2) void k_fine_bwd_dq(int Nc, int K, float sl2
     }
     const bf16x8 b0 = acc_to_operand(ds), b1 = acc_to_operand(ds + 8);
 #pragma unroll
-    for (int x = 0; x < DVB; ++x) {
-      acc[x] = mfma32(TL::transposed_operand(Ks, kh * 32, 0, x * 32, lane), b0, acc[x]);
-      acc[x] = mfma32(TL::transposed_operand(Ks, kh * 32, 1, x * 32, lane), b1, acc[x]);
+    for (int j = 0; j < 2 * DVB; ++j) {
+      const int i = 2 * KS + j;
+      acc[j >> 1] = mfma32(op[i], (j & 1) ? b1 : b0, acc[j >> 1]);
+      if (i + AHEAD < NOP) op[i + AHEAD] = read_op(i + AHEAD);
+      __builtin_amdgcn_sched_barrier(0);
     }
   };
 
