@@ -48,6 +48,7 @@ typedef enum {
 } vsa_status;
 
 #define VSA_FLAG_INDICES_GIVEN 1u /* vsa_forward: block_idx is an INPUT, top-K is skipped */
+#define VSA_FLAG_RASTER_BLHD 2u   /* vsa_tile_permute: the raster tensor is token-major [B,L,H,d] */
 #define VSA_MAX_CUBES 4096        /* largest supported Nc                                 */
 
 typedef struct {
@@ -72,6 +73,10 @@ size_t vsa_workspace_bytes(const vsa_params_t* p, int backward);
  * tile()/untile()).
  *   inverse == 0: src [B,H,T*Hh*W,d] raster -> dst [B,H,Np,d] tiled, pad rows zero-filled.
  *   inverse != 0: src [B,H,Np,d] tiled -> dst [B,H,T*Hh*W,d] raster, pad rows dropped.
+ * With VSA_FLAG_RASTER_BLHD in p->flags the raster tensor (src or dst, by direction) is laid
+ * out [B, T*Hh*W, H, d] instead: the layout of the projections around the attention
+ * ("b h l d <-> b l (h d)" at both ends of the App. B listing), so that the head transpose
+ * rides on the permutation instead of costing a pass of its own.  The tiled side is unchanged.
  * src and dst must not overlap. */
 int vsa_tile_permute(const vsa_params_t* p, const void* src, void* dst, int inverse, void* hip_stream);
 

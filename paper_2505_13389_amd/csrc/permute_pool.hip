@@ -7,9 +7,10 @@ namespace vsa {
 // One thread per 16-byte chunk of a destination row.
 // Forward: destination = tiled row; its source is the raster row of the same (t,h,w), or
 // zeros for a pad slot.  Inverse: destination = raster row.  (Sec. 2.2 index equation.)
+// H > 0: the raster tensor is [B, L, H, d] (token-major); H == 0: [B, H, L, d].
 template <bool kInverse>
-__global__ __launch_bounds__(256) void k_tile_permute(Geo g, int BH, int chunks_per_row, const uint4* __restrict__ src,
-                                                      uint4* __restrict__ dst) {
+__global__ __launch_bounds__(256) void k_tile_permute(Geo g, int BH, int H, int chunks_per_row,
+                                                      const uint4* __restrict__ src, uint4* __restrict__ dst) {
   const long long rows_dst = kInverse ? (long long)g.L : g.Np;
   const long long total = (long long)BH * rows_dst * chunks_per_row;
   long long gid = (long long)blockIdx.x * blockDim.x + threadIdx.x;
@@ -26,25 +27,28 @@ __global__ __launch_bounds__(256) void k_tile_permute(Geo g, int BH, int chunks_
     uint4 val = make_uint4(0, 0, 0, 0);
     if (t < g.T && h < g.Hh && w < g.W) {
       long long nr = ((long long)t * g.Hh + h) * g.W + w;
-      val = src[(bh * g.L + nr) * chunks_per_row + ch];
+      const long long rr = H > 0 ? ((bh / H) * g.L + nr) * H + bh % H : bh * g.L + nr;
+      val = src[rr * chunks_per_row + ch];
     }
     dst[gid] = val;
   } else {
     int w = n % g.W, h = (n / g.W) % g.Hh, t = n / (g.W * g.Hh);
     long long c = ((long long)(t / g.Ct) * g.Nh + (h / g.Ch)) * g.Nw + (w / g.Cw);
     int in = ((t % g.Ct) * g.Ch + (h % g.Ch)) * g.Cw + (w % g.Cw);
-    dst[gid] = src[(bh * g.Np + c * kTile + in) * chunks_per_row + ch];
+    const long long rr = H > 0 ? ((bh / H) * g.L + n) * H + bh % H : bh * g.L + n;
+    dst[rr * chunks_per_row + ch] = src[(bh * g.Np + c * kTile + in) * chunks_per_row + ch];
   }
 }
 
-hipError_t launch_tile_permute(const Geo& g, int BH, int d, const void* src, void* dst, bool inverse, hipStream_t s) {
+hipError_t launch_tile_permute(const Geo& g, int BH, int H_blhd, int d, const void* src, void* dst, bool inverse,
+                               hipStream_t s) {
   int cpr = d / 8;
   long long total = (long long)BH * (inverse ? (long long)g.L : g.Np) * cpr;
   unsigned blocks = (unsigned)((total + 255) / 256);
   if (inverse)
-    k_tile_permute<true><<<blocks, 256, 0, s>>>(g, BH, cpr, (const uint4*)src, (uint4*)dst);
+    k_tile_permute<true><<<blocks, 256, 0, s>>>(g, BH, H_blhd, cpr, (const uint4*)src, (uint4*)dst);
   else
-    k_tile_permute<false><<<blocks, 256, 0, s>>>(g, BH, cpr, (const uint4*)src, (uint4*)dst);
+    k_tile_permute<false><<<blocks, 256, 0, s>>>(g, BH, H_blhd, cpr, (const uint4*)src, (uint4*)dst);
   return hipGetLastError();
 }
 

@@ -162,7 +162,7 @@ int vsa_tile_permute(const vsa_params_t* p, const void* src, void* dst, int inve
   if (!src || !dst) return VSA_ERR_NULL;
   if (misaligned(src) || misaligned(dst)) return VSA_ERR_ALIGN;
   hipStream_t s = (hipStream_t)hip_stream;
-  VSA_TRY("tile_permute", vsa::launch_tile_permute(g, p->B * p->H, p->d, src, dst, inverse != 0, s));
+  VSA_TRY("tile_permute", vsa::launch_tile_permute(g, p->B * p->H, (p->flags & VSA_FLAG_RASTER_BLHD) ? p->H : 0, p->d, src, dst, inverse != 0, s));
   return VSA_OK;
 }
 

@@ -5,7 +5,8 @@
 
 namespace vsa {
 
-hipError_t launch_tile_permute(const Geo& g, int BH, int d, const void* src, void* dst, bool inverse, hipStream_t s);
+hipError_t launch_tile_permute(const Geo& g, int BH, int H_blhd, int d, const void* src, void* dst, bool inverse,
+                               hipStream_t s);
 hipError_t launch_cube_masks(const Geo& g, uint64_t* mask, hipStream_t s);
 hipError_t launch_mfma_rate(const void* operands, float* sink, int workgroups, int iters, hipStream_t s);
 hipError_t launch_pool(const Geo& g, int BH, int d, const uint64_t* mask, const void* q, const void* k, const void* v,

@@ -14,6 +14,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libvsa.so")
 
 VSA_FLAG_INDICES_GIVEN = 1
+VSA_FLAG_RASTER_BLHD = 2
 STATUS = {0: "VSA_OK", -1: "VSA_ERR_NULL", -2: "VSA_ERR_BAD_ARG", -3: "VSA_ERR_UNSUPPORTED", -4: "VSA_ERR_ALIGN",
           -5: "VSA_ERR_WORKSPACE", -6: "VSA_ERR_HIP"}
 EXPORTS = ["vsa_padded_tokens", "vsa_workspace_bytes", "vsa_tile_permute", "vsa_forward", "vsa_backward",
@@ -106,8 +107,9 @@ def vsa_workspace_bytes(pb: Problem, backward: bool) -> int:
     return int(lib().vsa_workspace_bytes(C.byref(pb.params()), int(backward)))
 
 
-def vsa_tile_permute(pb: Problem, src: torch.Tensor, dst: torch.Tensor, inverse: bool = False):
-    rc = lib().vsa_tile_permute(C.byref(pb.params()), _p(src), _p(dst), int(inverse), _stream())
+def vsa_tile_permute(pb: Problem, src: torch.Tensor, dst: torch.Tensor, inverse: bool = False, blhd: bool = False):
+    flags = pb.flags | (VSA_FLAG_RASTER_BLHD if blhd else 0)
+    rc = lib().vsa_tile_permute(C.byref(pb.params(flags)), _p(src), _p(dst), int(inverse), _stream())
     if rc:
         raise VsaError("vsa_tile_permute", rc)
 

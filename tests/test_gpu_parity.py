@@ -71,6 +71,26 @@ def test_tile_permute_bit_exact_and_round_trip(vsa, grid3, d):
     assert np.array_equal(back.cpu().numpy().view(np.uint16), src)
 
 
+@pytest.mark.parametrize("grid3,d", [((5, 6, 7), 64), ((21, 30, 52), 128)])
+def test_tile_permute_token_major_raster(vsa, grid3, d):
+    """[B,L,H,d] raster layout: same tiled result as transposing to [B,H,L,d] first, and back."""
+    import torch
+    wl = Workload("perm_blhd", 2, 3, *grid3, d, 1)
+    g = grid_of(wl)
+    rng = np.random.default_rng(4)
+    src = rng.integers(0, 65536, size=(wl.B, wl.L, wl.H, d), dtype=np.uint16)
+    ref = orc.tile_u16(g, np.ascontiguousarray(src.transpose(0, 2, 1, 3)))
+    pb = problem_of(wl)
+    dsrc = torch.from_numpy(src.view(np.int16)).cuda()
+    dtiled = torch.full((wl.B, wl.H, g.Np, d), 0x5555, dtype=torch.int16, device="cuda")
+    vsa.vsa_tile_permute(pb, dsrc, dtiled, inverse=False, blhd=True)
+    back = torch.full_like(dsrc, 0x2222)
+    vsa.vsa_tile_permute(pb, dtiled, back, inverse=True, blhd=True)
+    torch.cuda.synchronize()
+    assert np.array_equal(dtiled.cpu().numpy().view(np.uint16), ref)
+    assert np.array_equal(back.cpu().numpy().view(np.uint16), src)
+
+
 # ------------------------------------------------------------------------------ coarse stage + top-K
 @pytest.mark.parametrize("name", ["tiny", "tiny_dense", "tiny128", "pad64", "pad128", "one_cube", "k1", "planted"])
 def test_coarse_stage_and_topk(vsa, name):
