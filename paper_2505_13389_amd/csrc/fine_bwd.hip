@@ -337,7 +337,9 @@ __global__ __launch_bounds__(256, 1) void k_fine_bwd_dkv(int Nc, int K, float sl
     //   pb*, sb*       P and dS of tile t as bf16 operands
     //   dt, qt         transposed dOf and Q operands of tile t
     f32x16 sA, dpA;
-    bf16x8 pb0, pb1, sb0, sb1, dt[DVB][2], qt[DVB][2];
+    // P, dS operands alternate between two register sets by iteration parity (no copies to rotate them)
+    uint4 pbs[2][2], sbs[2][2];
+    bf16x8 dt[DVB][2], qt[DVB][2];
 
     fill(0, beg);
     fill(1, beg + 1);
@@ -354,8 +356,8 @@ __global__ __launch_bounds__(256, 1) void k_fine_bwd_dkv(int Nc, int K, float sl
         p[i] = fast_exp2(s0[i] * sl2);
         ds[i] = p[i] * dp0[i];
       }
-      pb0 = acc_to_operand(p), pb1 = acc_to_operand(p + 8);
-      sb0 = acc_to_operand(ds), sb1 = acc_to_operand(ds + 8);
+      pbs[0][0] = pack8(p), pbs[0][1] = pack8(p + 8);
+      sbs[0][0] = pack8(ds), sbs[0][1] = pack8(ds + 8);
 #pragma unroll
       for (int x = 0; x < DVB; ++x) {
         dt[x][0] = TL::transposed_operand(smem + TL::BYTES, qh * 32, 0, x * 32, lane);
@@ -406,7 +408,8 @@ __global__ __launch_bounds__(256, 1) void k_fine_bwd_dkv(int Nc, int K, float sl
       const unsigned char* D2 = Q2 + TL::BYTES;
       bf16x8 qa[KS], da[KS], la, dla;
       float pn[16], dsn[16];
-      uint4 pu0, pu1, su0, su1, rowv;
+      uint4 rowv;
+      constexpr int PAR = ST & 1;  // this iteration consumes set PAR and fills set PAR ^ 1
       auto value = [&](int i) {
         pn[i] = fast_exp2(sA[i] * sl2);
         dsn[i] = pn[i] * dpA[i];
@@ -418,8 +421,8 @@ __global__ __launch_bounds__(256, 1) void k_fine_bwd_dkv(int Nc, int K, float sl
           value(e);
           if (e & 1) {
             const uint32_t pp = pack_bf16(pn[e - 1], pn[e]), ss = pack_bf16(dsn[e - 1], dsn[e]);
-            uint4& pu = e < 8 ? pu0 : pu1;
-            uint4& su = e < 8 ? su0 : su1;
+            uint4& pu = pbs[PAR ^ 1][e >> 3];
+            uint4& su = sbs[PAR ^ 1][e >> 3];
             const int w = (e >> 1) & 3;
             if (w == 0) pu.x = pp, su.x = ss;
             if (w == 1) pu.y = pp, su.y = ss;
@@ -434,10 +437,10 @@ __global__ __launch_bounds__(256, 1) void k_fine_bwd_dkv(int Nc, int K, float sl
 #pragma unroll
       for (int i = 0; i < NA; ++i) {
         const int x = i >> 2, sub = i & 3;
-        if (sub == 0) dva[x] = mfma32(dt[x][0], pb0, dva[x]);
-        if (sub == 1) dva[x] = mfma32(dt[x][1], pb1, dva[x]);
-        if (sub == 2) dka[x] = mfma32(qt[x][0], sb0, dka[x]);
-        if (sub == 3) dka[x] = mfma32(qt[x][1], sb1, dka[x]);
+        if (sub == 0) dva[x] = mfma32(dt[x][0], __builtin_bit_cast(bf16x8, pbs[PAR][0]), dva[x]);
+        if (sub == 1) dva[x] = mfma32(dt[x][1], __builtin_bit_cast(bf16x8, pbs[PAR][1]), dva[x]);
+        if (sub == 2) dka[x] = mfma32(qt[x][0], __builtin_bit_cast(bf16x8, sbs[PAR][0]), dka[x]);
+        if (sub == 3) dka[x] = mfma32(qt[x][1], __builtin_bit_cast(bf16x8, sbs[PAR][1]), dka[x]);
         if (i < KS) qa[i] = TL::rowmajor_at(Q2, la_2, i);
         else da[i - KS] = TL::rowmajor_at(D2, la_2, i - KS);
         if (i == 0) rowv = row_read(smem + S2 * STAGE);
@@ -474,8 +477,6 @@ __global__ __launch_bounds__(256, 1) void k_fine_bwd_dkv(int Nc, int K, float sl
       }
       sA = sN;
       dpA = dpN;
-      pb0 = __builtin_bit_cast(bf16x8, pu0), pb1 = __builtin_bit_cast(bf16x8, pu1);
-      sb0 = __builtin_bit_cast(bf16x8, su0), sb1 = __builtin_bit_cast(bf16x8, su1);
     };
 
     for (int t = beg; t < end; t += 4) {
