@@ -128,14 +128,16 @@ hipError_t launch_bwd_pre(int BH, int Nc, int d, const uint64_t* mask, const voi
 // The summation order over k is fixed, so results are deterministic.
 typedef float f32x16g __attribute__((ext_vector_type(16)));
 
-__device__ __forceinline__ void gemm_stage(float (*T)[36], const float* __restrict__ base, int rows_valid, int k_valid,
+// One thread's share of a 64-row x 32-k slice: 8 values.  sk == 1: 8 consecutive k of row tid/4;
+// otherwise (rows contiguous in memory) 8 consecutive rows at k = tid/8, stored transposed.
+// Out-of-range elements read as zero.  Fetch and store are separate so that the next slice can
+// be in flight (in registers) while the matrix instructions work on the current one.
+__device__ __forceinline__ void gemm_fetch(float* v, const float* __restrict__ base, int rows_valid, int k_valid,
                                            long long srow, long long sk, int tid) {
-  // T[r][kk] = base[r*srow + kk*sk] for r < rows_valid, kk < k_valid, else 0 (64 rows x 32 k)
   if (sk == 1) {
     const int r = tid >> 2, kq = (tid & 3) * 8;
     const float* p = base + r * srow + kq;
     const bool vec = (r < rows_valid) && (kq + 8 <= k_valid) && ((srow & 3) == 0) && ((((uintptr_t)base) & 15) == 0);
-    float v[8];
     if (vec) {
       const float4 x = *(const float4*)p, y = *(const float4*)(p + 4);
       v[0] = x.x; v[1] = x.y; v[2] = x.z; v[3] = x.w; v[4] = y.x; v[5] = y.y; v[6] = y.z; v[7] = y.w;
@@ -143,13 +145,22 @@ __device__ __forceinline__ void gemm_stage(float (*T)[36], const float* __restri
 #pragma unroll
       for (int i = 0; i < 8; ++i) v[i] = (r < rows_valid && kq + i < k_valid) ? p[i] : 0.f;
     }
-    *(float4*)&T[r][kq] = make_float4(v[0], v[1], v[2], v[3]);
-    *(float4*)&T[r][kq + 4] = make_float4(v[4], v[5], v[6], v[7]);
-  } else {  // rows contiguous in memory: coalesced reads along the row axis, transposing LDS writes
+  } else {
     const int kk = tid >> 3, rq = (tid & 7) * 8;
     const float* p = base + (long long)kk * sk + (long long)rq * srow;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) T[rq + i][kk] = (rq + i < rows_valid && kk < k_valid) ? p[i * srow] : 0.f;
+    for (int i = 0; i < 8; ++i) v[i] = (rq + i < rows_valid && kk < k_valid) ? p[i * srow] : 0.f;
+  }
+}
+__device__ __forceinline__ void gemm_store(float (*T)[36], const float* v, long long sk, int tid) {
+  if (sk == 1) {
+    const int r = tid >> 2, kq = (tid & 3) * 8;
+    *(float4*)&T[r][kq] = make_float4(v[0], v[1], v[2], v[3]);
+    *(float4*)&T[r][kq + 4] = make_float4(v[4], v[5], v[6], v[7]);
+  } else {
+    const int kk = tid >> 3, rq = (tid & 7) * 8;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) T[rq + i][kk] = v[i];
   }
 }
 
@@ -166,10 +177,17 @@ __global__ __launch_bounds__(256) void k_gemm32(int M, int N, int Kd, float alph
   f32x16g acc;
 #pragma unroll
   for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+  float va[8], vb[8];
+  gemm_fetch(va, ab, M - m0, Kd, sam, sak, tid);
+  gemm_fetch(vb, bb, N - n0, Kd, sbn, sbk, tid);
   for (int k0 = 0; k0 < Kd; k0 += 32) {
-    gemm_stage(As, ab + (long long)k0 * sak, M - m0, Kd - k0, sam, sak, tid);
-    gemm_stage(Bs, bb + (long long)k0 * sbk, N - n0, Kd - k0, sbn, sbk, tid);
+    gemm_store(As, va, sak, tid);
+    gemm_store(Bs, vb, sbk, tid);
     __syncthreads();
+    if (k0 + 32 < Kd) {  // next slice on its way while this one is multiplied
+      gemm_fetch(va, ab + (long long)(k0 + 32) * sak, M - m0, Kd - k0 - 32, sam, sak, tid);
+      gemm_fetch(vb, bb + (long long)(k0 + 32) * sbk, N - n0, Kd - k0 - 32, sbn, sbk, tid);
+    }
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const float4 av = *(const float4*)&As[wm * 32 + l32][8 * j + 4 * h];
