@@ -55,7 +55,8 @@ __global__ __launch_bounds__(256) void k_coarse_rows(int rows, int Nc, int K, fl
   if (lane == 0 && lse_c) lse_c[row] = lse;
 
   if (emit_idx) {
-    // K-th largest key by bitwise binary search: T = max{t : #(key >= t) >= K}.
+    // K-th largest key by bitwise binary search: T = max{t : #(key >= t) >= K}, stopped early once a
+    // prefix separates exactly K keys (the count is wave-uniform, so is the exit).
     uint32_t T = 0;
     for (int bit = 31; bit >= 0; --bit) {
       const uint32_t cand = T | (1u << bit);
@@ -66,7 +67,10 @@ __global__ __launch_bounds__(256) void k_coarse_rows(int rows, int Nc, int K, fl
           uint32_t key = (ch * 64 + lane < Nc) ? sortable_key(s[ch]) : 0u;
           cnt += __popcll(__ballot(key >= cand));
         }
-      if (cnt >= K) T = cand;
+      if (cnt >= K) {
+        T = cand;
+        if (cnt == K) break;  // exactly K keys at or above this prefix: the lower bits cannot change the set
+      }
     }
     int n_gt = 0;
 #pragma unroll

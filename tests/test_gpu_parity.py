@@ -242,3 +242,40 @@ def test_error_paths_return_status_and_launch_nothing(vsa):
                         None, None, None, None, buf.workspace)
     assert e.value.status == -2
     torch.cuda.synchronize()
+
+
+# ------------------------------------------------------------------------------ HIP graph replay
+def test_forward_backward_replay_from_hip_graph(vsa):
+    """The entry points only enqueue kernels (no allocation, no synchronisation, no memset nodes), so
+    a caller may capture them: every replay must reproduce the eager result bit for bit."""
+    import torch
+    wl = SMALL["pad128"]
+    dev = to_dev(tiled_bits(wl, seed=3))
+    buf = vsa.Buffers(problem_of(wl), backward=True)
+    args = (dev["q"], dev["k"], dev["v"], dev["gate_c"], dev["gate_f"])
+    outs = lambda: (buf.out, buf.block_idx, buf.out_fine, buf.lse_fine, buf.dq, buf.dk, buf.dv, buf.dgate_c, buf.dgate_f)
+    buf.forward(*args)
+    buf.backward(*args, dev["dout"])
+    torch.cuda.synchronize()
+    ref = [t.clone() for t in outs()]
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):  # warm-up on the capture stream
+        buf.forward(*args)
+        buf.backward(*args, dev["dout"])
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        buf.forward(*args)
+        buf.backward(*args, dev["dout"])
+    for rep in range(3):
+        for t in outs():  # eager work between the replays: poison every output
+            t.fill_(-1) if t.dtype == torch.int32 else t.fill_(float("nan"))
+        buf.workspace.fill_(0xFF)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for got, want in zip(outs(), ref):
+            assert torch.equal(got.view(torch.uint8), want.view(torch.uint8)), f"replay {rep} differs from the eager run"
