@@ -375,9 +375,6 @@ __global__ __launch_bounds__(256, 1) void k_fine_bwd_dkv(int Nc, int K, float sl
     //   A: dV, dK of tile t          | row-major reads of tile t+2, the copies of tile t+4,
     //                                | P, dS of tile t+1
     //   B: S', dP' of tile t+2       | transposed reads of tile t+1
-    unsigned goff_im[TL::IPW];  // per-lane source offsets less the instruction offset of copy i
-#pragma unroll
-    for (int i = 0; i < TL::IPW; ++i) goff_im[i] = goff[i] - (unsigned)i * 1024u;
     const int lane_a = TL::rowmajor_lane(qh * 32, lane);
     int lane_b0, lane_b1;
     TL::transposed_lane(qh * 32, lane, lane_b0, lane_b1);
@@ -450,10 +447,10 @@ __global__ __launch_bounds__(256, 1) void k_fine_bwd_dkv(int Nc, int K, float sl
         if (i < 2 * TL::IPW) {
           const void* g = i < TL::IPW ? gq : gd;
           const int r = i % TL::IPW;
-          if (r == 0) lds_dma16_at<0>(g, goff_im[0]);
-          if (r == 1) lds_dma16_at<1024>(g, goff_im[1 % TL::IPW]);
-          if (r == 2) lds_dma16_at<2048>(g, goff_im[2 % TL::IPW]);
-          if (r == 3) lds_dma16_at<3072>(g, goff_im[3 % TL::IPW]);
+          if (r == 0) lds_dma16_at<0>(g, goff[0]);
+          if (r == 1) lds_dma16_at<1024>(g, goff[1 % TL::IPW]);
+          if (r == 2) lds_dma16_at<2048>(g, goff[2 % TL::IPW]);
+          if (r == 3) lds_dma16_at<3072>(g, goff[3 % TL::IPW]);
         } else if (i == 2 * TL::IPW) lds_dma4(gl, (unsigned)(wave * 256 + lane * 4), ll);
         value_step(i * 16 / NA, (i + 1) * 16 / NA);  // P, dS of tile t+1 (S', dP' of it die here)
         __builtin_amdgcn_sched_barrier(0);

@@ -132,24 +132,36 @@ struct Tile {
   // then makes the whole tile visible.
   static constexpr int RPI = 1024 / ROW_BYTES;   // rows per wave instruction
   static constexpr int IPW = kTile / RPI / 4;    // instructions per wave and tile, 4 waves copying
-  // NW wavefronts share the copy of one tile; `part` in [0, NW) is this wave's share.
+  // NW wavefronts share the copy of one tile; `part` in [0, NW) is this wave's share.  The
+  // offsets come out LESS the instruction offset (i KiB) that copy i of a tile carries: the
+  // instruction adds its immediate to both the global and the LDS address, so one M0 value
+  // serves all copies of a tile.  (The source row of copy i lies at least i KiB into the tile,
+  // so the difference is never negative.)
   template <int NW = 4>
   __device__ static __forceinline__ void lane_offsets(int part, int lane, unsigned* off) {
     constexpr int N = kTile / RPI / NW;
 #pragma unroll
     for (int i = 0; i < N; ++i) {
       const int r = (part * N + i) * RPI + lane / CPR, pc = lane % CPR;
-      off[i] = (unsigned)((r * CPR + (pc ^ swz(r))) * 16);
+      off[i] = (unsigned)((r * CPR + (pc ^ swz(r))) * 16) - (unsigned)i * 1024u;
     }
+  }
+  // copy i (compile-time) of this wave's share; M0 must hold the LDS address of the share
+  template <int I>
+  __device__ static __forceinline__ void copy_step(const void* g, const unsigned* off) {
+    lds_dma16_at<I * 1024>(g, off[I]);
   }
   template <int NW = 4>
   __device__ static __forceinline__ void async_load(const uint4* __restrict__ src, long long row0, unsigned char* tile,
                                                     int part, const unsigned* off) {
     constexpr int N = kTile / RPI / NW;
+    static_assert(N >= 1 && N <= 4, "copies per wave and tile");
     const void* g = uniform_ptr(src + row0 * CPR);
-    const unsigned lds0 = __builtin_amdgcn_readfirstlane(lds_address(tile) + (unsigned)(part * N) * 1024u);
-#pragma unroll
-    for (int i = 0; i < N; ++i) lds_dma16(g, off[i], lds0 + (unsigned)i * 1024u);
+    set_m0(__builtin_amdgcn_readfirstlane(lds_address(tile) + (unsigned)(part * N) * 1024u));
+    copy_step<0>(g, off);
+    if (N > 1) copy_step<1 % N>(g, off);
+    if (N > 2) copy_step<2 % N>(g, off);
+    if (N > 3) copy_step<3 % N>(g, off);
   }
 
   // MFMA 32x32x16 operand whose 32-index is the tile ROW and whose contraction index runs
