@@ -23,6 +23,9 @@ SMALL = {
     "k1": Workload("k1", 1, 2, 8, 8, 8, 128, 1),
     "planted": Workload("planted", 1, 2, 8, 16, 16, 64, 8, planted=True),
     "planted_pad128": Workload("planted_pad128", 1, 2, 7, 14, 15, 128, 6, planted=True),
+    # other 64-token cube shapes (Sec. 3.2 ablates the tile shape; the volume is what the kernels fix)
+    "cube_2x4x8": Workload("cube_2x4x8", 1, 2, 7, 10, 20, 128, 5, cube=(2, 4, 8)),
+    "cube_1x8x8": Workload("cube_1x8x8", 1, 2, 3, 20, 17, 64, 4, cube=(1, 8, 8)),
 }
 
 
@@ -92,7 +95,8 @@ def test_tile_permute_token_major_raster(vsa, grid3, d):
 
 
 # ------------------------------------------------------------------------------ coarse stage + top-K
-@pytest.mark.parametrize("name", ["tiny", "tiny_dense", "tiny128", "pad64", "pad128", "one_cube", "k1", "planted"])
+@pytest.mark.parametrize("name", ["tiny", "tiny_dense", "tiny128", "pad64", "pad128", "one_cube", "k1", "planted",
+                                  "cube_2x4x8", "cube_1x8x8"])
 def test_coarse_stage_and_topk(vsa, name):
     wl = SMALL[name]
     bits = tiled_bits(wl, seed=1)
@@ -115,7 +119,8 @@ def test_topk_ties_go_to_the_lower_index(vsa):
 
 
 # ------------------------------------------------------------------------------ forward
-@pytest.mark.parametrize("name", ["tiny", "tiny_dense", "tiny128", "pad64", "pad128", "one_cube", "k1"])
+@pytest.mark.parametrize("name", ["tiny", "tiny_dense", "tiny128", "pad64", "pad128", "one_cube", "k1", "cube_2x4x8",
+                                  "cube_1x8x8"])
 @pytest.mark.parametrize("with_gate_f", [True, False])
 def test_forward_on_oracle_indices(vsa, name, with_gate_f):
     """The fine kernel on the oracle's own selection: a near-tie flip can neither hide nor fake an error."""
@@ -182,7 +187,8 @@ def test_forward_is_deterministic_and_ignores_pad_slots(vsa):
 
 
 # ------------------------------------------------------------------------------ backward
-@pytest.mark.parametrize("name", ["tiny", "tiny_dense", "tiny128", "pad64", "pad128", "one_cube", "k1", "planted"])
+@pytest.mark.parametrize("name", ["tiny", "tiny_dense", "tiny128", "pad64", "pad128", "one_cube", "k1", "planted",
+                                  "cube_2x4x8", "cube_1x8x8"])
 @pytest.mark.parametrize("with_gate_f", [True, False])
 def test_backward_on_oracle_indices(vsa, name, with_gate_f):
     import torch
