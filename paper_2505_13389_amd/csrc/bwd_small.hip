@@ -12,16 +12,6 @@ namespace vsa {
 //   ld_i = (lse_i * log2(e), Delta_i) as one pair per row, lse = +inf on pad rows (makes P = 0
 //          there in the fine backward kernels)
 // One workgroup per (b*h, cube); thread layout as in the pooling kernel.
-// x as bf16 hi + mid + lo (slots 0..2) and `slot3` as bf16 in slot 3 of an MFMA operand
-__device__ __forceinline__ uint2 split3_bf16(float x, float slot3) {
-  const __bf16 hi = (__bf16)x;
-  const float r1 = x - (float)hi;
-  const __bf16 mid = (__bf16)r1;
-  const __bf16 lo = (__bf16)(r1 - (float)mid);
-  auto bits = [](__bf16 v) { return (uint32_t)__builtin_bit_cast(unsigned short, v); };
-  return make_uint2(bits(hi) | (bits(mid) << 16), bits(lo) | (bits((__bf16)slot3) << 16));
-}
-
 template <int D>
 __global__ __launch_bounds__(256) void k_bwd_pre(int Nc, const uint64_t* __restrict__ mask, const uint4* __restrict__ dout,
                                                  const uint4* __restrict__ gc, const uint4* __restrict__ gf,

@@ -84,6 +84,23 @@ __global__ __launch_bounds__(256, 2) void k_fine_bwd_dq(int Nc, int K, float sl2
   int lane_b0, lane_b1;
   TL::transposed_lane(kh * 32, lane, lane_b0, lane_b1);
 
+  // Per-row terms folded into the matrix products (the vector pipe is the scarcer resource here):
+  // one extra MFMA step adds -lse2[q]/sl2 to S^T, so that P = exp2(S' * sl2), plus a large negative
+  // bias on pad keys; one extra step subtracts Delta[q] from dP^T.  Query-side operands (lane = query
+  // column, slots 0..2 = the fp32 value split into three bf16 parts, slot 3 = 1 resp. 0) are fixed for
+  // the workgroup; the key-side operand is (1, 1, 1, bias of key l%32).  Only the lane half h = 0
+  // carries contraction slots 0..7; the other half is zero.  Pad query rows (lse = +inf) get a large
+  // finite negative number: P underflows to exactly 0.
+  constexpr uint32_t kOneBits = 0x3f80u, kBiasBits = 0xc6eau;  // bf16 1.0 and bf16(-29952)
+  bf16x8 bq_s, bq_d, a_d;
+  {
+    const float inv_sl2 = 1.0f / sl2;
+    const uint2 sb = split3_bf16(lse2 == INFINITY ? -30000.f : -lse2 * inv_sl2, 1.f), db = split3_bf16(-dl, 0.f);
+    bq_s = __builtin_bit_cast(bf16x8, make_uint4(h == 0 ? sb.x : 0u, h == 0 ? sb.y : 0u, 0u, 0u));
+    bq_d = __builtin_bit_cast(bf16x8, make_uint4(h == 0 ? db.x : 0u, h == 0 ? db.y : 0u, 0u, 0u));
+    a_d = __builtin_bit_cast(bf16x8, make_uint4(h == 0 ? kOneBits * 0x10001u : 0u, h == 0 ? kOneBits : 0u, 0u, 0u));
+  }
+
   // Per tile: wait for this wave's share of tile t, barrier (tile t complete, and every wave is
   // done with tile t-1), start the copy of tile t+1 into the other stage, do the math on tile t.
   auto body = [&](const unsigned char* cur, unsigned char* nxt, int t) {
@@ -129,14 +146,17 @@ __global__ __launch_bounds__(256, 2) void k_fine_bwd_dq(int Nc, int K, float sl2
       __builtin_amdgcn_sched_barrier(0);
     }
 
+    // one more step on each product brings in the per-row terms and the pad-key bias (see bq_s)
+    {
+      const bool dead = !((mh >> l32) & 1);
+      const uint32_t w1 = kOneBits | ((dead ? kBiasBits : 0u) << 16);
+      const bf16x8 a_s = __builtin_bit_cast(bf16x8, make_uint4(h == 0 ? kOneBits * 0x10001u : 0u, h == 0 ? w1 : 0u, 0u, 0u));
+      sacc = mfma32(a_s, bq_s, sacc);
+      dpacc = mfma32(a_d, bq_d, dpacc);
+    }
     float ds[16];
 #pragma unroll
-    for (int i = 0; i < 16; ++i) ds[i] = fast_exp2(fmaf(sacc[i], sl2, -lse2)) * (dpacc[i] - dl);
-    if (mh != 0xffffffffu) {
-#pragma unroll
-      for (int i = 0; i < 16; ++i)
-        if (!((mh >> (8 * (i / 4) + 4 * h + (i % 4))) & 1)) ds[i] = 0.f;
-    }
+    for (int i = 0; i < 16; ++i) ds[i] = fast_exp2(sacc[i] * sl2) * dpacc[i];
     const bf16x8 b0 = acc_to_operand(ds), b1 = acc_to_operand(ds + 8);
 #pragma unroll
     for (int j = 0; j < 2 * DVB; ++j) {

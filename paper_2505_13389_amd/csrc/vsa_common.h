@@ -43,6 +43,16 @@ __device__ __forceinline__ uint4 pack8(const float* f) {
   return u;
 }
 
+// x as bf16 hi + mid + lo (slots 0..2) and `slot3` as bf16 in slot 3 of an MFMA operand
+__device__ __forceinline__ uint2 split3_bf16(float x, float slot3) {
+  const __bf16 hi = (__bf16)x;
+  const float r1 = x - (float)hi;
+  const __bf16 mid = (__bf16)r1;
+  const __bf16 lo = (__bf16)(r1 - (float)mid);
+  auto bits = [](__bf16 v) { return (uint32_t)__builtin_bit_cast(unsigned short, v); };
+  return make_uint2(bits(hi) | (bits(mid) << 16), bits(lo) | (bits((__bf16)slot3) << 16));
+}
+
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 __device__ __forceinline__ float fast_log2(float x) { return __builtin_amdgcn_logf(x); }
 
