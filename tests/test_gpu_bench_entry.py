@@ -22,3 +22,15 @@ def test_mfma_rate_probe_rejects_bad_arguments():
     sink = torch.zeros(256, device="cuda")
     with pytest.raises(vsa.VsaError):
         vsa.vsa_bench_mfma_rate(ops, sink, 1, 0)
+
+
+def test_selection_quality_diagnostic_on_planted_inputs(monkeypatch, capsys):
+    """Structured inputs: the coarse stage must pick cubes that hold far more of the dense attention
+    mass than random cubes do, and no more than the best possible choice."""
+    import sys
+    from paper_2505_13389_amd import selection_quality
+    monkeypatch.setattr(sys, "argv", ["selection_quality", "--workload", "sweep_h8_d64_k32", "--heads", "1"])
+    line = selection_quality.main()
+    assert line["mass_on_random_cubes"] < 0.5 * line["mass_on_selected_cubes"]
+    assert line["mass_on_selected_cubes"] <= line["mass_on_best_cubes"] + 1e-9
+    assert abs(line["mass_on_random_cubes"] - line["density"]) < 0.1
