@@ -252,89 +252,120 @@ hipError_t launch_coarse_bwd(int BH, int Nc, int d, float scale, const float* qc
 }
 
 // ---------------------------------------------------------------------------------------------
-// Transposed block map: for every key cube j of a (b,h), the ascending list of query cubes
-// whose index list contains j (CSR: row_ptr[bh][Nc+1], col[bh][Nc*K]).
-// One workgroup per (b,h) does a stable counting sort of the (query cube, key cube) pairs.
-// Wavefront w owns a contiguous range of query cubes; since the key cubes within one query
-// row are distinct, a wavefront can bump per-key counters row by row without atomics, and the
-// per-wavefront counters are combined by a prefix over w.  No float math, fully deterministic.
-constexpr int kMapCounters = 32768;
-constexpr int kMaxCubes = 4096;  // = 4 entries per thread of a 1024-thread scan
-__global__ __launch_bounds__(1024) void k_transpose_map(int Nc, int K, int W, const int32_t* __restrict__ idx,
-                                                        int32_t* __restrict__ row_ptr, int32_t* __restrict__ col) {
-  __shared__ int cnt[kMapCounters];   // [W][Nc]
-  __shared__ int total[kMaxCubes];
+// Transposed block map (CSR): for every key cube j the ascending list of the query cubes that
+// selected it.  Built through a bit matrix so that every step is parallel over the whole grid and
+// the result does not depend on any execution order (no float or ordering-sensitive atomics; the
+// only atomic is a bitwise OR in LDS):
+//   bits[bh][j][w], bit q%32 of word q/32  <-  1 for every (q, j) in the index list
+//   row_ptr = exclusive scan over j of popcount(row j)        (a wavefront per row, then one
+//                                                               workgroup per (b, h) for the scan)
+//   col     = positions of the set bits of row j, ascending   (one wavefront per (b, h, j))
+constexpr int kMaxCubes = 4096;  // = 4 entries per thread of the 1024-thread scan
+
+// One workgroup per (b, h, word column w): the 32 query cubes 32w .. 32w+31 OR their bits into a
+// per-key word held in LDS, then every key row gets its word w written exactly once (no global
+// atomics, nothing to clear beforehand).
+__global__ __launch_bounds__(256) void k_map_bits(int Nc, int K, int W32, const int32_t* __restrict__ idx,
+                                                  uint32_t* __restrict__ bits) {
+  __shared__ uint32_t word[kMaxCubes];
+  const int w = blockIdx.x % W32, tid = threadIdx.x;
+  const long long bh = blockIdx.x / W32;
+  for (int j = tid; j < Nc; j += 256) word[j] = 0u;
+  __syncthreads();
+  const int q_lo = w * 32, nq = min(32, Nc - q_lo);
+  const int32_t* my = idx + (bh * Nc + q_lo) * (long long)K;
+  for (int e = tid; e < nq * K; e += 256) atomicOr(&word[my[e]], 1u << (e / K));
+  __syncthreads();
+  for (int j = tid; j < Nc; j += 256) bits[(bh * Nc + j) * W32 + w] = word[j];
+}
+
+// in-degree of every key cube: one wavefront per (b, h, j), written to row_ptr[bh][j] (scanned next)
+__global__ __launch_bounds__(256) void k_map_degree(int Nc, int W32, long long rows, const uint32_t* __restrict__ bits,
+                                                    int32_t* __restrict__ row_ptr) {
+  const long long row = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);  // bh * Nc + j
+  const int lane = threadIdx.x & 63;
+  if (row >= rows) return;
+  const uint32_t* r = bits + row * W32;
+  int c = 0;
+  for (int w = lane; w < W32; w += 64) c += __popc(r[w]);
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) c += __shfl_xor(c, o);
+  if (lane == 0) row_ptr[(row / Nc) * (Nc + 1) + row % Nc] = c;
+}
+
+// exclusive scan of the in-degrees of one (b, h), in place; row_ptr[Nc] = total
+__global__ __launch_bounds__(1024) void k_map_scan(int Nc, int32_t* __restrict__ row_ptr) {
   __shared__ int wsum[16];
   const int bh = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int32_t* my = idx + (long long)bh * Nc * K;
   int32_t* rp = row_ptr + (long long)bh * (Nc + 1);
-  int32_t* cl = col + (long long)bh * Nc * K;
-  const int per = (Nc + W - 1) / W;
-  const int c_lo = min(Nc, wave * per), c_hi = min(Nc, c_lo + per);
-
-  for (int i = tid; i < W * Nc; i += 1024) cnt[i] = 0;
-  __syncthreads();
-  if (wave < W)
-    for (int c = c_lo; c < c_hi; ++c)
-      for (int r = lane; r < K; r += 64) cnt[wave * Nc + my[(long long)c * K + r]] += 1;
-  __syncthreads();
-  // per key cube: exclusive prefix over wavefronts, total in-degree
-  for (int j = tid; j < Nc; j += 1024) {
-    int run = 0;
-    for (int w = 0; w < W; ++w) {
-      int t = cnt[w * Nc + j];
-      cnt[w * Nc + j] = run;
-      run += t;
-    }
-    total[j] = run;
-  }
-  __syncthreads();
-  // exclusive scan of total[0..Nc) -> row_ptr.  Each thread scans a contiguous slice of 4.
-  {
-    const int j0 = tid * 4;
-    int v[4], sum = 0;
+  const int j0 = tid * 4;
+  int v[4], sum = 0;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      v[i] = (j0 + i < Nc) ? total[j0 + i] : 0;
-      sum += v[i];
-    }
-    int incl = sum;
+  for (int i = 0; i < 4; ++i) {
+    v[i] = (j0 + i < Nc) ? rp[j0 + i] : 0;
+    sum += v[i];
+  }
+  int incl = sum;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    int t = __shfl_up(incl, o);
+    if (lane >= o) incl += t;
+  }
+  if (lane == 63) wsum[wave] = incl;
+  __syncthreads();
+  int base = 0;
+  for (int w = 0; w < wave; ++w) base += wsum[w];
+  int run = base + incl - sum;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    if (j0 + i < Nc) rp[j0 + i] = run;
+    run += v[i];
+  }
+  if (tid == 1023) rp[Nc] = run;
+}
+
+// the list of key cube j: positions of the set bits of its row, ascending (one wavefront per row)
+__global__ __launch_bounds__(256) void k_map_fill(int Nc, int W32, long long rows, const uint32_t* __restrict__ bits,
+                                                  const int32_t* __restrict__ row_ptr, int32_t* __restrict__ col,
+                                                  long long col_stride) {
+  const long long row = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);  // bh * Nc + j
+  const int lane = threadIdx.x & 63;
+  if (row >= rows) return;
+  const long long bh = row / Nc;
+  int base = row_ptr[bh * (Nc + 1) + row % Nc];
+  int32_t* cl = col + bh * col_stride;
+  const uint32_t* r = bits + row * W32;
+  for (int w0 = 0; w0 < W32; w0 += 64) {
+    uint32_t word = (w0 + lane < W32) ? r[w0 + lane] : 0u;
+    const int c = __popc(word);
+    int incl = c;
 #pragma unroll
     for (int o = 1; o < 64; o <<= 1) {
       int t = __shfl_up(incl, o);
       if (lane >= o) incl += t;
     }
-    if (lane == 63) wsum[wave] = incl;
-    __syncthreads();
-    int base = 0;
-    for (int w = 0; w < wave; ++w) base += wsum[w];
-    int run = base + incl - sum;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      if (j0 + i < Nc) {
-        total[j0 + i] = run;  // now the row start
-        rp[j0 + i] = run;
-      }
-      run += v[i];
+    int pos = base + incl - c;
+    while (word) {
+      const int b = __ffs(word) - 1;
+      cl[pos++] = (w0 + lane) * 32 + b;
+      word &= word - 1;
     }
-    if (tid == 1023) rp[Nc] = run;
+    base += __shfl(incl, 63);
   }
-  __syncthreads();
-  if (wave < W)
-    for (int c = c_lo; c < c_hi; ++c)
-      for (int r = lane; r < K; r += 64) {
-        const int j = my[(long long)c * K + r];
-        const int pos = total[j] + cnt[wave * Nc + j];
-        cnt[wave * Nc + j] += 1;
-        cl[pos] = c;
-      }
 }
 
-hipError_t launch_transpose_map(int BH, int Nc, int K, const int32_t* idx, int32_t* row_ptr, int32_t* col,
-                                hipStream_t s) {
-  int W = kMapCounters / Nc;
-  if (W > 16) W = 16;
-  k_transpose_map<<<BH, 1024, 0, s>>>(Nc, K, W, idx, row_ptr, col);
+hipError_t launch_transpose_map(int BH, int Nc, int K, const int32_t* idx, uint32_t* bits, int32_t* row_ptr,
+                                int32_t* col, hipStream_t s) {
+  const int W32 = (Nc + 31) / 32;
+  const long long rows = (long long)BH * Nc;
+  hipError_t e;
+  k_map_bits<<<(unsigned)(BH * W32), 256, 0, s>>>(Nc, K, W32, idx, bits);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  k_map_degree<<<(unsigned)((rows + 3) / 4), 256, 0, s>>>(Nc, W32, rows, bits, row_ptr);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  k_map_scan<<<BH, 1024, 0, s>>>(Nc, row_ptr);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  k_map_fill<<<(unsigned)((rows + 3) / 4), 256, 0, s>>>(Nc, W32, rows, bits, row_ptr, col, (long long)Nc * K);
   return hipGetLastError();
 }
 
