@@ -138,8 +138,15 @@ __device__ __forceinline__ void gemm_fetch(float* v, const float* __restrict__ b
   } else {
     const int kk = tid >> 3, rq = (tid & 7) * 8;
     const float* p = base + (long long)kk * sk + (long long)rq * srow;
+    const bool vec = (srow == 1) && (rq + 8 <= rows_valid) && (kk < k_valid) && ((sk & 3) == 0) &&
+                     ((((uintptr_t)base) & 15) == 0);
+    if (vec) {
+      const float4 x = *(const float4*)p, y = *(const float4*)(p + 4);
+      v[0] = x.x; v[1] = x.y; v[2] = x.z; v[3] = x.w; v[4] = y.x; v[5] = y.y; v[6] = y.z; v[7] = y.w;
+    } else {
 #pragma unroll
-    for (int i = 0; i < 8; ++i) v[i] = (rq + i < rows_valid && kk < k_valid) ? p[i * srow] : 0.f;
+      for (int i = 0; i < 8; ++i) v[i] = (rq + i < rows_valid && kk < k_valid) ? p[i * srow] : 0.f;
+    }
   }
 }
 __device__ __forceinline__ void gemm_store(float (*T)[36], const float* v, long long sk, int tid) {
@@ -154,14 +161,23 @@ __device__ __forceinline__ void gemm_store(float (*T)[36], const float* v, long 
   }
 }
 
-__global__ __launch_bounds__(256) void k_gemm32(int M, int N, int Kd, float alpha, const float* __restrict__ a,
-                                                long long sab, int sam, int sak, const float* __restrict__ bm,
-                                                long long sbb, int sbk, int sbn, float* __restrict__ cm, long long scb) {
+// Up to three independent problems of the same shape run as one launch (blockIdx.z = problem *
+// batch + batch index): the small coarse-stage products do not fill the chip one at a time.
+struct GemmOperands {
+  const float* a; long long sab; int sam, sak;
+  const float* b; long long sbb; int sbk, sbn;
+  float* c; long long scb; float alpha;
+};
+struct GemmSet { GemmOperands p[3]; };
+
+__global__ __launch_bounds__(256) void k_gemm32(int M, int N, int Kd, int batch, GemmSet set) {
   __shared__ __attribute__((aligned(16))) float As[64][36];
   __shared__ __attribute__((aligned(16))) float Bs[64][36];
-  const int b = blockIdx.z, m0 = blockIdx.y * 64, n0 = blockIdx.x * 64;
-  const float* ab = a + b * sab + (long long)m0 * sam;
-  const float* bb = bm + b * sbb + (long long)n0 * sbn;
+  const GemmOperands& g = set.p[blockIdx.z / batch];
+  const int b = blockIdx.z % batch, m0 = blockIdx.y * 64, n0 = blockIdx.x * 64;
+  const int sam = g.sam, sak = g.sak, sbk = g.sbk, sbn = g.sbn;
+  const float* ab = g.a + b * g.sab + (long long)m0 * sam;
+  const float* bb = g.b + b * g.sbb + (long long)n0 * sbn;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave & 1, wn = wave >> 1, l32 = lane & 31, h = lane >> 5;
   f32x16g acc;
@@ -189,7 +205,8 @@ __global__ __launch_bounds__(256) void k_gemm32(int M, int N, int Kd, float alph
     }
     __syncthreads();
   }
-  float* cb = cm + b * scb;
+  float* cb = g.c + b * g.scb;
+  const float alpha = g.alpha;
   const int n = n0 + wn * 32 + l32;
 #pragma unroll
   for (int i = 0; i < 16; ++i) {
@@ -198,15 +215,24 @@ __global__ __launch_bounds__(256) void k_gemm32(int M, int N, int Kd, float alph
   }
 }
 
-hipError_t gemm32(int batch, int M, int N, int Kd, float alpha, const float* a, long long sab, int sam, int sak,
-                  const float* b, long long sbb, int sbk, int sbn, float* c, long long scb, hipStream_t s) {
-  dim3 grid((N + 63) / 64, (M + 63) / 64, batch);
-  k_gemm32<<<grid, 256, 0, s>>>(M, N, Kd, alpha, a, sab, sam, sak, b, sbb, sbk, sbn, c, scb);
+static GemmOperands gemm_operands(float alpha, const float* a, long long sab, int sam, int sak, const float* b,
+                                  long long sbb, int sbk, int sbn, float* c, long long scb) {
+  GemmOperands o;
+  o.a = a; o.sab = sab; o.sam = sam; o.sak = sak;
+  o.b = b; o.sbb = sbb; o.sbk = sbk; o.sbn = sbn;
+  o.c = c; o.scb = scb; o.alpha = alpha;
+  return o;
+}
+static hipError_t gemm32_set(int nprob, int batch, int M, int N, int Kd, const GemmSet& set, hipStream_t s) {
+  dim3 grid((N + 63) / 64, (M + 63) / 64, batch * nprob);
+  k_gemm32<<<grid, 256, 0, s>>>(M, N, Kd, batch, set);
   return hipGetLastError();
 }
-static hipError_t sgemm(int batch, int M, int N, int Kd, float alpha, const float* a, long long sab, int sam, int sak,
-                        const float* b, long long sbb, int sbk, int sbn, float* c, long long scb, hipStream_t s) {
-  return gemm32(batch, M, N, Kd, alpha, a, sab, sam, sak, b, sbb, sbk, sbn, c, scb, s);
+hipError_t gemm32(int batch, int M, int N, int Kd, float alpha, const float* a, long long sab, int sam, int sak,
+                  const float* b, long long sbb, int sbk, int sbn, float* c, long long scb, hipStream_t s) {
+  GemmSet set;
+  set.p[0] = set.p[1] = set.p[2] = gemm_operands(alpha, a, sab, sam, sak, b, sbb, sbk, sbn, c, scb);
+  return gemm32_set(1, batch, M, N, Kd, set, s);
 }
 
 // Row-wise softmax backward on the coarse score matrix, in place:
@@ -238,17 +264,19 @@ hipError_t launch_coarse_bwd(int BH, int Nc, int d, float scale, const float* qc
                              float* dvc, hipStream_t s) {
   const long long sx = (long long)Nc * d, ss = (long long)Nc * Nc;
   hipError_t e;
-  // sc = scale * Qc Kc^T ; dAc = dOc Vc^T
-  if ((e = sgemm(BH, Nc, Nc, d, scale, qc, sx, d, 1, kc, sx, 1, d, ac, ss, s)) != hipSuccess) return e;
-  if ((e = sgemm(BH, Nc, Nc, d, 1.f, doc, sx, d, 1, vc, sx, 1, d, dsc, ss, s)) != hipSuccess) return e;
+  GemmSet set;
+  // one launch: sc = scale * Qc Kc^T ; dAc = dOc Vc^T
+  set.p[0] = gemm_operands(scale, qc, sx, d, 1, kc, sx, 1, d, ac, ss);
+  set.p[1] = set.p[2] = gemm_operands(1.f, doc, sx, d, 1, vc, sx, 1, d, dsc, ss);
+  if ((e = gemm32_set(2, BH, Nc, Nc, d, set, s)) != hipSuccess) return e;
   k_coarse_softmax_bwd<<<(BH * Nc + 3) / 4, 256, 0, s>>>(BH * Nc, Nc, lse_c, ac, dsc);
   if ((e = hipGetLastError()) != hipSuccess) return e;
-  // dVc[j][e] = sum_c Ac[c][j] dOc[c][e]
-  if ((e = sgemm(BH, Nc, d, Nc, 1.f, ac, ss, 1, Nc, doc, sx, d, 1, dvc, sx, s)) != hipSuccess) return e;
-  // dQc[c][e] = scale sum_j dSc[c][j] Kc[j][e]
-  if ((e = sgemm(BH, Nc, d, Nc, scale, dsc, ss, Nc, 1, kc, sx, d, 1, dqc, sx, s)) != hipSuccess) return e;
-  // dKc[j][e] = scale sum_c dSc[c][j] Qc[c][e]
-  return sgemm(BH, Nc, d, Nc, scale, dsc, ss, 1, Nc, qc, sx, d, 1, dkc, sx, s);
+  // one launch: dVc[j][e] = sum_c Ac[c][j] dOc[c][e] ; dQc[c][e] = scale sum_j dSc[c][j] Kc[j][e] ;
+  //             dKc[j][e] = scale sum_c dSc[c][j] Qc[c][e]
+  set.p[0] = gemm_operands(1.f, ac, ss, 1, Nc, doc, sx, d, 1, dvc, sx);
+  set.p[1] = gemm_operands(scale, dsc, ss, Nc, 1, kc, sx, d, 1, dqc, sx);
+  set.p[2] = gemm_operands(scale, dsc, ss, 1, Nc, qc, sx, d, 1, dkc, sx);
+  return gemm32_set(3, BH, Nc, d, Nc, set, s);
 }
 
 // ---------------------------------------------------------------------------------------------
