@@ -108,8 +108,17 @@ hipError_t launch_coarse(int BH, int Nc, int d, int K, float scale, const float*
   if ((e = gemm32(BH, Nc, Nc, d, scale, qc, sx, d, 1, kc, sx, 1, d, sc, ss, s)) != hipSuccess) return e;
   const int rows = BH * Nc;
   const unsigned grid = (unsigned)((rows + 3) / 4);
-  if (Nc <= 512)
+  // NCH = logits per lane (compile-time bound of the per-lane loops): the smallest that covers Nc
+  if (Nc <= 128)
+    k_coarse_rows<2><<<grid, 256, 0, s>>>(rows, Nc, K, sc, lse_c, idx, emit_idx);
+  else if (Nc <= 256)
+    k_coarse_rows<4><<<grid, 256, 0, s>>>(rows, Nc, K, sc, lse_c, idx, emit_idx);
+  else if (Nc <= 512)
     k_coarse_rows<8><<<grid, 256, 0, s>>>(rows, Nc, K, sc, lse_c, idx, emit_idx);
+  else if (Nc <= 768)
+    k_coarse_rows<12><<<grid, 256, 0, s>>>(rows, Nc, K, sc, lse_c, idx, emit_idx);
+  else if (Nc <= 1024)
+    k_coarse_rows<16><<<grid, 256, 0, s>>>(rows, Nc, K, sc, lse_c, idx, emit_idx);
   else if (Nc <= 1536)
     k_coarse_rows<24><<<grid, 256, 0, s>>>(rows, Nc, K, sc, lse_c, idx, emit_idx);
   else
