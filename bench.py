@@ -145,9 +145,9 @@ def main():
     buf = vsa.Buffers(pb)
     a = (dev["q"], dev["k"], dev["v"], dev["gate_c"], dev["gate_f"])
 
-    def step():
+    def step():  # one layer's training step: the backward gets the workspace the forward left behind
         buf.forward(*a)
-        buf.backward(*a, dev["dout"])
+        buf.backward(*a, dev["dout"], workspace_kept=True)
 
     ms = time_steps(step, args.steps, args.warmup, torch)
     ms_fwd = time_steps(lambda: buf.forward(*a), args.steps, 1, torch)
@@ -206,7 +206,7 @@ def main():
 
         def dstep():
             dbuf.forward(*a)
-            dbuf.backward(*a, dev["dout"])
+            dbuf.backward(*a, dev["dout"], workspace_kept=True)
         ms_dense = time_steps(dstep, max(2, args.steps // 8), 1, torch)
         speedup = ms_dense / ms
         del dbuf

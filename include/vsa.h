@@ -49,6 +49,10 @@ typedef enum {
 
 #define VSA_FLAG_INDICES_GIVEN 1u /* vsa_forward: block_idx is an INPUT, top-K is skipped */
 #define VSA_FLAG_RASTER_BLHD 2u   /* vsa_tile_permute: the raster tensor is token-major [B,L,H,d] */
+#define VSA_FLAG_WORKSPACE_KEPT 4u /* vsa_backward: `workspace` is the buffer the matching vsa_forward
+                                      call (same parameters, same q, k, v) was given, and nothing has
+                                      written to it since: the pooled tensors it still holds are used
+                                      instead of being computed again.  Size it for the backward. */
 #define VSA_MAX_CUBES 4096        /* largest supported Nc                                 */
 
 typedef struct {

@@ -224,8 +224,11 @@ int vsa_backward(const vsa_params_t* p, const void* q, const void* k, const void
   const int BH = p->B * p->H;
   const float scale = scale_of(p);
 
-  VSA_TRY("cube_masks", vsa::launch_cube_masks(g, w.mask, s));
-  VSA_TRY("pool", vsa::launch_pool(g, BH, p->d, w.mask, q, k, v, w.qc, w.kc, w.vc, s));
+  // forward and backward carve the cube masks and the pooled tensors at the same offsets
+  if (!(p->flags & VSA_FLAG_WORKSPACE_KEPT)) {
+    VSA_TRY("cube_masks", vsa::launch_cube_masks(g, w.mask, s));
+    VSA_TRY("pool", vsa::launch_pool(g, BH, p->d, w.mask, q, k, v, w.qc, w.kc, w.vc, s));
+  }
   VSA_TRY("bwd_pre", vsa::launch_bwd_pre(BH, g.Nc, p->d, w.mask, dout, gate_c, gate_f, out_fine, out_coarse, dgate_c, dgate_f,
                               w.dof, w.ld, w.ldb, scale, w.doc, lse_fine, s));
   VSA_TRY("coarse_bwd", vsa::launch_coarse_bwd(BH, g.Nc, p->d, scale, w.qc, w.kc, w.vc, lse_coarse, w.doc, w.ac, w.dsc, w.dqc, w.dkc,

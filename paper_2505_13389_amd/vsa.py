@@ -15,6 +15,7 @@ LIB_PATH = os.path.join(_HERE, "libvsa.so")
 
 VSA_FLAG_INDICES_GIVEN = 1
 VSA_FLAG_RASTER_BLHD = 2
+VSA_FLAG_WORKSPACE_KEPT = 4
 STATUS = {0: "VSA_OK", -1: "VSA_ERR_NULL", -2: "VSA_ERR_BAD_ARG", -3: "VSA_ERR_UNSUPPORTED", -4: "VSA_ERR_ALIGN",
           -5: "VSA_ERR_WORKSPACE", -6: "VSA_ERR_HIP"}
 EXPORTS = ["vsa_padded_tokens", "vsa_workspace_bytes", "vsa_tile_permute", "vsa_forward", "vsa_backward",
@@ -125,8 +126,9 @@ def vsa_forward(pb: Problem, q, k, v, gate_c, gate_f, out, block_idx, out_fine, 
 
 
 def vsa_backward(pb: Problem, q, k, v, gate_c, gate_f, dout, block_idx, out_fine, lse_fine, out_coarse, lse_coarse,
-                 dq, dk, dv, dgate_c, dgate_f, workspace):
-    rc = lib().vsa_backward(C.byref(pb.params()), _p(q), _p(k), _p(v), _p(gate_c), _p(gate_f), _p(dout),
+                 dq, dk, dv, dgate_c, dgate_f, workspace, workspace_kept: bool = False):
+    flags = pb.flags | (VSA_FLAG_WORKSPACE_KEPT if workspace_kept else 0)
+    rc = lib().vsa_backward(C.byref(pb.params(flags)), _p(q), _p(k), _p(v), _p(gate_c), _p(gate_f), _p(dout),
                             _p(block_idx), _p(out_fine), _p(lse_fine), _p(out_coarse), _p(lse_coarse), _p(dq), _p(dk),
                             _p(dv), _p(dgate_c), _p(dgate_f), _p(workspace),
                             0 if workspace is None else workspace.numel() * workspace.element_size(), _stream())
@@ -161,10 +163,11 @@ class Buffers:
         vsa_forward(self.pb, q, k, v, gate_c, gate_f, self.out, self.block_idx, self.out_fine, self.lse_fine,
                     self.out_coarse, self.lse_coarse, self.workspace, indices_given=indices_given)
 
-    def backward(self, q, k, v, gate_c, gate_f, dout):
+    def backward(self, q, k, v, gate_c, gate_f, dout, workspace_kept=False):
+        """workspace_kept: forward() ran on the same q, k, v and nothing touched the workspace since."""
         vsa_backward(self.pb, q, k, v, gate_c, gate_f, dout, self.block_idx, self.out_fine, self.lse_fine,
                      self.out_coarse, self.lse_coarse, self.dq, self.dk, self.dv, self.dgate_c, self.dgate_f,
-                     self.workspace)
+                     self.workspace, workspace_kept=workspace_kept)
 
 
 def vsa_bench_mfma_rate(operands: torch.Tensor, sink: torch.Tensor, workgroups: int, iters: int) -> float:

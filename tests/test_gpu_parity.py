@@ -210,6 +210,25 @@ def test_backward_on_oracle_indices(vsa, name, with_gate_f):
         assert not bf16_to_np(getattr(buf, name_))[:, :, ~valid].any(), f"{name_}: pad rows must be zero"
 
 
+def test_backward_with_kept_workspace_is_bit_identical(vsa):
+    """VSA_FLAG_WORKSPACE_KEPT only skips recomputing the pooled tensors the forward left behind."""
+    import torch
+    wl = SMALL["pad128"]
+    dev = to_dev(tiled_bits(wl, seed=5))
+    buf = run_gpu_fwd(vsa, wl, dev, backward=True)
+    args = (dev["q"], dev["k"], dev["v"], dev["gate_c"], dev["gate_f"], dev["dout"])
+    buf.backward(*args)
+    torch.cuda.synchronize()
+    ref = [t.clone() for t in (buf.dq, buf.dk, buf.dv, buf.dgate_c, buf.dgate_f)]
+    buf.forward(*args[:5])
+    for t in (buf.dq, buf.dk, buf.dv, buf.dgate_c, buf.dgate_f):
+        t.fill_(float("nan"))
+    buf.backward(*args, workspace_kept=True)
+    torch.cuda.synchronize()
+    for got, want in zip((buf.dq, buf.dk, buf.dv, buf.dgate_c, buf.dgate_f), ref):
+        assert torch.equal(got.view(torch.int16), want.view(torch.int16))
+
+
 def test_backward_is_deterministic(vsa):
     import torch
     wl = SMALL["planted_pad128"]
