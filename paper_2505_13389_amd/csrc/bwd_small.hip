@@ -321,35 +321,78 @@ __global__ __launch_bounds__(256) void k_map_degree(int Nc, int W32, long long r
   if (lane == 0) row_ptr[(row / Nc) * (Nc + 1) + row % Nc] = c;
 }
 
-// exclusive scan of the in-degrees of one (b, h), in place; row_ptr[Nc] = total
-__global__ __launch_bounds__(1024) void k_map_scan(int Nc, int32_t* __restrict__ row_ptr) {
-  __shared__ int wsum[16];
-  const int bh = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  int32_t* rp = row_ptr + (long long)bh * (Nc + 1);
-  const int j0 = tid * 4;
-  int v[4], sum = 0;
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    v[i] = (j0 + i < Nc) ? rp[j0 + i] : 0;
-    sum += v[i];
-  }
+// Exclusive scan over 4 * 1024 values, 4 consecutive ones per thread of a 1024-thread workgroup:
+// v[i] is replaced by the sum of everything before it; returns the grand total.
+__device__ __forceinline__ int block_scan4(int* v, int* wsum, int tid) {
+  const int lane = tid & 63, wave = tid >> 6;
+  const int sum = v[0] + v[1] + v[2] + v[3];
   int incl = sum;
 #pragma unroll
   for (int o = 1; o < 64; o <<= 1) {
     int t = __shfl_up(incl, o);
     if (lane >= o) incl += t;
   }
+  __syncthreads();  // wsum may still be read by a previous call
   if (lane == 63) wsum[wave] = incl;
   __syncthreads();
-  int base = 0;
-  for (int w = 0; w < wave; ++w) base += wsum[w];
+  int base = 0, total = 0;
+  for (int w = 0; w < 16; ++w) {
+    if (w < wave) base += wsum[w];
+    total += wsum[w];
+  }
   int run = base + incl - sum;
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    if (j0 + i < Nc) rp[j0 + i] = run;
-    run += v[i];
+    const int t = v[i];
+    v[i] = run;
+    run += t;
   }
-  if (tid == 1023) rp[Nc] = run;
+  return total;
+}
+
+// exclusive scan of the in-degrees of one (b, h), in place; row_ptr[Nc] = total.  Also sorts the
+// key cubes by in-degree, longest list first (counting sort; the order among equal degrees is
+// whatever the LDS atomics give, it only decides which workgroup starts when): `order` is the
+// sequence in which the dK/dV pass takes them, so that the workgroups still running at the end of
+// the launch are the short ones.
+__global__ __launch_bounds__(1024) void k_map_scan(int Nc, int32_t* __restrict__ row_ptr, int32_t* __restrict__ order) {
+  __shared__ int wsum[16];
+  __shared__ int hist[kMaxCubes];  // bucket x: cubes of in-degree Nc - x (the last bucket also takes
+                                   // what lies beyond it), then the next free slot of the bucket
+  const int bh = blockIdx.x, tid = threadIdx.x;
+  int32_t* rp = row_ptr + (long long)bh * (Nc + 1);
+  const int j0 = tid * 4;
+  int deg[4], v[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    deg[i] = (j0 + i < Nc) ? rp[j0 + i] : 0;
+    v[i] = deg[i];
+    hist[j0 + i] = 0;
+  }
+  const int total = block_scan4(v, wsum, tid);  // (its barriers also cover the clearing of hist)
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+    if (j0 + i < Nc) rp[j0 + i] = v[i];
+  if (tid == 0) rp[Nc] = total;
+  // counting sort by in-degree, descending
+  int bucket[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    bucket[i] = min(Nc - deg[i], kMaxCubes - 1);
+    if (j0 + i < Nc) atomicAdd(&hist[bucket[i]], 1);
+  }
+  __syncthreads();
+  int first[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) first[i] = hist[j0 + i];
+  block_scan4(first, wsum, tid);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) hist[j0 + i] = first[i];
+  __syncthreads();
+  int32_t* ord = order + (long long)bh * Nc;
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+    if (j0 + i < Nc) ord[atomicAdd(&hist[bucket[i]], 1)] = j0 + i;
 }
 
 // the list of key cube j: positions of the set bits of its row, ascending (one wavefront per row)
@@ -383,7 +426,7 @@ __global__ __launch_bounds__(256) void k_map_fill(int Nc, int W32, long long row
 }
 
 hipError_t launch_transpose_map(int BH, int Nc, int K, const int32_t* idx, uint32_t* bits, int32_t* row_ptr,
-                                int32_t* col, hipStream_t s) {
+                                int32_t* col, int32_t* order, hipStream_t s) {
   const int W32 = (Nc + 31) / 32;
   const long long rows = (long long)BH * Nc;
   hipError_t e;
@@ -391,7 +434,7 @@ hipError_t launch_transpose_map(int BH, int Nc, int K, const int32_t* idx, uint3
   if ((e = hipGetLastError()) != hipSuccess) return e;
   k_map_degree<<<(unsigned)((rows + 3) / 4), 256, 0, s>>>(Nc, W32, rows, bits, row_ptr);
   if ((e = hipGetLastError()) != hipSuccess) return e;
-  k_map_scan<<<BH, 1024, 0, s>>>(Nc, row_ptr);
+  k_map_scan<<<BH, 1024, 0, s>>>(Nc, row_ptr, order);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   k_map_fill<<<(unsigned)((rows + 3) / 4), 256, 0, s>>>(Nc, W32, rows, bits, row_ptr, col, (long long)Nc * K);
   return hipGetLastError();

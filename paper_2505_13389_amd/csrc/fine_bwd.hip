@@ -5,10 +5,11 @@
 //   dK_j = scale sum_i dS_ij q_i,  dV_j = sum_i P_ij dOf_i   (key-tile-major pass over the
 //                                                             transposed block map)
 // Both passes add the pooled-path gradient dXc[cube]/cnt to every valid row in their epilogue
-// and write zeros to pad rows.  Work split and operand layouts follow the forward kernel: all
-// products are computed transposed, the streamed tiles sit in a double-buffered LDS stage, the
-// resident tile sits in registers, and each wavefront pair owning the same output rows is
-// merged once at the end.
+// and write zeros to pad rows.  Work split and operand layouts follow the forward kernel: the
+// streamed tiles are copied global -> LDS asynchronously (two stages in the dQ pass, four in the
+// dK/dV pass), the resident tile sits in registers, and each wavefront pair owning the same output
+// rows is merged once at the end.  The per-row terms (lse, Delta) and the pad-key mask enter the
+// products through extra MFMA steps rather than per-element vector arithmetic.
 #include <type_traits>
 
 #include "fine_tile.h"
@@ -244,6 +245,7 @@ __global__ __launch_bounds__(256, 1) void k_fine_bwd_dkv(int Nc, int K, float sl
                                                          const uint4* __restrict__ dof,
                                                          const int32_t* __restrict__ row_ptr,
                                                          const int32_t* __restrict__ col,
+                                                         const int32_t* __restrict__ order,
                                                          const uint4* __restrict__ ldb,
                                                          const float* __restrict__ dkc, const float* __restrict__ dvc,
                                                          const uint64_t* __restrict__ mask, uint4* __restrict__ dk,
@@ -256,8 +258,8 @@ __global__ __launch_bounds__(256, 1) void k_fine_bwd_dkv(int Nc, int K, float sl
   __shared__ __attribute__((aligned(16))) unsigned char smem[4 * STAGE];
   static_assert(2 * 64 * OS * 4 <= 4 * STAGE, "merge buffers must fit");
 
-  const int j = blockIdx.x % Nc;
   const long long bh = blockIdx.x / Nc;
+  const int j = order[blockIdx.x];  // key cubes of a (b, h) are taken longest list first
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int kh = wave & 1, qh = wave >> 1, l32 = lane & 31, h = lane >> 5;
   const long long rows0 = bh * (long long)Nc * kTile;
@@ -543,18 +545,18 @@ __global__ __launch_bounds__(256, 1) void k_fine_bwd_dkv(int Nc, int K, float sl
 }
 
 hipError_t launch_fine_bwd_dkv(int BH, int Nc, int d, int K, float scale, const void* q, const void* k, const void* v,
-                               const void* dof, const int32_t* row_ptr, const int32_t* col, const void* ldb,
-                               const float* dkc, const float* dvc, const uint64_t* mask, void* dk,
+                               const void* dof, const int32_t* row_ptr, const int32_t* col, const int32_t* order,
+                               const void* ldb, const float* dkc, const float* dvc, const uint64_t* mask, void* dk,
                                void* dv, hipStream_t s) {
   const float sl2 = scale * kLog2e;
   const unsigned grid = (unsigned)(BH * Nc);
   if (d == 128)
     k_fine_bwd_dkv<128><<<grid, 256, 0, s>>>(Nc, K, sl2, scale, (const uint4*)q, (const uint4*)k, (const uint4*)v,
-                                             (const uint4*)dof, row_ptr, col, (const uint4*)ldb, dkc, dvc, mask, (uint4*)dk,
+                                             (const uint4*)dof, row_ptr, col, order, (const uint4*)ldb, dkc, dvc, mask, (uint4*)dk,
                                              (uint4*)dv);
   else
     k_fine_bwd_dkv<64><<<grid, 256, 0, s>>>(Nc, K, sl2, scale, (const uint4*)q, (const uint4*)k, (const uint4*)v,
-                                            (const uint4*)dof, row_ptr, col, (const uint4*)ldb, dkc, dvc, mask, (uint4*)dk,
+                                            (const uint4*)dof, row_ptr, col, order, (const uint4*)ldb, dkc, dvc, mask, (uint4*)dk,
                                             (uint4*)dv);
   return hipGetLastError();
 }
