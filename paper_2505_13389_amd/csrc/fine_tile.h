@@ -38,6 +38,9 @@ __device__ __forceinline__ void lds_dma16_at(const void* base, unsigned voff) {
   static_assert(IMM >= 0 && IMM < 4096, "13-bit signed instruction offset");
   asm volatile("global_load_lds_dwordx4 %0, %1 offset:%2" : : "v"(voff), "s"(base), "n"(IMM) : "memory");
 }
+// M0 is written here and read by the copies that follow in program order (volatile asm statements
+// keep their order).  Nothing else in these kernels uses M0: no dynamically indexed register arrays
+// (v_movrel), no GWS or message instructions.
 __device__ __forceinline__ void set_m0(unsigned lds_addr) { asm volatile("s_mov_b32 m0, %0" : : "s"(lds_addr) : "m0", "memory"); }
 __device__ __forceinline__ void lds_dma4(const void* base, unsigned voff, unsigned lds_addr) {
   asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dword %0, %1"
