@@ -26,6 +26,9 @@ SMALL = {
     # other 64-token cube shapes (Sec. 3.2 ablates the tile shape; the volume is what the kernels fix)
     "cube_2x4x8": Workload("cube_2x4x8", 1, 2, 7, 10, 20, 128, 5, cube=(2, 4, 8)),
     "cube_1x8x8": Workload("cube_1x8x8", 1, 2, 3, 20, 17, 64, 4, cube=(1, 8, 8)),
+    # list lengths around the 64-entry chunks in which the kernels hold their index lists
+    "k64": Workload("k64", 1, 1, 12, 16, 24, 64, 64),
+    "k65": Workload("k65", 1, 1, 12, 16, 23, 64, 65),
 }
 
 
@@ -120,7 +123,7 @@ def test_topk_ties_go_to_the_lower_index(vsa):
 
 # ------------------------------------------------------------------------------ forward
 @pytest.mark.parametrize("name", ["tiny", "tiny_dense", "tiny128", "pad64", "pad128", "one_cube", "k1", "cube_2x4x8",
-                                  "cube_1x8x8"])
+                                  "cube_1x8x8", "k64", "k65"])
 @pytest.mark.parametrize("with_gate_f", [True, False])
 def test_forward_on_oracle_indices(vsa, name, with_gate_f):
     """The fine kernel on the oracle's own selection: a near-tie flip can neither hide nor fake an error."""
@@ -188,7 +191,7 @@ def test_forward_is_deterministic_and_ignores_pad_slots(vsa):
 
 # ------------------------------------------------------------------------------ backward
 @pytest.mark.parametrize("name", ["tiny", "tiny_dense", "tiny128", "pad64", "pad128", "one_cube", "k1", "planted",
-                                  "cube_2x4x8", "cube_1x8x8"])
+                                  "cube_2x4x8", "cube_1x8x8", "k64", "k65"])
 @pytest.mark.parametrize("with_gate_f", [True, False])
 def test_backward_on_oracle_indices(vsa, name, with_gate_f):
     import torch
