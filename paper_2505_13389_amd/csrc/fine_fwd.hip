@@ -46,8 +46,9 @@ __global__ __launch_bounds__(256, 2) void k_fine_fwd(int Nc, int K, float sl2, c
   __shared__ float ml[4 * 32 * 2];
   static_assert(2 * 32 * OS * 4 <= STAGE, "merge buffer must fit in one stage");
 
-  const int c = blockIdx.x % Nc;
-  const long long bh = blockIdx.x / Nc;
+  const unsigned wg = xcd_chunked_id(blockIdx.x, gridDim.x);
+  const int c = wg % Nc;
+  const long long bh = wg / Nc;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int qh = wave & 1, kh = wave >> 1, l32 = lane & 31, h = lane >> 5;
   const long long rows0 = bh * (long long)Nc * kTile;  // first row of this (b,h)

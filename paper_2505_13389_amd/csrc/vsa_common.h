@@ -43,6 +43,17 @@ __device__ __forceinline__ uint4 pack8(const float* f) {
   return u;
 }
 
+// Workgroups are dealt to the 8 XCDs (each with its own L2) round-robin by blockIdx.  This maps
+// blockIdx to a logical id such that every XCD works through one contiguous run of logical ids
+// (a bijection on [0, total) for any total): neighbouring query cubes, whose selected key cubes
+// overlap when attention is local, then share an L2, and the XCDs work on different heads.
+// Only for kernels whose workgroups all carry the same amount of work: a contiguous run of a
+// list sorted by length would leave the XCDs unevenly loaded.
+__device__ __forceinline__ unsigned xcd_chunked_id(unsigned b, unsigned total) {
+  const unsigned x = b & 7u, per = total >> 3, rem = total & 7u;
+  return x * per + (x < rem ? x : rem) + (b >> 3);
+}
+
 // x as bf16 hi + mid + lo (slots 0..2) and `slot3` as bf16 in slot 3 of an MFMA operand
 __device__ __forceinline__ uint2 split3_bf16(float x, float slot3) {
   const __bf16 hi = (__bf16)x;
