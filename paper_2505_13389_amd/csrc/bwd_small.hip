@@ -389,10 +389,11 @@ __global__ __launch_bounds__(1024) void k_map_scan(int Nc, int32_t* __restrict__
 #pragma unroll
   for (int i = 0; i < 4; ++i) hist[j0 + i] = first[i];
   __syncthreads();
-  int32_t* ord = order + (long long)bh * Nc;
+  // one descriptor per dK/dV workgroup: (key cube, begin and end of its list in col, 0)
+  int4* ord = (int4*)order + (long long)bh * Nc;
 #pragma unroll
   for (int i = 0; i < 4; ++i)
-    if (j0 + i < Nc) ord[atomicAdd(&hist[bucket[i]], 1)] = j0 + i;
+    if (j0 + i < Nc) ord[atomicAdd(&hist[bucket[i]], 1)] = make_int4(j0 + i, v[i], v[i] + deg[i], 0);
 }
 
 // the list of key cube j: positions of the set bits of its row, ascending (one wavefront per row)

@@ -44,6 +44,21 @@ __global__ __launch_bounds__(256, 2) void k_fine_bwd_dq(int Nc, int K, float sl2
   const int32_t* my_idx = idx + (bh * Nc + c) * (long long)K;
   const uint64_t qmask = mask[c];
 
+  // Start-up order: the list first (one round trip), then the copy of tile 0, and only then the
+  // loads of the key masks, Q, dO_f and the per-row terms, so that everything the first iteration
+  // needs is in flight together.  The empty asm consumes the loaded registers: the compiler has to
+  // place its wait for them right there (it also drains the copy, which it cannot see), and its own
+  // vmcnt bookkeeping has nothing left to wait for inside the loop (see Tile::async_load).
+  unsigned goff[TL::IPW];
+  TL::lane_offsets(wave, lane, goff);
+  CubeList cubes;
+  cubes.init(my_idx, mask, K, kh, lane);
+  {
+    const int jt = cubes.cube(0);
+    TL::async_load(k, rows0 + (long long)jt * kTile, stage0, wave, goff);
+    TL::async_load(v, rows0 + (long long)jt * kTile, stage0 + TL::BYTES, wave, goff);
+  }
+  cubes.load_masks();
   const long long qrow_g = rows0 + c * kTile + qh * 32 + l32;
   bf16x8 qreg[KS], doreg[KS];
   {
@@ -58,22 +73,13 @@ __global__ __launch_bounds__(256, 2) void k_fine_bwd_dq(int Nc, int K, float sl2
   // lse2 = lse*log2(e), +inf on pad query rows (then P = 0 and the row contributes nothing)
   float lse2 = ld[2 * qrow_g];
   float dl = ld[2 * qrow_g + 1];
-  // Everything loaded the ordinary way must have arrived before the first hand-ordered copy is
-  // issued (the compiler cannot see those copies; see Tile::async_load).
 #pragma unroll
   for (int s = 0; s < KS; ++s) asm volatile("" : "+v"(qreg[s]), "+v"(doreg[s]));
-  asm volatile("" : "+v"(lse2), "+v"(dl));
-
-  unsigned goff[TL::IPW];
-  TL::lane_offsets(wave, lane, goff);
-  CubeList cubes;
-  cubes.init(my_idx, mask, K, kh, lane);
+  asm volatile("" : "+v"(lse2), "+v"(dl), "+v"(cubes.km_v));
   uint32_t km_cur;  // valid-key mask (this wave's key half) of the tile of this iteration
   {
     int jt;
     cubes.get(0, jt, km_cur);
-    TL::async_load(k, rows0 + (long long)jt * kTile, stage0, wave, goff);
-    TL::async_load(v, rows0 + (long long)jt * kTile, stage0 + TL::BYTES, wave, goff);
   }
 
   f32x16 acc[DVB];
@@ -173,6 +179,11 @@ __global__ __launch_bounds__(256, 2) void k_fine_bwd_dq(int Nc, int K, float sl2
     body(stage0, stage1, t);
     if (t + 1 < K) body(stage1, stage0, t + 1);
   }
+  // the pooled-gradient term of this thread's column chunk (the same chunk for all of its items),
+  // requested before the partial results go through LDS
+  static_assert(256 % CPR == 0, "a thread keeps its column chunk");
+  const float* dqcr = dqc + (bh * Nc + c) * D + (tid % CPR) * 8;
+  const float4 pc0 = *(const float4*)dqcr, pc1 = *(const float4*)(dqcr + 4);
   __syncthreads();
 
   {
@@ -188,7 +199,8 @@ __global__ __launch_bounds__(256, 2) void k_fine_bwd_dq(int Nc, int K, float sl2
   __syncthreads();
 
   const float inv_cnt = 1.0f / (float)__popcll(qmask);
-  const float* dqcr = dqc + (bh * Nc + c) * D;
+  const float pooled[8] = {pc0.x * inv_cnt, pc0.y * inv_cnt, pc0.z * inv_cnt, pc0.w * inv_cnt,
+                           pc1.x * inv_cnt, pc1.y * inv_cnt, pc1.z * inv_cnt, pc1.w * inv_cnt};
 #pragma unroll
   for (int it = 0; it < LPT; ++it) {
     const int item = it * 256 + tid, r = item / CPR, ch = item % CPR;
@@ -198,7 +210,7 @@ __global__ __launch_bounds__(256, 2) void k_fine_bwd_dq(int Nc, int K, float sl2
     if ((qmask >> r) & 1) {
       float res[8];
 #pragma unroll
-      for (int e = 0; e < 8; ++e) res[e] = fmaf(Oa[e] + Ob[e], scale, dqcr[ch * 8 + e] * inv_cnt);
+      for (int e = 0; e < 8; ++e) res[e] = fmaf(Oa[e] + Ob[e], scale, pooled[e]);
       ov = pack8(res);
     }
     dq[(rows0 + c * kTile + r) * CPR + ch] = ov;
@@ -244,7 +256,6 @@ template <int D>
 __global__ __launch_bounds__(256, 1) void k_fine_bwd_dkv(int Nc, int K, float sl2, float scale, const uint4* __restrict__ q,
                                                          const uint4* __restrict__ k, const uint4* __restrict__ v,
                                                          const uint4* __restrict__ dof,
-                                                         const int32_t* __restrict__ row_ptr,
                                                          const int32_t* __restrict__ col,
                                                          const int32_t* __restrict__ order,
                                                          const uint4* __restrict__ ldb,
@@ -259,15 +270,22 @@ __global__ __launch_bounds__(256, 1) void k_fine_bwd_dkv(int Nc, int K, float sl
   __shared__ __attribute__((aligned(16))) unsigned char smem[4 * STAGE];
   static_assert(2 * 64 * OS * 4 <= 4 * STAGE, "merge buffers must fit");
 
+  // Start-up: one descriptor load (key cube, begin and end of its list; the key cubes of a (b, h)
+  // come longest list first), then the list chunk, the key mask and the resident K, V rows all in
+  // flight together, one wait, then the first copies.
   const long long bh = blockIdx.x / Nc;
-  const int j = order[blockIdx.x];  // key cubes of a (b, h) are taken longest list first
+  const int4 desc = ((const int4*)order)[blockIdx.x];
+  const int j = desc.x, beg = desc.y, end = desc.z, n = end - beg;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int kh = wave & 1, qh = wave >> 1, l32 = lane & 31, h = lane >> 5;
   const long long rows0 = bh * (long long)Nc * kTile;
-  const uint64_t kmask = mask[j];
-  const int32_t* rp = row_ptr + bh * (Nc + 1);
-  const int beg = rp[j], end = rp[j + 1];
   const int32_t* my_col = col + bh * (long long)Nc * K;
+  // The list of streamed query cubes sits in a register, 64 entries at a time (lane e holds
+  // entry e of the current chunk), so that the loop reads an index with v_readlane and issues
+  // no scalar or vector memory load of its own.
+  int chunk = 0;
+  int col_v = n > 0 ? my_col[beg + min(lane, n - 1)] : 0;
+  const uint64_t kmask = mask[j];
 
   bf16x8 kreg[KS], vreg[KS];
   {
@@ -283,6 +301,7 @@ __global__ __launch_bounds__(256, 1) void k_fine_bwd_dkv(int Nc, int K, float sl
   // ordinary loads done before the first hand-ordered copy (see Tile::async_load)
 #pragma unroll
   for (int s = 0; s < KS; ++s) asm volatile("" : "+v"(kreg[s]), "+v"(vreg[s]));
+  asm volatile("" : "+v"(col_v));
 
   f32x16 dka[DVB], dva[DVB];
 #pragma unroll
@@ -294,13 +313,6 @@ __global__ __launch_bounds__(256, 1) void k_fine_bwd_dkv(int Nc, int K, float sl
     unsigned goff[TL::IPW];
     TL::lane_offsets(wave, lane, goff);
     const unsigned lds0 = lds_address(smem);
-    const int n = end - beg;
-    // The list of streamed query cubes sits in a register, 64 entries at a time (lane e holds
-    // entry e of the current chunk), so that the loop reads an index with v_readlane and issues
-    // no scalar or vector memory load of its own.
-    int chunk = 0;
-    int col_v = my_col[beg + min(lane, n - 1)];
-    asm volatile("" : "+v"(col_v));
     auto entry = [&](int t) {  // cube of list entry min(t, end - 1)
       const int e = min(t, end - 1) - beg;
       if ((e >> 6) != chunk) {
@@ -507,6 +519,16 @@ __global__ __launch_bounds__(256, 1) void k_fine_bwd_dkv(int Nc, int K, float sl
     }
     wait_vmcnt<0>();  // the refetches issued past the end of the list
   }
+  // the pooled-gradient terms of this thread's column chunk (the same chunk for all of its items),
+  // requested before the partial results go through LDS
+  static_assert(256 % CPR == 0, "a thread keeps its column chunk");
+  float4 pk[2], pv[2];
+  {
+    const float* a = dkc + (bh * Nc + j) * D + (tid % CPR) * 8;
+    const float* b = dvc + (bh * Nc + j) * D + (tid % CPR) * 8;
+    pk[0] = *(const float4*)a, pk[1] = *(const float4*)(a + 4);
+    pv[0] = *(const float4*)b, pv[1] = *(const float4*)(b + 4);
+  }
   __syncthreads();
 
   // merge the two query halves; dK first, then dV through the same buffers
@@ -524,7 +546,9 @@ __global__ __launch_bounds__(256, 1) void k_fine_bwd_dkv(int Nc, int K, float sl
         *(float4*)&Op[l32 * OS + x * 32 + 8 * g4 + 4 * h] = val;
       }
     __syncthreads();
-    const float* pooled = (pass == 0 ? dkc : dvc) + (bh * Nc + j) * D;
+    const float4 p0 = pass == 0 ? pk[0] : pv[0], p1 = pass == 0 ? pk[1] : pv[1];
+    const float pooled[8] = {p0.x * inv_cnt, p0.y * inv_cnt, p0.z * inv_cnt, p0.w * inv_cnt,
+                             p1.x * inv_cnt, p1.y * inv_cnt, p1.z * inv_cnt, p1.w * inv_cnt};
     const float mul = pass == 0 ? scale : 1.0f;
     uint4* dst = pass == 0 ? dk : dv;
 #pragma unroll
@@ -536,7 +560,7 @@ __global__ __launch_bounds__(256, 1) void k_fine_bwd_dkv(int Nc, int K, float sl
       if ((kmask >> r) & 1) {
         float res[8];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) res[e] = fmaf(Oa[e] + Ob[e], mul, pooled[ch * 8 + e] * inv_cnt);
+        for (int e = 0; e < 8; ++e) res[e] = fmaf(Oa[e] + Ob[e], mul, pooled[e]);
         ov = pack8(res);
       }
       dst[(rows0 + j * kTile + r) * CPR + ch] = ov;
@@ -546,18 +570,18 @@ __global__ __launch_bounds__(256, 1) void k_fine_bwd_dkv(int Nc, int K, float sl
 }
 
 hipError_t launch_fine_bwd_dkv(int BH, int Nc, int d, int K, float scale, const void* q, const void* k, const void* v,
-                               const void* dof, const int32_t* row_ptr, const int32_t* col, const int32_t* order,
+                               const void* dof, const int32_t* col, const int32_t* order,
                                const void* ldb, const float* dkc, const float* dvc, const uint64_t* mask, void* dk,
                                void* dv, hipStream_t s) {
   const float sl2 = scale * kLog2e;
   const unsigned grid = (unsigned)(BH * Nc);
   if (d == 128)
     k_fine_bwd_dkv<128><<<grid, 256, 0, s>>>(Nc, K, sl2, scale, (const uint4*)q, (const uint4*)k, (const uint4*)v,
-                                             (const uint4*)dof, row_ptr, col, order, (const uint4*)ldb, dkc, dvc, mask, (uint4*)dk,
+                                             (const uint4*)dof, col, order, (const uint4*)ldb, dkc, dvc, mask, (uint4*)dk,
                                              (uint4*)dv);
   else
     k_fine_bwd_dkv<64><<<grid, 256, 0, s>>>(Nc, K, sl2, scale, (const uint4*)q, (const uint4*)k, (const uint4*)v,
-                                            (const uint4*)dof, row_ptr, col, order, (const uint4*)ldb, dkc, dvc, mask, (uint4*)dk,
+                                            (const uint4*)dof, col, order, (const uint4*)ldb, dkc, dvc, mask, (uint4*)dk,
                                             (uint4*)dv);
   return hipGetLastError();
 }

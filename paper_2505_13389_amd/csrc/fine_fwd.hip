@@ -54,18 +54,6 @@ __global__ __launch_bounds__(256, 2) void k_fine_fwd(int Nc, int K, float sl2, c
   const long long rows0 = bh * (long long)Nc * kTile;  // first row of this (b,h)
   const int32_t* my_idx = idx + (bh * Nc + c) * (long long)K;
 
-  bf16x8 qreg[KS];
-  {
-    const uint4* qrow = q + (rows0 + c * kTile + qh * 32 + l32) * CPR;
-#pragma unroll
-    for (int s = 0; s < KS; ++s) qreg[s] = __builtin_bit_cast(bf16x8, qrow[2 * s + h]);
-  }
-  // Q must have arrived before the first hand-ordered copy is issued: afterwards the compiler's
-  // own vmcnt bookkeeping (which cannot see those copies) has nothing left to wait for in the loop.
-  // The empty asm consumes the registers, so the compiler has to place its wait right here.
-#pragma unroll
-  for (int s = 0; s < KS; ++s) asm volatile("" : "+v"(qreg[s]));
-
   // Software pipeline of the K/V stream.  Two LDS stages; at the top of iteration t the whole
   // tile pair t is pulled from its stage into registers (MFMA operands), which frees the stage
   // at once for tile t+2, so two tile pairs per workgroup are in flight behind the math of one.
@@ -79,19 +67,31 @@ __global__ __launch_bounds__(256, 2) void k_fine_fwd(int Nc, int K, float sl2, c
     TL::async_load(k, rows0 + (long long)j * kTile, st, wave, goff);
     TL::async_load(v, rows0 + (long long)j * kTile, st + TL::BYTES, wave, goff);
   };
-  // Every iteration issues exactly NL copies, also past the end of the list (the last tile is
-  // simply fetched again): the number of copies younger than the tile being waited for is then
-  // always NL, which both the hand-written waits and the compiler's own bookkeeping rely on.
+  // Start-up order: the list first (one round trip), then the copies of tiles 0 and 1, and only
+  // then the loads of the key masks and of Q, so that everything the first iteration needs is in
+  // flight together.  The empty asm below consumes the loaded registers: the compiler has to place
+  // its wait for them right there (it also drains the two copies, which it cannot see), and its
+  // own vmcnt bookkeeping has nothing left to wait for inside the loop.
   // km0 / km1: valid-key masks (this wave's key half) of the tile of this iteration / the next
   CubeList cubes;
   cubes.init(my_idx, mask, K, kh, lane);
+  issue(stage0, cubes.cube(0));
+  issue(stage1, cubes.cube(min(1, K - 1)));
+  cubes.load_masks();
+  bf16x8 qreg[KS];
+  {
+    const uint4* qrow = q + (rows0 + c * kTile + qh * 32 + l32) * CPR;
+#pragma unroll
+    for (int s = 0; s < KS; ++s) qreg[s] = __builtin_bit_cast(bf16x8, qrow[2 * s + h]);
+  }
+#pragma unroll
+  for (int s = 0; s < KS; ++s) asm volatile("" : "+v"(qreg[s]));
+  asm volatile("" : "+v"(cubes.km_v));
   uint32_t km0, km1;
   {
     int j0, j1;
     cubes.get(0, j0, km0);
     cubes.get(min(1, K - 1), j1, km1);
-    issue(stage0, j0);
-    issue(stage1, j1);
   }
 
   float mref = -INFINITY, lsum = 0.f;
@@ -106,7 +106,8 @@ __global__ __launch_bounds__(256, 2) void k_fine_fwd(int Nc, int K, float sl2, c
 
   auto body = [&](unsigned char* cur, int t) {
     const uint32_t kmask = km0;
-    wait_vmcnt<NL>();  // this wave's share of tile pair t has landed (only the NL copies of t+1 may be pending)
+    // this wave's share of tile pair t has landed (only the NL copies of t+1 may be pending)
+    if (t + 1 < K) wait_vmcnt<NL>(); else wait_vmcnt<0>();
     __builtin_amdgcn_s_barrier();
     const unsigned char* Ks = cur;
     const unsigned char* Vs = cur + TL::BYTES;
@@ -122,9 +123,11 @@ __global__ __launch_bounds__(256, 2) void k_fine_fwd(int Nc, int K, float sl2, c
     __builtin_amdgcn_s_barrier();
     {
       int j2;
-      uint32_t km2;
-      cubes.get(min(t + 2, K - 1), j2, km2);
-      issue(cur, j2);
+      uint32_t km2 = 0;
+      if (t + 2 < K) {
+        cubes.get(t + 2, j2, km2);
+        issue(cur, j2);
+      }
       km0 = km1;
       km1 = km2;
     }
@@ -188,10 +191,24 @@ __global__ __launch_bounds__(256, 2) void k_fine_fwd(int Nc, int K, float sl2, c
     body(stage0, t);
     if (t + 1 < K) body(stage1, t + 1);
   }
-  wait_vmcnt<0>();  // the two refetches issued past the end of the list
   __syncthreads();
 
   // ---- merge the two key halves, normalise, gate, store
+  // The gates and the coarse output of this thread's items are requested first: they arrive while
+  // the partial results go through LDS.  Pad rows are loaded too (they exist in memory) and ignored.
+  const uint64_t qmask = mask[c];
+  uint4 gc_raw[LPT], gf_raw[LPT];
+  float4 oc_raw[LPT][2];
+#pragma unroll
+  for (int it = 0; it < LPT; ++it) {
+    const int item = it * 256 + tid, r = item / CPR, ch = item % CPR;
+    const long long g = (rows0 + c * kTile + r) * CPR + ch;
+    const float* ocr = oc + (bh * Nc + c) * D + ch * 8;
+    gc_raw[it] = gc[g];
+    gf_raw[it] = gf ? gf[g] : make_uint4(0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u);  // bf16 ones
+    oc_raw[it][0] = *(const float4*)ocr;
+    oc_raw[it][1] = *(const float4*)(ocr + 4);
+  }
   // Partial O of wave (qh, kh) goes to rows qh*32.. of stage `kh` (fp32 [64][D] each).
   lsum += __shfl_xor(lsum, 32);
   {
@@ -210,8 +227,6 @@ __global__ __launch_bounds__(256, 2) void k_fine_fwd(int Nc, int K, float sl2, c
   }
   __syncthreads();
 
-  const uint64_t qmask = mask[c];
-  const float* ocr = oc + (bh * Nc + c) * D;
 #pragma unroll
   for (int it = 0; it < LPT; ++it) {
     const int item = it * 256 + tid, r = item / CPR, ch = item % CPR;
@@ -234,13 +249,9 @@ __global__ __launch_bounds__(256, 2) void k_fine_fwd(int Nc, int K, float sl2, c
     uint4 ov = make_uint4(0, 0, 0, 0), fv = make_uint4(0, 0, 0, 0);
     if (valid) {
       float gcv[8], gfv[8];
-      unpack8(gc[g], gcv);
-      if (gf) unpack8(gf[g], gfv);
-      else {
-#pragma unroll
-        for (int e = 0; e < 8; ++e) gfv[e] = 1.f;
-      }
-      const float4 c0 = *(const float4*)(ocr + ch * 8), c1 = *(const float4*)(ocr + ch * 8 + 4);
+      unpack8(gc_raw[it], gcv);
+      unpack8(gf_raw[it], gfv);
+      const float4 c0 = oc_raw[it][0], c1 = oc_raw[it][1];
       const float ocv[8] = {c0.x, c0.y, c0.z, c0.w, c1.x, c1.y, c1.z, c1.w};
 #pragma unroll
       for (int e = 0; e < 8; ++e) res[e] = fmaf(ocv[e], gcv[e], of[e] * gfv[e]);

@@ -73,18 +73,28 @@ struct CubeList {
   const uint64_t* mask;
   int n, half, lane, chunk, idx_v;
   uint32_t km_v;
-  __device__ __forceinline__ void load_chunk(int c) {
+  __device__ __forceinline__ void load_indices(int c) {
     chunk = c;
     idx_v = list[min((c << 6) + lane, n - 1)];
+    asm volatile("" : "+v"(idx_v));  // consumed at once: the compiler's wait for the load is placed right here
+  }
+  __device__ __forceinline__ void load_masks() {
     const uint64_t m = mask[idx_v];
     km_v = half ? (uint32_t)(m >> 32) : (uint32_t)m;
-    // consumed at once: the compiler's wait for these loads is placed right here
-    asm volatile("" : "+v"(idx_v), "+v"(km_v));
   }
+  __device__ __forceinline__ void load_chunk(int c) {
+    load_indices(c);
+    load_masks();
+    asm volatile("" : "+v"(km_v));
+  }
+  // After init() the cube indices of the first chunk are there (cube() works); the key masks are
+  // still in flight until the caller's next wait for its own loads, so that the first copies can
+  // be issued one memory round trip earlier.
   __device__ __forceinline__ void init(const int32_t* list_, const uint64_t* mask_, int n_, int half_, int lane_) {
     list = list_, mask = mask_, n = n_, half = half_, lane = lane_;
-    load_chunk(0);
+    load_indices(0);
   }
+  __device__ __forceinline__ int cube(int e) const { return __builtin_amdgcn_readlane(idx_v, e & 63); }
   // cube index and key mask of entry e (wave-uniform, 0 <= e < n)
   __device__ __forceinline__ void get(int e, int& cube, uint32_t& km) {
     if ((e >> 6) != chunk) load_chunk(e >> 6);

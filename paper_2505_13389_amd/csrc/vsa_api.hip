@@ -103,7 +103,7 @@ BwdWs carve_bwd(const vsa_params_t* p, const Geo& g, void* ws) {
   w.row_ptr = c.take<int32_t>(bh * (g.Nc + 1));
   w.col = c.take<int32_t>(bh * g.Nc * p->topk);
   w.bits = c.take<uint32_t>(bh * g.Nc * ((g.Nc + 31) / 32));
-  w.order = c.take<int32_t>(bh * g.Nc);
+  w.order = c.take<int32_t>(4 * bh * g.Nc);  // (cube, list begin, list end, 0) per dK/dV workgroup
   w.bytes = c.used;
   return w;
 }
@@ -237,7 +237,7 @@ int vsa_backward(const vsa_params_t* p, const void* q, const void* k, const void
   VSA_TRY("transpose_map", vsa::launch_transpose_map(BH, g.Nc, p->topk, block_idx, w.bits, w.row_ptr, w.col, w.order, s));
   VSA_TRY("fine_bwd_dq", vsa::launch_fine_bwd_dq(BH, g.Nc, p->d, p->topk, scale, q, k, v, w.dof, block_idx, w.ld,
                                   w.dqc, w.mask, dq, s));
-  VSA_TRY("fine_bwd_dkv", vsa::launch_fine_bwd_dkv(BH, g.Nc, p->d, p->topk, scale, q, k, v, w.dof, w.row_ptr, w.col, w.order, w.ldb, w.dkc,
+  VSA_TRY("fine_bwd_dkv", vsa::launch_fine_bwd_dkv(BH, g.Nc, p->d, p->topk, scale, q, k, v, w.dof, w.col, w.order, w.ldb, w.dkc,
                                    w.dvc, w.mask, dk, dv, s));
   return VSA_OK;
 }

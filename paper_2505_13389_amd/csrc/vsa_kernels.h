@@ -31,7 +31,7 @@ hipError_t launch_fine_bwd_dq(int BH, int Nc, int d, int K, float scale, const v
                               const void* dof, const int32_t* idx, const float* ld,
                               const float* dqc, const uint64_t* mask, void* dq, hipStream_t s);
 hipError_t launch_fine_bwd_dkv(int BH, int Nc, int d, int K, float scale, const void* q, const void* k, const void* v,
-                               const void* dof, const int32_t* row_ptr, const int32_t* col, const int32_t* order,
+                               const void* dof, const int32_t* col, const int32_t* order,
                                const void* ldb, const float* dkc, const float* dvc, const uint64_t* mask, void* dk,
                                void* dv, hipStream_t s);
 
