@@ -35,9 +35,13 @@ __global__ __launch_bounds__(256, 2) void k_fine_bwd_dq(int Nc, int K, float sl2
   __shared__ __attribute__((aligned(16))) unsigned char stage1[STAGE];
   static_assert(2 * 32 * OS * 4 <= STAGE, "merge buffer must fit in one stage");
 
-  const unsigned wg = xcd_chunked_id(blockIdx.x, gridDim.x);
+  // (K = Nc: plain blockIdx order and staggered walks, as in the forward kernel)
+  const bool same_lists = K == Nc;
+  const unsigned wg = same_lists ? blockIdx.x : xcd_chunked_id(blockIdx.x, gridDim.x);
   const int c = wg % Nc;
   const long long bh = wg / Nc;
+  const int rot = same_lists ? ((c >> 3) & 15) % K : 0;
+  auto ent = [&](int t) { const int e = t + rot; return e >= K ? e - K : e; };
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int qh = wave & 1, kh = wave >> 1, l32 = lane & 31, h = lane >> 5;
   const long long rows0 = bh * (long long)Nc * kTile;
@@ -54,7 +58,7 @@ __global__ __launch_bounds__(256, 2) void k_fine_bwd_dq(int Nc, int K, float sl2
   CubeList cubes;
   cubes.init(my_idx, mask, K, kh, lane);
   {
-    const int jt = cubes.cube(0);
+    const int jt = cubes.cube(ent(0));
     TL::async_load(k, rows0 + (long long)jt * kTile, stage0, wave, goff);
     TL::async_load(v, rows0 + (long long)jt * kTile, stage0 + TL::BYTES, wave, goff);
   }
@@ -79,7 +83,7 @@ __global__ __launch_bounds__(256, 2) void k_fine_bwd_dq(int Nc, int K, float sl2
   uint32_t km_cur;  // valid-key mask (this wave's key half) of the tile of this iteration
   {
     int jt;
-    cubes.get(0, jt, km_cur);
+    cubes.get(ent(0), jt, km_cur);
   }
 
   f32x16 acc[DVB];
@@ -117,7 +121,7 @@ __global__ __launch_bounds__(256, 2) void k_fine_bwd_dq(int Nc, int K, float sl2
     __builtin_amdgcn_s_barrier();
     if (t + 1 < K) {
       int jt;
-      cubes.get(t + 1, jt, km_cur);
+      cubes.get(ent(t + 1), jt, km_cur);
       TL::async_load(k, rows0 + (long long)jt * kTile, nxt, wave, goff);
       TL::async_load(v, rows0 + (long long)jt * kTile, nxt + TL::BYTES, wave, goff);
     }

@@ -46,9 +46,16 @@ __global__ __launch_bounds__(256, 2) void k_fine_fwd(int Nc, int K, float sl2, c
   __shared__ float ml[4 * 32 * 2];
   static_assert(2 * 32 * OS * 4 <= STAGE, "merge buffer must fit in one stage");
 
-  const unsigned wg = xcd_chunked_id(blockIdx.x, gridDim.x);
+  // With K = Nc every workgroup of a head walks the same list: then all XCDs work on the same head
+  // (plain blockIdx order), which keeps that list's tiles shared chip-wide, and the workgroups that
+  // run side by side on an XCD (cubes c, c+8, ...) start their walk a few entries apart and wrap
+  // around -- otherwise they ask for the same cache lines in the same cycles.
+  const bool same_lists = K == Nc;
+  const unsigned wg = same_lists ? blockIdx.x : xcd_chunked_id(blockIdx.x, gridDim.x);
   const int c = wg % Nc;
   const long long bh = wg / Nc;
+  const int rot = same_lists ? ((c >> 3) & 15) % K : 0;
+  auto ent = [&](int t) { const int e = t + rot; return e >= K ? e - K : e; };
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int qh = wave & 1, kh = wave >> 1, l32 = lane & 31, h = lane >> 5;
   const long long rows0 = bh * (long long)Nc * kTile;  // first row of this (b,h)
@@ -75,8 +82,8 @@ __global__ __launch_bounds__(256, 2) void k_fine_fwd(int Nc, int K, float sl2, c
   // km0 / km1: valid-key masks (this wave's key half) of the tile of this iteration / the next
   CubeList cubes;
   cubes.init(my_idx, mask, K, kh, lane);
-  issue(stage0, cubes.cube(0));
-  issue(stage1, cubes.cube(min(1, K - 1)));
+  issue(stage0, cubes.cube(ent(0)));
+  issue(stage1, cubes.cube(ent(min(1, K - 1))));
   cubes.load_masks();
   bf16x8 qreg[KS];
   {
@@ -90,8 +97,8 @@ __global__ __launch_bounds__(256, 2) void k_fine_fwd(int Nc, int K, float sl2, c
   uint32_t km0, km1;
   {
     int j0, j1;
-    cubes.get(0, j0, km0);
-    cubes.get(min(1, K - 1), j1, km1);
+    cubes.get(ent(0), j0, km0);
+    cubes.get(ent(min(1, K - 1)), j1, km1);
   }
 
   float mref = -INFINITY, lsum = 0.f;
@@ -125,7 +132,7 @@ __global__ __launch_bounds__(256, 2) void k_fine_fwd(int Nc, int K, float sl2, c
       int j2;
       uint32_t km2 = 0;
       if (t + 2 < K) {
-        cubes.get(t + 2, j2, km2);
+        cubes.get(ent(t + 2), j2, km2);
         issue(cur, j2);
       }
       km0 = km1;
