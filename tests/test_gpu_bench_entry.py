@@ -34,3 +34,18 @@ def test_selection_quality_diagnostic_on_planted_inputs(monkeypatch, capsys):
     assert line["mass_on_random_cubes"] < 0.5 * line["mass_on_selected_cubes"]
     assert line["mass_on_selected_cubes"] <= line["mass_on_best_cubes"] + 1e-9
     assert abs(line["mass_on_random_cubes"] - line["density"]) < 0.1
+
+
+def test_topk_sweep_runs_and_scales_with_density(monkeypatch, capsys):
+    """The sweep module: one shape, three top-K settings; time must grow with top-K and the
+    dense setting must be its own reference."""
+    import sys
+    from paper_2505_13389_amd import sweep
+    monkeypatch.setattr(sys, "argv", ["sweep", "--heads", "8", "--dims", "64", "--topk", "16", "64",
+                                      "--steps", "5", "--warmup", "2"])
+    rows = sweep.main()
+    by_k = {r["topk"]: r for r in rows}
+    assert sorted(by_k) == [16, 64, 256]
+    assert by_k[256]["fwd_bwd_speedup_vs_dense"] == 1.0
+    assert by_k[16]["fwd_bwd_ms"] < by_k[64]["fwd_bwd_ms"] < by_k[256]["fwd_bwd_ms"]
+    assert 1.0 < by_k[64]["fwd_bwd_speedup_vs_dense"] <= by_k[64]["ideal_speedup"] * 1.05
