@@ -21,6 +21,11 @@ SMALL = {
     "pad128": Workload("pad128", 2, 1, 6, 10, 9, 128, 5),
     "one_cube": Workload("one_cube", 1, 1, 4, 4, 4, 64, 1),
     "k1": Workload("k1", 1, 2, 8, 8, 8, 128, 1),
+    # two and three entries: the first / last iterations of the copy pipelines with nothing in between
+    "k2": Workload("k2", 1, 2, 8, 8, 8, 64, 2),
+    "k3_d128": Workload("k3_d128", 1, 2, 8, 8, 12, 128, 3),
+    # top-K = all cubes with more than 8 cubes: the staggered list walk of that setting wraps around
+    "dense_pad128": Workload("dense_pad128", 1, 2, 10, 14, 13, 128, 48),
     "planted": Workload("planted", 1, 2, 8, 16, 16, 64, 8, planted=True),
     "planted_pad128": Workload("planted_pad128", 1, 2, 7, 14, 15, 128, 6, planted=True),
     # other 64-token cube shapes (Sec. 3.2 ablates the tile shape; the volume is what the kernels fix)
@@ -123,7 +128,7 @@ def test_topk_ties_go_to_the_lower_index(vsa):
 
 # ------------------------------------------------------------------------------ forward
 @pytest.mark.parametrize("name", ["tiny", "tiny_dense", "tiny128", "pad64", "pad128", "one_cube", "k1", "cube_2x4x8",
-                                  "cube_1x8x8", "k64", "k65"])
+                                  "cube_1x8x8", "k64", "k65", "k2", "k3_d128", "dense_pad128"])
 @pytest.mark.parametrize("with_gate_f", [True, False])
 def test_forward_on_oracle_indices(vsa, name, with_gate_f):
     """The fine kernel on the oracle's own selection: a near-tie flip can neither hide nor fake an error."""
@@ -191,7 +196,7 @@ def test_forward_is_deterministic_and_ignores_pad_slots(vsa):
 
 # ------------------------------------------------------------------------------ backward
 @pytest.mark.parametrize("name", ["tiny", "tiny_dense", "tiny128", "pad64", "pad128", "one_cube", "k1", "planted",
-                                  "cube_2x4x8", "cube_1x8x8", "k64", "k65"])
+                                  "cube_2x4x8", "cube_1x8x8", "k64", "k65", "k2", "k3_d128", "dense_pad128"])
 @pytest.mark.parametrize("with_gate_f", [True, False])
 def test_backward_on_oracle_indices(vsa, name, with_gate_f):
     import torch
