@@ -352,9 +352,10 @@ __device__ __forceinline__ int block_scan4(int* v, int* wsum, int tid) {
 
 // exclusive scan of the in-degrees of one (b, h), in place; row_ptr[Nc] = total.  Also sorts the
 // key cubes by in-degree, longest list first (counting sort; the order among equal degrees is
-// whatever the LDS atomics give, it only decides which workgroup starts when): `order` is the
-// sequence in which the dK/dV pass takes them, so that the workgroups still running at the end of
-// the launch are the short ones.
+// whatever the LDS atomics give, it only decides which workgroup starts when): `order` holds one
+// 16-byte descriptor (key cube, begin and end of its list in col, 0) per dK/dV workgroup, in the
+// sequence in which that pass takes them, so that the workgroups still running at the end of the
+// launch are the short ones and a workgroup finds its list with a single load.
 __global__ __launch_bounds__(1024) void k_map_scan(int Nc, int32_t* __restrict__ row_ptr, int32_t* __restrict__ order) {
   __shared__ int wsum[16];
   __shared__ int hist[kMaxCubes];  // bucket x: cubes of in-degree Nc - x (the last bucket also takes
