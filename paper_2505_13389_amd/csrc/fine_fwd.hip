@@ -61,29 +61,26 @@ __global__ __launch_bounds__(256, 2) void k_fine_fwd(int Nc, int K, float sl2, c
   const long long rows0 = bh * (long long)Nc * kTile;  // first row of this (b,h)
   const int32_t* my_idx = idx + (bh * Nc + c) * (long long)K;
 
-  // Software pipeline of the K/V stream.  Two LDS stages; at the top of iteration t the whole
-  // tile pair t is pulled from its stage into registers (MFMA operands), which frees the stage
-  // at once for tile t+2, so two tile pairs per workgroup are in flight behind the math of one.
-  //   wait(own share of tile t landed) ; barrier ; LDS -> registers ; barrier ; refill ; math
-  // The barriers are raw s_barrier (no fence): a fence would drain the copies still in flight.
-  // vmcnt is waited by hand: copies complete in issue order, NL = copies per wave and tile pair.
-  constexpr int NL = 2 * TL::IPW;
+  // Software pipeline of the K/V stream: two LDS stages (K tile + V tile each), the copy of tile
+  // t+1 runs behind the math of tile t.  Per tile: wait for this wave's share of tile t, one
+  // barrier (tile t complete; every wave is done with tile t-1), start the copy of tile t+1 into
+  // the other stage, do the math with operands read from LDS just ahead of their use.
+  // The barrier is a raw s_barrier (no fence): a fence would drain the copy still in flight.
+  // vmcnt is waited by hand (the compiler cannot see the copies; see Tile::async_load).
   unsigned goff[TL::IPW];
   TL::lane_offsets(wave, lane, goff);
   auto issue = [&](unsigned char* st, int j) {
     TL::async_load(k, rows0 + (long long)j * kTile, st, wave, goff);
     TL::async_load(v, rows0 + (long long)j * kTile, st + TL::BYTES, wave, goff);
   };
-  // Start-up order: the list first (one round trip), then the copies of tiles 0 and 1, and only
-  // then the loads of the key masks and of Q, so that everything the first iteration needs is in
-  // flight together.  The empty asm below consumes the loaded registers: the compiler has to place
-  // its wait for them right there (it also drains the two copies, which it cannot see), and its
-  // own vmcnt bookkeeping has nothing left to wait for inside the loop.
-  // km0 / km1: valid-key masks (this wave's key half) of the tile of this iteration / the next
+  // Start-up order: the list first (one round trip), then the copy of tile 0, and only then the
+  // loads of the key masks and of Q, so that everything the first iteration needs is in flight
+  // together.  The empty asm below consumes the loaded registers: the compiler has to place its
+  // wait for them right there (it also drains the copy), and its own vmcnt bookkeeping has nothing
+  // left to wait for inside the loop.
   CubeList cubes;
   cubes.init(my_idx, mask, K, kh, lane);
   issue(stage0, cubes.cube(ent(0)));
-  issue(stage1, cubes.cube(ent(min(1, K - 1))));
   cubes.load_masks();
   bf16x8 qreg[KS];
   {
@@ -94,12 +91,14 @@ __global__ __launch_bounds__(256, 2) void k_fine_fwd(int Nc, int K, float sl2, c
 #pragma unroll
   for (int s = 0; s < KS; ++s) asm volatile("" : "+v"(qreg[s]));
   asm volatile("" : "+v"(cubes.km_v));
-  uint32_t km0, km1;
+  uint32_t km_cur;  // valid-key mask (this wave's key half) of the tile of this iteration
   {
-    int j0, j1;
-    cubes.get(ent(0), j0, km0);
-    cubes.get(ent(min(1, K - 1)), j1, km1);
+    int j0;
+    cubes.get(ent(0), j0, km_cur);
   }
+  const int lane_a = TL::rowmajor_lane(kh * 32, lane);
+  int lane_b0, lane_b1;
+  TL::transposed_lane(kh * 32, lane, lane_b0, lane_b1);
 
   float mref = -INFINITY, lsum = 0.f;
   const bf16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
@@ -111,40 +110,45 @@ __global__ __launch_bounds__(256, 2) void k_fine_fwd(int Nc, int K, float sl2, c
 #pragma unroll
     for (int i = 0; i < 16; ++i) o[x][i] = 0.f;
 
-  auto body = [&](unsigned char* cur, int t) {
-    const uint32_t kmask = km0;
-    // this wave's share of tile pair t has landed (only the NL copies of t+1 may be pending)
-    if (t + 1 < K) wait_vmcnt<NL>(); else wait_vmcnt<0>();
+  auto body = [&](const unsigned char* cur, unsigned char* nxt, int t) {
+    const uint32_t kmask = km_cur;
+    wait_vmcnt<0>();
     __builtin_amdgcn_s_barrier();
+    if (t + 1 < K) {
+      int jn;
+      cubes.get(ent(t + 1), jn, km_cur);
+      issue(nxt, jn);
+    }
+    __builtin_amdgcn_sched_barrier(0);
     const unsigned char* Ks = cur;
     const unsigned char* Vs = cur + TL::BYTES;
-    bf16x8 ka[KS], va[DVB][2];
+    // Operand i: K rows (S^T steps), then transposed V (O^T steps).  The K operands are requested a
+    // fixed number of matrix instructions ahead of their use, the V operands during the last S^T
+    // steps and the softmax arithmetic; addresses are rebuilt from three lane values (one XOR each).
+    int la = lane_a, lb0 = lane_b0, lb1 = lane_b1;
+    asm volatile("" : "+v"(la), "+v"(lb0), "+v"(lb1));
+    constexpr int NOP = KS + 2 * DVB, AHEAD = 4;
+    bf16x8 op[NOP];
+    auto read_op = [&](int i) {
+      if (i < KS) return TL::rowmajor_at(Ks, la, i);
+      const int j = i - KS;
+      return TL::transposed_at(Vs, lb0, lb1, j & 1, j >> 1);
+    };
 #pragma unroll
-    for (int s = 0; s < KS; ++s) ka[s] = TL::rowmajor_operand(Ks, kh * 32, s, lane);
-#pragma unroll
-    for (int x = 0; x < DVB; ++x) {
-      va[x][0] = TL::transposed_operand(Vs, kh * 32, 0, x * 32, lane);
-      va[x][1] = TL::transposed_operand(Vs, kh * 32, 1, x * 32, lane);
-    }
-    wait_lgkmcnt0();  // this wave's LDS reads of the stage are done
-    __builtin_amdgcn_s_barrier();
-    {
-      int j2;
-      uint32_t km2 = 0;
-      if (t + 2 < K) {
-        cubes.get(ent(t + 2), j2, km2);
-        issue(cur, j2);
-      }
-      km0 = km1;
-      km1 = km2;
-    }
+    for (int i = 0; i < AHEAD; ++i) op[i] = read_op(i);
     __builtin_amdgcn_sched_barrier(0);
 
     f32x16 sacc;
 #pragma unroll
     for (int i = 0; i < 16; ++i) sacc[i] = 0.f;
 #pragma unroll
-    for (int s = 0; s < KS; ++s) sacc = mfma32(ka[s], qreg[s], sacc);
+    for (int i = 0; i < KS; ++i) {
+      sacc = mfma32(op[i], qreg[i], sacc);
+      op[i + AHEAD] = read_op(i + AHEAD);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+#pragma unroll
+    for (int i = KS + AHEAD; i < NOP; ++i) op[i] = read_op(i);
 
     // Pad keys of a partially filled cube never take part: one extra MFMA adds a large negative
     // bias to their rows of S^T (A = bias of key l%32 in contraction slot 0, B = ones in slot 0).
@@ -189,14 +193,14 @@ __global__ __launch_bounds__(256, 2) void k_fine_fwd(int Nc, int K, float sl2, c
     const bf16x8 pb0 = acc_to_operand(p), pb1 = acc_to_operand(p + 8);
 #pragma unroll
     for (int x = 0; x < DVB; ++x) {
-      o[x] = mfma32(va[x][0], pb0, o[x]);
-      o[x] = mfma32(va[x][1], pb1, o[x]);
+      o[x] = mfma32(op[KS + 2 * x], pb0, o[x]);
+      o[x] = mfma32(op[KS + 2 * x + 1], pb1, o[x]);
     }
   };
 
   for (int t = 0; t < K; t += 2) {
-    body(stage0, t);
-    if (t + 1 < K) body(stage1, t + 1);
+    body(stage0, stage1, t);
+    if (t + 1 < K) body(stage1, stage0, t + 1);
   }
   __syncthreads();
 
