@@ -115,16 +115,32 @@ __global__ __launch_bounds__(256, 2) void k_fine_bwd_dq(int Nc, int K, float sl2
 
   // Per tile: wait for this wave's share of tile t, barrier (tile t complete, and every wave is
   // done with tile t-1), start the copy of tile t+1 into the other stage, do the math on tile t.
-  auto body = [&](const unsigned char* cur, unsigned char* nxt, int t) {
+  auto body = [&](auto copy_tag, const unsigned char* cur, unsigned char* nxt, int t) {
+    constexpr bool COPY = decltype(copy_tag)::value;  // false for the last tile of the list
     const uint32_t mh = km_cur;
     wait_vmcnt<0>();
     __builtin_amdgcn_s_barrier();
-    if (t + 1 < K) {
-      int jt;
-      cubes.get(ent(t + 1), jt, km_cur);
-      TL::async_load(k, rows0 + (long long)jt * kTile, nxt, wave, goff);
-      TL::async_load(v, rows0 + (long long)jt * kTile, nxt + TL::BYTES, wave, goff);
-    }
+    // The copy of the next tile is not issued in one burst here -- eight wavefronts doing that at
+    // the same moment queue up behind one another in the load path and stall -- but one
+    // instruction per matrix step below.
+    int jt = 0;
+    if (COPY) cubes.get(ent(t + 1), jt, km_cur);
+    const void* gk = uniform_ptr(k + (rows0 + (long long)jt * kTile) * CPR);
+    const void* gv = uniform_ptr(v + (rows0 + (long long)jt * kTile) * CPR);
+    const unsigned ln = __builtin_amdgcn_readfirstlane(lds_address(nxt) + (unsigned)(wave * TL::IPW) * 1024u);
+    auto copy_piece = [&](int i) {
+      if (!COPY) return;
+      if (i == 0) set_m0(ln);
+      if (i == TL::IPW) set_m0(ln + TL::BYTES);
+      if (i < 2 * TL::IPW) {
+        const void* g = i < TL::IPW ? gk : gv;
+        const int r = i % TL::IPW;
+        if (r == 0) lds_dma16_at<0>(g, goff[0]);
+        if (r == 1) lds_dma16_at<1024>(g, goff[1 % TL::IPW]);
+        if (r == 2) lds_dma16_at<2048>(g, goff[2 % TL::IPW]);
+        if (r == 3) lds_dma16_at<3072>(g, goff[3 % TL::IPW]);
+      }
+    };
     __builtin_amdgcn_sched_barrier(0);
     const unsigned char* Ks = cur;
     const unsigned char* Vs = cur + TL::BYTES;
@@ -155,6 +171,7 @@ __global__ __launch_bounds__(256, 2) void k_fine_bwd_dq(int Nc, int K, float sl2
       if (i < KS) sacc = mfma32(op[i], qreg[i < KS ? i : 0], sacc);
       else dpacc = mfma32(op[i], doreg[i < KS ? 0 : i - KS], dpacc);
       if (i + AHEAD < NOP) op[i + AHEAD] = read_op(i + AHEAD);
+      if (!(i & 1)) copy_piece(i >> 1);
       __builtin_amdgcn_sched_barrier(0);
     }
 
@@ -179,9 +196,20 @@ __global__ __launch_bounds__(256, 2) void k_fine_bwd_dq(int Nc, int K, float sl2
     }
   };
 
-  for (int t = 0; t < K; t += 2) {
-    body(stage0, stage1, t);
-    if (t + 1 < K) body(stage1, stage0, t + 1);
+  {
+    const std::true_type copy;
+    const std::false_type last;
+    int t = 0;
+    for (; t + 2 < K; t += 2) {
+      body(copy, stage0, stage1, t);
+      body(copy, stage1, stage0, t + 1);
+    }
+    if (t + 1 < K) {
+      body(copy, stage0, stage1, t);
+      body(last, stage1, stage0, t + 1);
+    } else {
+      body(last, stage0, stage1, t);
+    }
   }
   // the pooled-gradient term of this thread's column chunk (the same chunk for all of its items),
   // requested before the partial results go through LDS

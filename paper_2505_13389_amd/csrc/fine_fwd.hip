@@ -13,6 +13,8 @@
 //   O^T[dv,  q] += V_tile^T (A operand, transposing LDS reads) x P^T (B operand = the S^T
 //                  accumulator registers converted to bf16 in place)
 // In the 32x32 accumulator layout lane l holds query column l%32 and 16 key (or dv) rows.
+#include <type_traits>
+
 #include "fine_tile.h"
 #include "vsa_kernels.h"
 
@@ -110,15 +112,33 @@ __global__ __launch_bounds__(256, 2) void k_fine_fwd(int Nc, int K, float sl2, c
 #pragma unroll
     for (int i = 0; i < 16; ++i) o[x][i] = 0.f;
 
-  auto body = [&](const unsigned char* cur, unsigned char* nxt, int t) {
+  auto body = [&](auto copy_tag, const unsigned char* cur, unsigned char* nxt, int t) {
+    constexpr bool COPY = decltype(copy_tag)::value;  // false for the last tile of the list
     const uint32_t kmask = km_cur;
     wait_vmcnt<0>();
     __builtin_amdgcn_s_barrier();
-    if (t + 1 < K) {
-      int jn;
-      cubes.get(ent(t + 1), jn, km_cur);
-      issue(nxt, jn);
-    }
+    // The copy of the next tile is not issued in one burst here -- eight wavefronts doing that at
+    // the same moment queue up behind one another in the load path and stall -- but one
+    // instruction per S^T step below.
+    int jn = 0;
+    if (COPY) cubes.get(ent(t + 1), jn, km_cur);
+    const void* gk = uniform_ptr(k + (rows0 + (long long)jn * kTile) * CPR);
+    const void* gv = uniform_ptr(v + (rows0 + (long long)jn * kTile) * CPR);
+    const unsigned ln = __builtin_amdgcn_readfirstlane(lds_address(nxt) + (unsigned)(wave * TL::IPW) * 1024u);
+    auto copy_piece = [&](int i) {
+      if (!COPY) return;
+      if (i == 0) set_m0(ln);
+      if (i == TL::IPW) set_m0(ln + TL::BYTES);
+      if (i < 2 * TL::IPW) {
+        const void* g = i < TL::IPW ? gk : gv;
+        const int r = i % TL::IPW;
+        if (r == 0) lds_dma16_at<0>(g, goff[0]);
+        if (r == 1) lds_dma16_at<1024>(g, goff[1 % TL::IPW]);
+        if (r == 2) lds_dma16_at<2048>(g, goff[2 % TL::IPW]);
+        if (r == 3) lds_dma16_at<3072>(g, goff[3 % TL::IPW]);
+      }
+    };
+    constexpr int PIECES_PER_STEP = (2 * TL::IPW + KS - 1) / KS;
     __builtin_amdgcn_sched_barrier(0);
     const unsigned char* Ks = cur;
     const unsigned char* Vs = cur + TL::BYTES;
@@ -145,6 +165,8 @@ __global__ __launch_bounds__(256, 2) void k_fine_fwd(int Nc, int K, float sl2, c
     for (int i = 0; i < KS; ++i) {
       sacc = mfma32(op[i], qreg[i], sacc);
       op[i + AHEAD] = read_op(i + AHEAD);
+#pragma unroll
+      for (int c2 = 0; c2 < PIECES_PER_STEP; ++c2) copy_piece(i * PIECES_PER_STEP + c2);
       __builtin_amdgcn_sched_barrier(0);
     }
 #pragma unroll
@@ -198,9 +220,20 @@ __global__ __launch_bounds__(256, 2) void k_fine_fwd(int Nc, int K, float sl2, c
     }
   };
 
-  for (int t = 0; t < K; t += 2) {
-    body(stage0, stage1, t);
-    if (t + 1 < K) body(stage1, stage0, t + 1);
+  {
+    const std::true_type copy;
+    const std::false_type last;
+    int t = 0;
+    for (; t + 2 < K; t += 2) {
+      body(copy, stage0, stage1, t);
+      body(copy, stage1, stage0, t + 1);
+    }
+    if (t + 1 < K) {
+      body(copy, stage0, stage1, t);
+      body(last, stage1, stage0, t + 1);
+    } else {
+      body(last, stage0, stage1, t);
+    }
   }
   __syncthreads();
 
