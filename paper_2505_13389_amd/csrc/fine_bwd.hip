@@ -300,7 +300,6 @@ __global__ __launch_bounds__(256, 1) void k_fine_bwd_dkv(int Nc, int K, float sl
   constexpr int STAGE = 2 * TL::BYTES + kTile * 16;  // Q tile, dOf tile, 16 bytes of (lse2, Delta) operand slots per row
   constexpr int NLP = 2 * TL::IPW + 1;                  // copies per wave and stage
   __shared__ __attribute__((aligned(16))) unsigned char smem[4 * STAGE];
-  static_assert(2 * 64 * OS * 4 <= 4 * STAGE, "merge buffers must fit");
 
   // Start-up: one descriptor load (key cube, begin and end of its list; the key cubes of a (b, h)
   // come longest list first), then the list chunk, the key mask and the resident K, V rows all in
@@ -563,12 +562,13 @@ __global__ __launch_bounds__(256, 1) void k_fine_bwd_dkv(int Nc, int K, float sl
   }
   __syncthreads();
 
-  // merge the two query halves; dK first, then dV through the same buffers
+  // merge the two query halves: all four partial results (dK, dV x two query halves) go through LDS at once
   const float inv_cnt = 1.0f / (float)__popcll(kmask);
-  float* part0 = (float*)smem;
-  float* part1 = (float*)smem + 64 * OS;
+  static_assert(4 * 64 * OS * 4 <= 4 * STAGE, "merge buffers must fit");
+  float* parts = (float*)smem;  // [dK half 0][dK half 1][dV half 0][dV half 1], each [64][OS]
+#pragma unroll
   for (int pass = 0; pass < 2; ++pass) {
-    float* Op = (qh == 0 ? part0 : part1) + kh * 32 * OS;
+    float* Op = parts + (pass * 2 + qh) * 64 * OS + kh * 32 * OS;
 #pragma unroll
     for (int x = 0; x < DVB; ++x)
 #pragma unroll
@@ -577,12 +577,17 @@ __global__ __launch_bounds__(256, 1) void k_fine_bwd_dkv(int Nc, int K, float sl
         float4 val = make_float4(a[4 * g4], a[4 * g4 + 1], a[4 * g4 + 2], a[4 * g4 + 3]);
         *(float4*)&Op[l32 * OS + x * 32 + 8 * g4 + 4 * h] = val;
       }
-    __syncthreads();
+  }
+  __syncthreads();
+#pragma unroll
+  for (int pass = 0; pass < 2; ++pass) {
     const float4 p0 = pass == 0 ? pk[0] : pv[0], p1 = pass == 0 ? pk[1] : pv[1];
     const float pooled[8] = {p0.x * inv_cnt, p0.y * inv_cnt, p0.z * inv_cnt, p0.w * inv_cnt,
                              p1.x * inv_cnt, p1.y * inv_cnt, p1.z * inv_cnt, p1.w * inv_cnt};
     const float mul = pass == 0 ? scale : 1.0f;
     uint4* dst = pass == 0 ? dk : dv;
+    const float* part0 = parts + pass * 2 * 64 * OS;
+    const float* part1 = part0 + 64 * OS;
 #pragma unroll
     for (int it = 0; it < LPT; ++it) {
       const int item = it * 256 + tid, r = item / CPR, ch = item % CPR;
@@ -597,7 +602,6 @@ __global__ __launch_bounds__(256, 1) void k_fine_bwd_dkv(int Nc, int K, float sl
       }
       dst[(rows0 + j * kTile + r) * CPR + ch] = ov;
     }
-    __syncthreads();
   }
 }
 
