@@ -130,6 +130,28 @@ def test_wan13b_forward_backward(vsa):
     check_head(vsa, wl, dev, buf, 0, 5, backward=True)
 
 
+def test_wan13b_is_bit_reproducible_in_the_benchmark_configuration(vsa):
+    """Two forward+backward steps as bench.py runs them (backward on the workspace the forward left)
+    must give the same bits: no result depends on the order in which workgroups happen to run."""
+    import torch
+    wl = WORKLOADS["wan1.3b"]
+    dev = synth.device_iid_inputs(wl, seed=4, tiled_rows=wl.Np)
+    buf = vsa.Buffers(problem_of(wl))
+    a = (dev["q"], dev["k"], dev["v"], dev["gate_c"], dev["gate_f"])
+    names = ("out", "out_fine", "block_idx", "dq", "dk", "dv", "dgate_c", "dgate_f")
+    runs = []
+    for _ in range(2):
+        for n in names:
+            getattr(buf, n).zero_()
+        buf.forward(*a)
+        buf.backward(*a, dev["dout"], workspace_kept=True)
+        torch.cuda.synchronize()
+        runs.append([getattr(buf, n).clone() for n in names])
+    for n, x, y in zip(names, *runs):
+        assert torch.equal(x.view(torch.int16) if x.dtype == torch.bfloat16 else x,
+                           y.view(torch.int16) if y.dtype == torch.bfloat16 else y), n
+
+
 def test_wan14b_forward_sampled_cubes(vsa):
     wl = WORKLOADS["wan14b"]
     dev = synth.device_iid_inputs(wl, seed=3, tiled_rows=wl.Np)
