@@ -93,7 +93,9 @@ int vsa_tile_permute(const vsa_params_t* p, const void* src, void* dst, int inve
  *   block_idx    out  int32 [B,H,Nc,topk]: selected key cubes of each query cube, ascending
  *                     (the topk largest coarse logits, ties to the lower cube index);
  *                in   when flags has VSA_FLAG_INDICES_GIVEN (must be ascending, distinct,
- *                     each in [0,Nc); not validated on the device)
+ *                     each in [0,Nc); not validated: for a list that breaks this the results
+ *                     are unspecified, but entries outside [0,Nc) are clamped or skipped, so
+ *                     no access leaves the buffers)
  *   out_fine     out  bf16 [B,H,Np,d]  O_f           } saved for vsa_backward;
  *   lse_fine     out  fp32 [B,H,Np]    log-sum-exp of the scaled fine logits (0 on pads)
  *   out_coarse   out  fp32 [B,H,Nc,d]  O_c per cube  } any of these four may be NULL

@@ -302,7 +302,10 @@ __global__ __launch_bounds__(256) void k_map_bits(int Nc, int K, int W32, const 
   __syncthreads();
   const int q_lo = w * 32, nq = min(32, Nc - q_lo);
   const int32_t* my = idx + (bh * Nc + q_lo) * (long long)K;
-  for (int e = tid; e < nq * K; e += 256) atomicOr(&word[my[e]], 1u << (e / K));
+  for (int e = tid; e < nq * K; e += 256) {
+    const unsigned c = (unsigned)my[e];
+    if (c < (unsigned)Nc) atomicOr(&word[c], 1u << (e / K));  // (a caller-supplied list is not trusted)
+  }
   __syncthreads();
   for (int j = tid; j < Nc; j += 256) bits[(bh * Nc + j) * W32 + w] = word[j];
 }

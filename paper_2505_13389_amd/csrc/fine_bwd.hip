@@ -56,7 +56,7 @@ __global__ __launch_bounds__(256, 2) void k_fine_bwd_dq(int Nc, int K, float sl2
   unsigned goff[TL::IPW];
   TL::lane_offsets(wave, lane, goff);
   CubeList cubes;
-  cubes.init(my_idx, mask, K, kh, lane);
+  cubes.init(my_idx, mask, K, kh, lane, Nc);
   {
     const int jt = cubes.cube(ent(0));
     TL::async_load(k, rows0 + (long long)jt * kTile, stage0, wave, goff);

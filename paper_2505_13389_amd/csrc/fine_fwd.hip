@@ -81,7 +81,7 @@ __global__ __launch_bounds__(256, 2) void k_fine_fwd(int Nc, int K, float sl2, c
   // wait for them right there (it also drains the copy), and its own vmcnt bookkeeping has nothing
   // left to wait for inside the loop.
   CubeList cubes;
-  cubes.init(my_idx, mask, K, kh, lane);
+  cubes.init(my_idx, mask, K, kh, lane, Nc);
   issue(stage0, cubes.cube(ent(0)));
   cubes.load_masks();
   bf16x8 qreg[KS];

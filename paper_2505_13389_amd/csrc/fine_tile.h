@@ -71,12 +71,15 @@ __device__ __forceinline__ void wait_lgkmcnt0() { __builtin_amdgcn_s_waitcnt(0xC
 struct CubeList {
   const int32_t* list;
   const uint64_t* mask;
-  int n, half, lane, chunk, idx_v;
+  int n, half, lane, chunk, idx_v, ncubes;
   uint32_t km_v;
   __device__ __forceinline__ void load_indices(int c) {
     chunk = c;
     idx_v = list[min((c << 6) + lane, n - 1)];
     asm volatile("" : "+v"(idx_v));  // consumed at once: the compiler's wait for the load is placed right here
+    // a caller-supplied list is not trusted: an entry outside [0, ncubes) must not turn into an
+    // out-of-bounds fetch (the result for such a list is unspecified, the access pattern is not)
+    idx_v = min(max(idx_v, 0), ncubes - 1);
   }
   __device__ __forceinline__ void load_masks() {
     const uint64_t m = mask[idx_v];
@@ -90,8 +93,9 @@ struct CubeList {
   // After init() the cube indices of the first chunk are there (cube() works); the key masks are
   // still in flight until the caller's next wait for its own loads, so that the first copies can
   // be issued one memory round trip earlier.
-  __device__ __forceinline__ void init(const int32_t* list_, const uint64_t* mask_, int n_, int half_, int lane_) {
-    list = list_, mask = mask_, n = n_, half = half_, lane = lane_;
+  __device__ __forceinline__ void init(const int32_t* list_, const uint64_t* mask_, int n_, int half_, int lane_,
+                                       int ncubes_) {
+    list = list_, mask = mask_, n = n_, half = half_, lane = lane_, ncubes = ncubes_;
     load_indices(0);
   }
   __device__ __forceinline__ int cube(int e) const { return __builtin_amdgcn_readlane(idx_v, e & 63); }

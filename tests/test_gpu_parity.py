@@ -312,3 +312,32 @@ def test_forward_backward_replay_from_hip_graph(vsa):
         torch.cuda.synchronize()
         for got, want in zip(outs(), ref):
             assert torch.equal(got.view(torch.uint8), want.view(torch.uint8)), f"replay {rep} differs from the eager run"
+
+
+def test_invalid_index_lists_stay_inside_the_buffers(vsa):
+    """Caller-supplied lists are not validated; entries outside [0, Nc), duplicates and disorder give
+    unspecified values but every access must stay in bounds: the calls complete, the results are
+    finite, pad rows stay zero, and a correct call right afterwards is still correct."""
+    import torch
+    wl = SMALL["pad128"]
+    bits = tiled_bits(wl, seed=21, pad_garbage=True)
+    dev = to_dev(bits)
+    buf = vsa.Buffers(problem_of(wl), backward=True)
+    rng = np.random.Generator(np.random.PCG64(5))
+    bad = rng.integers(-7, buf.Nc + 7, size=tuple(buf.block_idx.shape), dtype=np.int64).astype(np.int32)
+    bad[0, 0, 0, :] = np.iinfo(np.int32).max
+    bad[0, 0, 1, :] = np.iinfo(np.int32).min
+    buf.block_idx.copy_(torch.from_numpy(bad))
+    a = (dev["q"], dev["k"], dev["v"], dev["gate_c"], dev["gate_f"])
+    buf.forward(*a, indices_given=True)
+    buf.backward(*a, dev["dout"])
+    torch.cuda.synchronize()
+    valid, _ = orc.valid_mask(grid_of(wl))
+    for name_ in ("out", "dq", "dk", "dv"):
+        t = bf16_to_np(getattr(buf, name_))
+        assert np.isfinite(t).all(), name_
+        assert not t[:, :, ~valid].any(), f"{name_}: pad rows must be zero"
+    # the library is unharmed: the regular path still matches the oracle
+    ref = run_oracle_fwd(wl, widen(bits))
+    good = run_gpu_fwd(vsa, wl, dev, block_idx=ref["block_idx"])
+    assert_close(bf16_to_np(good.out), ref["out"], "out")
