@@ -225,7 +225,7 @@ __global__ __launch_bounds__(256, 2) void k_fine_bwd_dq(int Nc, int K, float sl2
 #pragma unroll
       for (int g4 = 0; g4 < 4; ++g4) {
         float4 val = make_float4(acc[x][4 * g4], acc[x][4 * g4 + 1], acc[x][4 * g4 + 2], acc[x][4 * g4 + 3]);
-        *(float4*)&Op[l32 * OS + x * 32 + 8 * g4 + 4 * h] = val;
+        *(float4*)&Op[merge_offset(l32, x * 32 + 8 * g4 + 4 * h, OS)] = val;
       }
   }
   __syncthreads();
@@ -236,13 +236,15 @@ __global__ __launch_bounds__(256, 2) void k_fine_bwd_dq(int Nc, int K, float sl2
 #pragma unroll
   for (int it = 0; it < LPT; ++it) {
     const int item = it * 256 + tid, r = item / CPR, ch = item % CPR;
-    const float* Oa = (const float*)stage0 + r * OS + ch * 8;
-    const float* Ob = (const float*)stage1 + r * OS + ch * 8;
+    const int m0 = merge_offset(r, ch * 8, OS), m1 = merge_offset(r, ch * 8 + 4, OS);
+    const float4 a0 = *(const float4*)((const float*)stage0 + m0), a1 = *(const float4*)((const float*)stage0 + m1);
+    const float4 b0 = *(const float4*)((const float*)stage1 + m0), b1 = *(const float4*)((const float*)stage1 + m1);
+    const float sum[8] = {a0.x + b0.x, a0.y + b0.y, a0.z + b0.z, a0.w + b0.w, a1.x + b1.x, a1.y + b1.y, a1.z + b1.z, a1.w + b1.w};
     uint4 ov = make_uint4(0, 0, 0, 0);
     if ((qmask >> r) & 1) {
       float res[8];
 #pragma unroll
-      for (int e = 0; e < 8; ++e) res[e] = fmaf(Oa[e] + Ob[e], scale, pooled[e]);
+      for (int e = 0; e < 8; ++e) res[e] = fmaf(sum[e], scale, pooled[e]);
       ov = pack8(res);
     }
     dq[(rows0 + c * kTile + r) * CPR + ch] = ov;
@@ -575,7 +577,7 @@ __global__ __launch_bounds__(256, 1) void k_fine_bwd_dkv(int Nc, int K, float sl
       for (int g4 = 0; g4 < 4; ++g4) {
         const f32x16& a = pass == 0 ? dka[x] : dva[x];
         float4 val = make_float4(a[4 * g4], a[4 * g4 + 1], a[4 * g4 + 2], a[4 * g4 + 3]);
-        *(float4*)&Op[l32 * OS + x * 32 + 8 * g4 + 4 * h] = val;
+        *(float4*)&Op[merge_offset(l32, x * 32 + 8 * g4 + 4 * h, OS)] = val;
       }
   }
   __syncthreads();
@@ -591,13 +593,15 @@ __global__ __launch_bounds__(256, 1) void k_fine_bwd_dkv(int Nc, int K, float sl
 #pragma unroll
     for (int it = 0; it < LPT; ++it) {
       const int item = it * 256 + tid, r = item / CPR, ch = item % CPR;
-      const float* Oa = part0 + r * OS + ch * 8;
-      const float* Ob = part1 + r * OS + ch * 8;
+      const int m0 = merge_offset(r, ch * 8, OS), m1 = merge_offset(r, ch * 8 + 4, OS);
+      const float4 a0 = *(const float4*)(part0 + m0), a1 = *(const float4*)(part0 + m1);
+      const float4 b0 = *(const float4*)(part1 + m0), b1 = *(const float4*)(part1 + m1);
+      const float sum[8] = {a0.x + b0.x, a0.y + b0.y, a0.z + b0.z, a0.w + b0.w, a1.x + b1.x, a1.y + b1.y, a1.z + b1.z, a1.w + b1.w};
       uint4 ov = make_uint4(0, 0, 0, 0);
       if ((kmask >> r) & 1) {
         float res[8];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) res[e] = fmaf(Oa[e] + Ob[e], mul, pooled[e]);
+        for (int e = 0; e < 8; ++e) res[e] = fmaf(sum[e], mul, pooled[e]);
         ov = pack8(res);
       }
       dst[(rows0 + j * kTile + r) * CPR + ch] = ov;

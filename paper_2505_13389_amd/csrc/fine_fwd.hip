@@ -262,7 +262,7 @@ __global__ __launch_bounds__(256, 2) void k_fine_fwd(int Nc, int K, float sl2, c
 #pragma unroll
       for (int g4 = 0; g4 < 4; ++g4) {
         float4 val = make_float4(o[x][4 * g4], o[x][4 * g4 + 1], o[x][4 * g4 + 2], o[x][4 * g4 + 3]);
-        *(float4*)&Op[l32 * OS + x * 32 + 8 * g4 + 4 * h] = val;
+        *(float4*)&Op[merge_offset(l32, x * 32 + 8 * g4 + 4 * h, OS)] = val;
       }
   }
   if (h == 0) {
@@ -281,11 +281,12 @@ __global__ __launch_bounds__(256, 2) void k_fine_fwd(int Nc, int K, float sl2, c
     float fa = fast_exp2(ma - M), fb = fast_exp2(mb - M);
     const float inv = 1.0f / (la * fa + lb * fb);
     fa *= inv; fb *= inv;
-    const float* Oa = (const float*)stage0 + r * OS + ch * 8;
-    const float* Ob = (const float*)stage1 + r * OS + ch * 8;
+    const int m0 = merge_offset(r, ch * 8, OS), m1 = merge_offset(r, ch * 8 + 4, OS);
+    const float* Oa = (const float*)stage0;
+    const float* Ob = (const float*)stage1;
     float of[8], res[8];
-    const float4 a0 = *(const float4*)Oa, a1 = *(const float4*)(Oa + 4);
-    const float4 b0 = *(const float4*)Ob, b1 = *(const float4*)(Ob + 4);
+    const float4 a0 = *(const float4*)(Oa + m0), a1 = *(const float4*)(Oa + m1);
+    const float4 b0 = *(const float4*)(Ob + m0), b1 = *(const float4*)(Ob + m1);
     of[0] = a0.x * fa + b0.x * fb; of[1] = a0.y * fa + b0.y * fb; of[2] = a0.z * fa + b0.z * fb; of[3] = a0.w * fa + b0.w * fb;
     of[4] = a1.x * fa + b1.x * fb; of[5] = a1.y * fa + b1.y * fb; of[6] = a1.z * fa + b1.z * fb; of[7] = a1.w * fa + b1.w * fb;
     const long long g = (rows0 + c * kTile + r) * CPR + ch;

@@ -227,6 +227,14 @@ struct Tile {
   }
 };
 
+// fp32 merge buffers [64][D] in LDS (partial results of the wavefronts that share output rows).
+// A row is D*4 bytes, a multiple of the 256 bytes the 64 banks span, so the 32 lanes of an
+// accumulator column (one row each) would all hit the same banks; the 16-byte chunks of a row are
+// therefore XOR-ed with the row number (mod 16).  `col` is a multiple of 4.
+__device__ __forceinline__ int merge_offset(int row, int col, int row_stride) {
+  return row * row_stride + ((((col >> 2) ^ (row & 15)) << 2));
+}
+
 // fp32 accumulator values [8s .. 8s+7] -> bf16 operand of k-step s (see transposed_operand).
 __device__ __forceinline__ bf16x8 acc_to_operand(const float* p) {
   uint4 u = pack8(p);
