@@ -86,12 +86,15 @@ def iid_inputs(wl: Workload, seed: int = 0, with_gate_f: bool = True):
 
 
 def planted_inputs(wl: Workload, seed: int = 0, sigma: float = 0.5, gain: float = 3.0, sinks: int = 0,
-                   with_gate_f: bool = True):
+                   with_gate_f: bool = True, sink_gain: float = 1.0):
     """Structured Q/K so that each query cube prefers its 3x3x3 neighbourhood of key cubes.
 
     Every cube gets a signature s_c ~ N(0,I).  Keys of cube c are s_c + sigma*eps; queries of
     cube c are gain * mean(s_c' over cubes within Chebyshev distance 1) + sigma*eps.  `sinks`
-    cubes have their signature added to every query (many query cubes then select them).
+    cubes have `sink_gain` times their signature added to every query: every query cube then
+    selects them, and (through the chance alignment of the other signatures with the sinks') the
+    in-degrees of the remaining key cubes spread widely; the smaller sink_gain, the more the
+    neighbourhood term shapes the rest of a list.
     """
     rng = _rng(1000 + seed)
     Ct, Ch, Cw = wl.cube
@@ -114,7 +117,7 @@ def planted_inputs(wl: Workload, seed: int = 0, sigma: float = 0.5, gain: float 
     if sinks:
         flat = sig.reshape(wl.B, wl.H, -1, wl.d)
         pick = rng.choice(flat.shape[2], size=sinks, replace=False)
-        qsig = qsig + flat[:, :, pick].sum(axis=2)[:, :, None, None, None, :]
+        qsig = qsig + sink_gain * flat[:, :, pick].sum(axis=2)[:, :, None, None, None, :]
     # cube coordinates of every raster token
     t, h, w = np.meshgrid(np.arange(wl.T), np.arange(wl.Hh), np.arange(wl.W), indexing="ij")
     ct, ch, cw = (t // Ct).ravel(), (h // Ch).ravel(), (w // Cw).ravel()

@@ -88,6 +88,11 @@ class Problem:
                          self.topk, self.softmax_scale, self.flags if flags is None else flags)
 
 
+def problem_of(wl, topk=None) -> Problem:
+    """The call shape of a named workload (synth.Workload); `topk` overrides the workload's own."""
+    return Problem(wl.B, wl.H, wl.T, wl.Hh, wl.W, wl.d, wl.topk if topk is None else topk, tuple(wl.cube))
+
+
 def _p(t):
     return None if t is None else C.c_void_p(t.data_ptr())
 

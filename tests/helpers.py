@@ -18,11 +18,16 @@ def grid_of(wl):
     return Grid(wl.T, wl.Hh, wl.W, *wl.cube)
 
 
-def tiled_bits(wl, seed=0, with_gate_f=True, planted=None, pad_garbage=False):
-    """Seeded inputs of a workload as TILED bf16 bit patterns (numpy uint16 [B,H,Np,d])."""
+def tiled_bits(wl, seed=0, with_gate_f=True, planted=None, pad_garbage=False, sinks=0, sink_gain=1.0):
+    """Seeded inputs of a workload as TILED bf16 bit patterns (numpy uint16 [B,H,Np,d]).
+    `sinks` > 0 (planted inputs only): that many key cubes attract every query cube."""
     if planted is None:
         planted = wl.planted
-    raw = (synth.planted_inputs if planted else synth.iid_inputs)(wl, seed, with_gate_f=with_gate_f)
+    if planted:
+        raw = synth.planted_inputs(wl, seed, with_gate_f=with_gate_f, sinks=sinks, sink_gain=sink_gain)
+    else:
+        assert sinks == 0
+        raw = synth.iid_inputs(wl, seed, with_gate_f=with_gate_f)
     g = grid_of(wl)
     out = {}
     for n in NAMES:
@@ -55,7 +60,7 @@ def bf16_to_np(t):
 
 def problem_of(wl, topk=None):
     from paper_2505_13389_amd import vsa
-    return vsa.Problem(wl.B, wl.H, wl.T, wl.Hh, wl.W, wl.d, wl.topk if topk is None else topk, wl.cube)
+    return vsa.problem_of(wl, topk)
 
 
 def assert_close(got, ref, name, max_abs=MAX_ABS, rel_l2=REL_L2):
