@@ -44,7 +44,8 @@ typedef enum {
   VSA_ERR_UNSUPPORTED = -3, /* cube volume != 64, d not in {64,128}, Nc above the limit */
   VSA_ERR_ALIGN = -4,       /* a device pointer is not 16-byte aligned                 */
   VSA_ERR_WORKSPACE = -5,   /* workspace NULL or smaller than vsa_workspace_bytes      */
-  VSA_ERR_HIP = -6          /* a kernel launch was rejected by the runtime             */
+  VSA_ERR_HIP = -6,         /* a kernel launch was rejected by the runtime             */
+  VSA_ERR_SCRATCH_LIMIT = -7 /* vsa_forward_static: the problem needs more scratch than the static buffer */
 } vsa_status;
 
 #define VSA_FLAG_INDICES_GIVEN 1u /* vsa_forward: block_idx is an INPUT, top-K is skipped */
@@ -54,6 +55,7 @@ typedef enum {
                                       written to it since: the pooled tensors it still holds are used
                                       instead of being computed again.  Size it for the backward. */
 #define VSA_MAX_CUBES 4096        /* largest supported Nc                                 */
+#define VSA_STATIC_SCRATCH_MIB 40 /* size of the scratch buffer behind vsa_forward_static, MiB */
 
 typedef struct {
   int32_t B, H;        /* batch, heads                                                   */
@@ -105,6 +107,25 @@ int vsa_tile_permute(const vsa_params_t* p, const void* src, void* dst, int inve
 int vsa_forward(const vsa_params_t* p, const void* q, const void* k, const void* v, const void* gate_c,
                 const void* gate_f, void* out, int32_t* block_idx, void* out_fine, float* lse_fine,
                 float* out_coarse, float* lse_coarse, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* vsa_forward for callers that cannot allocate and have no workspace to hand over: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results and
+ * errors as vsa_forward, minus the workspace: the scratch is a buffer of VSA_STATIC_SCRATCH_MIB MiB
+ * that is part of the library itself (one per GPU, held from the library's load until the process
+ * ends; vsa_static_scratch_bytes() returns its size).  The call allocates and frees nothing.
+ *   - A problem with vsa_workspace_bytes(p, 0) above that size is refused with
+ *     VSA_ERR_SCRATCH_LIMIT before anything is enqueued (40 MiB covers the 39936-token, 12-head,
+ *     top-78 forward; larger problems go through vsa_forward).
+ *   - The first call on a GPU looks the buffer's address up (no allocation); make that call
+ *     outside graph capture.
+ *   - All calls on one GPU share the buffer.  Every byte a call reads from it was written by
+ *     the same call before, so nothing has to be cleared between calls, but two calls that
+ *     overlap in time on one GPU (different streams, or graphs replayed side by side) race.
+ *   - VSA_FLAG_WORKSPACE_KEPT cannot refer to this buffer: the backward takes a workspace. */
+int vsa_forward_static(const vsa_params_t* p, const void* q, const void* k, const void* v, const void* gate_c,
+                       const void* gate_f, void* out, int32_t* block_idx, void* out_fine, float* lse_fine,
+                       float* out_coarse, float* lse_coarse, void* hip_stream);
+size_t vsa_static_scratch_bytes(void);
 
 /* Backward of vsa_forward with the selection held constant (Sec. 2.4 states that a
  * backward kernel exists; the gradients are the chain rule through Sec. 2.2's steps:

@@ -2,7 +2,13 @@
 // See include/vsa.h for the contract of every entry point.
 #include "../../include/vsa.h"
 
+#include <atomic>
+
 #include "vsa_kernels.h"
+
+// Scratch of vsa_forward_static (see there): part of the library's code object, one copy per GPU.
+constexpr size_t kStaticScratchBytes = (size_t)VSA_STATIC_SCRATCH_MIB << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
 namespace {
 
@@ -139,6 +145,60 @@ struct Timed {
     if ((expr) != hipSuccess) return VSA_ERR_HIP; \
   } while (0)
 
+int check_forward_args(const vsa_params_t* p, Geo* g, const void* q, const void* k, const void* v, const void* gate_c,
+                       const void* gate_f, const void* out, const int32_t* block_idx, const void* out_fine,
+                       const float* lse_fine, const float* out_coarse, const float* lse_coarse) {
+  int rc = check_params(p, g);
+  if (rc != VSA_OK) return rc;
+  if ((rc = check_topk(p, *g)) != VSA_OK) return rc;
+  const bool given = (p->flags & VSA_FLAG_INDICES_GIVEN) != 0;
+  if (!q || !k || !v || !gate_c || !out || (given && !block_idx)) return VSA_ERR_NULL;
+  if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(gate_c) || misaligned(gate_f) || misaligned(out) ||
+      misaligned(block_idx) || misaligned(out_fine) || misaligned(lse_fine) || misaligned(out_coarse) ||
+      misaligned(lse_coarse))
+    return VSA_ERR_ALIGN;
+  return VSA_OK;
+}
+
+// The forward's kernel sequence on validated arguments; `workspace` holds at least carve_fwd().bytes.
+int enqueue_forward(const vsa_params_t* p, const Geo& g, const void* q, const void* k, const void* v,
+                    const void* gate_c, const void* gate_f, void* out, int32_t* block_idx, void* out_fine,
+                    float* lse_fine, float* out_coarse, float* lse_coarse, void* workspace, hipStream_t s) {
+  const bool given = (p->flags & VSA_FLAG_INDICES_GIVEN) != 0;
+  FwdWs w = carve_fwd(p, g, workspace);
+  const int BH = p->B * p->H;
+  const float scale = scale_of(p);
+  float* oc = out_coarse ? out_coarse : w.oc;
+  float* lse_c = lse_coarse ? lse_coarse : w.lse_c;
+  int32_t* idx = block_idx ? block_idx : w.idx;
+
+  VSA_TRY("cube_masks", vsa::launch_cube_masks(g, w.mask, s));
+  VSA_TRY("pool", vsa::launch_pool(g, BH, p->d, w.mask, q, k, v, w.qc, w.kc, w.vc, s));
+  VSA_TRY("coarse", vsa::launch_coarse(BH, g.Nc, p->d, p->topk, scale, w.qc, w.kc, w.vc, w.sc, oc, lse_c, idx, given ? 0 : 1, s));
+  VSA_TRY("fine_fwd", vsa::launch_fine_fwd(BH, g.Nc, p->d, p->topk, scale, q, k, v, gate_c, gate_f, idx, oc, w.mask, out, out_fine,
+                               lse_fine, s));
+  return VSA_OK;
+}
+
+// Scratch of vsa_forward_static: device memory that belongs to the library's code object, one copy
+// per GPU at that GPU's own address, held until the process ends.  In host code the array's name is
+// only a handle for hipGetSymbolAddress -- never a device address -- so every use goes through the
+// pointer looked up once per device (with that device current) and kept here.
+constexpr int kMaxDevices = 64;
+std::atomic<void*> g_scratch_ptr[kMaxDevices];
+
+void* static_scratch_of_current_device() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+  void* ptr = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (!ptr) {
+    // two threads may both look it up: they get the same address
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return nullptr;
+    g_scratch_ptr[dev].store(ptr, std::memory_order_release);
+  }
+  return ptr;
+}
+
 }  // namespace
 
 extern "C" {
@@ -173,31 +233,27 @@ int vsa_forward(const vsa_params_t* p, const void* q, const void* k, const void*
                 const void* gate_f, void* out, int32_t* block_idx, void* out_fine, float* lse_fine,
                 float* out_coarse, float* lse_coarse, void* workspace, size_t workspace_bytes, void* hip_stream) {
   Geo g;
-  int rc = check_params(p, &g);
+  int rc = check_forward_args(p, &g, q, k, v, gate_c, gate_f, out, block_idx, out_fine, lse_fine, out_coarse, lse_coarse);
   if (rc != VSA_OK) return rc;
-  if ((rc = check_topk(p, g)) != VSA_OK) return rc;
-  const bool given = (p->flags & VSA_FLAG_INDICES_GIVEN) != 0;
-  if (!q || !k || !v || !gate_c || !out || (given && !block_idx)) return VSA_ERR_NULL;
-  if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(gate_c) || misaligned(gate_f) || misaligned(out) ||
-      misaligned(block_idx) || misaligned(out_fine) || misaligned(lse_fine) || misaligned(out_coarse) ||
-      misaligned(lse_coarse) || misaligned(workspace))
-    return VSA_ERR_ALIGN;
+  if (misaligned(workspace)) return VSA_ERR_ALIGN;
   if (!workspace || workspace_bytes < carve_fwd(p, g, nullptr).bytes) return VSA_ERR_WORKSPACE;
+  return enqueue_forward(p, g, q, k, v, gate_c, gate_f, out, block_idx, out_fine, lse_fine, out_coarse, lse_coarse,
+                         workspace, (hipStream_t)hip_stream);
+}
 
-  hipStream_t s = (hipStream_t)hip_stream;
-  FwdWs w = carve_fwd(p, g, workspace);
-  const int BH = p->B * p->H;
-  const float scale = scale_of(p);
-  float* oc = out_coarse ? out_coarse : w.oc;
-  float* lse_c = lse_coarse ? lse_coarse : w.lse_c;
-  int32_t* idx = block_idx ? block_idx : w.idx;
+size_t vsa_static_scratch_bytes(void) { return kStaticScratchBytes; }
 
-  VSA_TRY("cube_masks", vsa::launch_cube_masks(g, w.mask, s));
-  VSA_TRY("pool", vsa::launch_pool(g, BH, p->d, w.mask, q, k, v, w.qc, w.kc, w.vc, s));
-  VSA_TRY("coarse", vsa::launch_coarse(BH, g.Nc, p->d, p->topk, scale, w.qc, w.kc, w.vc, w.sc, oc, lse_c, idx, given ? 0 : 1, s));
-  VSA_TRY("fine_fwd", vsa::launch_fine_fwd(BH, g.Nc, p->d, p->topk, scale, q, k, v, gate_c, gate_f, idx, oc, w.mask, out, out_fine,
-                               lse_fine, s));
-  return VSA_OK;
+int vsa_forward_static(const vsa_params_t* p, const void* q, const void* k, const void* v, const void* gate_c,
+                       const void* gate_f, void* out, int32_t* block_idx, void* out_fine, float* lse_fine,
+                       float* out_coarse, float* lse_coarse, void* hip_stream) {
+  Geo g;
+  int rc = check_forward_args(p, &g, q, k, v, gate_c, gate_f, out, block_idx, out_fine, lse_fine, out_coarse, lse_coarse);
+  if (rc != VSA_OK) return rc;
+  if (carve_fwd(p, g, nullptr).bytes > kStaticScratchBytes) return VSA_ERR_SCRATCH_LIMIT;
+  void* ws = static_scratch_of_current_device();
+  if (!ws) return VSA_ERR_HIP;
+  return enqueue_forward(p, g, q, k, v, gate_c, gate_f, out, block_idx, out_fine, lse_fine, out_coarse, lse_coarse, ws,
+                         (hipStream_t)hip_stream);
 }
 
 int vsa_backward(const vsa_params_t* p, const void* q, const void* k, const void* v, const void* gate_c,
@@ -296,6 +352,7 @@ const char* vsa_status_string(int status) {
     case VSA_ERR_ALIGN: return "a device pointer is not 16-byte aligned";
     case VSA_ERR_WORKSPACE: return "workspace missing or too small";
     case VSA_ERR_HIP: return "a kernel launch failed";
+    case VSA_ERR_SCRATCH_LIMIT: return "the problem needs more scratch than the static buffer of vsa_forward_static holds";
     default: return "unknown status";
   }
 }

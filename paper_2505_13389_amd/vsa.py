@@ -17,10 +17,10 @@ VSA_FLAG_INDICES_GIVEN = 1
 VSA_FLAG_RASTER_BLHD = 2
 VSA_FLAG_WORKSPACE_KEPT = 4
 STATUS = {0: "VSA_OK", -1: "VSA_ERR_NULL", -2: "VSA_ERR_BAD_ARG", -3: "VSA_ERR_UNSUPPORTED", -4: "VSA_ERR_ALIGN",
-          -5: "VSA_ERR_WORKSPACE", -6: "VSA_ERR_HIP"}
+          -5: "VSA_ERR_WORKSPACE", -6: "VSA_ERR_HIP", -7: "VSA_ERR_SCRATCH_LIMIT"}
 EXPORTS = ["vsa_padded_tokens", "vsa_workspace_bytes", "vsa_tile_permute", "vsa_forward", "vsa_backward",
            "vsa_status_string", "vsa_profile_begin", "vsa_profile_count", "vsa_profile_name", "vsa_profile_ms",
-           "vsa_profile_end", "vsa_bench_mfma_rate"]
+           "vsa_profile_end", "vsa_bench_mfma_rate", "vsa_forward_static", "vsa_static_scratch_bytes"]
 
 
 class VsaParams(C.Structure):
@@ -55,6 +55,10 @@ def lib():
         L.vsa_tile_permute.restype = C.c_int
         L.vsa_forward.argtypes = [C.POINTER(VsaParams)] + [vp] * 12 + [C.c_size_t, vp]
         L.vsa_forward.restype = C.c_int
+        L.vsa_forward_static.argtypes = [C.POINTER(VsaParams)] + [vp] * 12
+        L.vsa_forward_static.restype = C.c_int
+        L.vsa_static_scratch_bytes.argtypes = []
+        L.vsa_static_scratch_bytes.restype = C.c_size_t
         L.vsa_backward.argtypes = [C.POINTER(VsaParams)] + [vp] * 17 + [C.c_size_t, vp]
         L.vsa_backward.restype = C.c_int
         L.vsa_bench_mfma_rate.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.POINTER(C.c_double), C.c_void_p]
@@ -128,6 +132,17 @@ def vsa_forward(pb: Problem, q, k, v, gate_c, gate_f, out, block_idx, out_fine, 
                            0 if workspace is None else workspace.numel() * workspace.element_size(), _stream())
     if rc:
         raise VsaError("vsa_forward", rc)
+
+
+def vsa_forward_static(pb: Problem, q, k, v, gate_c, gate_f, out, block_idx, out_fine, lse_fine, out_coarse,
+                       lse_coarse, indices_given: bool = False):
+    """vsa_forward on the library's own static scratch buffer (no workspace, no allocation)."""
+    flags = pb.flags | (VSA_FLAG_INDICES_GIVEN if indices_given else 0)
+    rc = lib().vsa_forward_static(C.byref(pb.params(flags)), _p(q), _p(k), _p(v), _p(gate_c), _p(gate_f), _p(out),
+                                  _p(block_idx), _p(out_fine), _p(lse_fine), _p(out_coarse), _p(lse_coarse),
+                                  _stream())
+    if rc:
+        raise VsaError("vsa_forward_static", rc)
 
 
 def vsa_backward(pb: Problem, q, k, v, gate_c, gate_f, dout, block_idx, out_fine, lse_fine, out_coarse, lse_coarse,

@@ -68,7 +68,7 @@ def test_null_and_topk_validation_happens_before_any_launch(lib):
 
 def test_status_strings(lib):
     seen = set()
-    for s in range(0, -7, -1):
+    for s in range(0, -8, -1):
         msg = lib.vsa_status_string(s)
         assert msg and msg not in seen
         seen.add(msg)
