@@ -142,6 +142,19 @@ int vsa_backward(const vsa_params_t* p, const void* q, const void* k, const void
                  void* dv, void* dgate_c, void* dgate_f, void* workspace, size_t workspace_bytes,
                  void* hip_stream);
 
+/* Host-only diagnostic (no GPU, nothing enqueued): replays on the CPU the index arithmetic the
+ * kernels apply to a block-index list -- the clamp of the forward and dQ passes, the skip rule and
+ * the capacity of the transposed map, the cutting of long transposed lists into runs with numbered
+ * partial-result slots -- through the very functions the kernels use, and counts every replayed
+ * access that would leave its buffer.  For checking on the CPU that caller-supplied lists of any
+ * content (VSA_FLAG_INDICES_GIVEN: entries outside [0,Nc), duplicates, disorder) stay in bounds.
+ *   host_block_idx  HOST int32 [B,H,Nc,topk]
+ *   report          HOST int64[8] or NULL: violations, longest transposed list, most dK/dV work
+ *                   items and partial-result slots and split lists of a (b,h), most transposed
+ *                   entries of a (b,h), split length, slot capacity
+ * Returns VSA_OK when no access leaves its buffer, VSA_ERR_BAD_ARG otherwise (or for bad params). */
+int vsa_host_replay_lists(const vsa_params_t* p, const int32_t* host_block_idx, int64_t* report);
+
 /* Per-kernel timing for benchmarks (not part of the paper's method).  Between
  * vsa_profile_begin and vsa_profile_end every kernel the other entry points enqueue is
  * bracketed by a pair of HIP events on the caller's stream, up to max_records kernels

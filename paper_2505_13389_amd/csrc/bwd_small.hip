@@ -1,6 +1,7 @@
 // Small backward steps: the elementwise preprocess, the coarse-stage backward (fp32) and the
 // transposed block map.  The gradient formulas are the chain rule through Sec. 2.2's gated sum,
 // coarse softmax attention and mean pooling.
+#include "list_rules.h"
 #include "vsa_kernels.h"
 
 namespace vsa {
@@ -303,8 +304,8 @@ __global__ __launch_bounds__(256) void k_map_bits(int Nc, int K, int W32, const 
   const int q_lo = w * 32, nq = min(32, Nc - q_lo);
   const int32_t* my = idx + (bh * Nc + q_lo) * (long long)K;
   for (int e = tid; e < nq * K; e += 256) {
-    const unsigned c = (unsigned)my[e];
-    if (c < (unsigned)Nc) atomicOr(&word[c], 1u << (e / K));  // (a caller-supplied list is not trusted)
+    const int c = my[e];
+    if (map_takes(c, Nc)) atomicOr(&word[c], 1u << (e / K));  // (a caller-supplied list is not trusted)
   }
   __syncthreads();
   for (int j = tid; j < Nc; j += 256) bits[(bh * Nc + j) * W32 + w] = word[j];
@@ -353,15 +354,35 @@ __device__ __forceinline__ int block_scan4(int* v, int* wsum, int tid) {
   return total;
 }
 
-// exclusive scan of the in-degrees of one (b, h), in place; row_ptr[Nc] = total.  Also sorts the
-// key cubes by in-degree, longest list first (counting sort; the order among equal degrees is
-// whatever the LDS atomics give, it only decides which workgroup starts when): `order` holds one
-// 16-byte descriptor (key cube, begin and end of its list in col, 0) per dK/dV workgroup, in the
-// sequence in which that pass takes them, so that the workgroups still running at the end of the
-// launch are the short ones and a workgroup finds its list with a single load.
-__global__ __launch_bounds__(1024) void k_map_scan(int Nc, int32_t* __restrict__ row_ptr, int32_t* __restrict__ order) {
+// sum of one value per thread over a 1024-thread workgroup, returned to every thread
+__device__ __forceinline__ int block_sum(int x, int* wsum, int tid) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o);
+  __syncthreads();  // wsum may still be read by a previous call
+  if ((tid & 63) == 0) wsum[tid >> 6] = x;
+  __syncthreads();
+  int total = 0;
+  for (int w = 0; w < 16; ++w) total += wsum[w];
+  return total;
+}
+
+// exclusive scan of the in-degrees of one (b, h), in place; row_ptr[Nc] = total.  Also cuts the
+// work of the dK/dV pass into items and sorts them by length, longest first (counting sort; the
+// order among equal lengths is whatever the LDS atomics give, it only decides which workgroup
+// starts when).  An item is a key cube's whole list, or -- for a list longer than the split length
+// -- one of ceil(deg / length) nearly equal runs of it; each run of such a SPLIT list accumulates
+// fp32 partial dK, dV into a numbered slot, summed afterwards in slot order by k_dkv_reduce, so the
+// result does not depend on which workgroup ran when.  The split length of a (b, h) is the smallest
+// one, not below `seg_min`, at which the runs of all its long lists fit into the `cap` slots the
+// slot buffer holds per (b, h): it depends on the in-degrees alone.
+//   order: one 16-byte descriptor (key cube, begin, end of the run in col, slot or -1) per dK/dV
+//          workgroup, Nc + cap of them per (b, h); unused ones carry key cube -1
+//   split: per (b, h) cap/2 + 1 descriptors: [0] = (number of split lists, 0, 0, 0), then
+//          (key cube, first slot, number of slots, 0) per split list, in cube order
+__global__ __launch_bounds__(1024) void k_map_scan(int Nc, int seg_min, int cap, int32_t* __restrict__ row_ptr,
+                                                   int32_t* __restrict__ order, int32_t* __restrict__ split) {
   __shared__ int wsum[16];
-  __shared__ int hist[kMaxCubes];  // bucket x: cubes of in-degree Nc - x (the last bucket also takes
+  __shared__ int hist[kMaxCubes];  // bucket x: items of length Nc - x (the last bucket also takes
                                    // what lies beyond it), then the next free slot of the bucket
   const int bh = blockIdx.x, tid = threadIdx.x;
   int32_t* rp = row_ptr + (long long)bh * (Nc + 1);
@@ -378,13 +399,55 @@ __global__ __launch_bounds__(1024) void k_map_scan(int Nc, int32_t* __restrict__
   for (int i = 0; i < 4; ++i)
     if (j0 + i < Nc) rp[j0 + i] = v[i];
   if (tid == 0) rp[Nc] = total;
-  // counting sort by in-degree, descending
-  int bucket[4];
+
+  // the split length: slots_wanted is non-increasing in it and 0 at Nc (no list is longer than Nc)
+  auto wanted = [&](int len) {
+    int w = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) w += slots_wanted(deg[i], len);
+    return block_sum(w, wsum, tid);
+  };
+  int seg = seg_min;
+  if (wanted(seg) > cap) {
+    int lo = seg, hi = max(Nc, seg + 1);  // wanted(lo) > cap >= wanted(hi)
+    while (hi - lo > 1) {
+      const int mid = (lo + hi) >> 1;
+      if (wanted(mid) <= cap) hi = mid; else lo = mid;
+    }
+    seg = hi;
+  }
+  // which lists are split, and into how many runs
+  int nseg[4], slot[4], rank[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    bucket[i] = min(Nc - deg[i], kMaxCubes - 1);
-    if (j0 + i < Nc) atomicAdd(&hist[bucket[i]], 1);
+    nseg[i] = split_runs(deg[i], seg);
+    slot[i] = nseg[i] > 1 ? nseg[i] : 0;
   }
+  block_scan4(slot, wsum, tid);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    if (nseg[i] > 1 && !split_granted(nseg[i], slot[i], cap)) nseg[i] = 1;
+    rank[i] = nseg[i] > 1 ? 1 : 0;
+  }
+  const int nsplit = block_scan4(rank, wsum, tid);
+  int4* sp = (int4*)split + (long long)bh * (cap / 2 + 1);
+  if (tid == 0) sp[0] = make_int4(nsplit, 0, 0, 0);
+  int extra[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    if (nseg[i] > 1) sp[1 + rank[i]] = make_int4(j0 + i, slot[i], nseg[i], 0);
+    extra[i] = nseg[i] - 1;
+  }
+  const int items = Nc + block_scan4(extra, wsum, tid);
+
+  // counting sort of the items by length, descending
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+    if (j0 + i < Nc)
+      for (int r = 0; r < nseg[i]; ++r) {
+        const int len = run_bound(deg[i], nseg[i], r + 1) - run_bound(deg[i], nseg[i], r);
+        atomicAdd(&hist[min(Nc - len, kMaxCubes - 1)], 1);
+      }
   __syncthreads();
   int first[4];
 #pragma unroll
@@ -393,11 +456,16 @@ __global__ __launch_bounds__(1024) void k_map_scan(int Nc, int32_t* __restrict__
 #pragma unroll
   for (int i = 0; i < 4; ++i) hist[j0 + i] = first[i];
   __syncthreads();
-  // one descriptor per dK/dV workgroup: (key cube, begin and end of its list in col, 0)
-  int4* ord = (int4*)order + (long long)bh * Nc;
+  int4* ord = (int4*)order + (long long)bh * (Nc + cap);
 #pragma unroll
   for (int i = 0; i < 4; ++i)
-    if (j0 + i < Nc) ord[atomicAdd(&hist[bucket[i]], 1)] = make_int4(j0 + i, v[i], v[i] + deg[i], 0);
+    if (j0 + i < Nc)
+      for (int r = 0; r < nseg[i]; ++r) {
+        const int lo = run_bound(deg[i], nseg[i], r), hi = run_bound(deg[i], nseg[i], r + 1);
+        ord[atomicAdd(&hist[min(Nc - (hi - lo), kMaxCubes - 1)], 1)] =
+            make_int4(j0 + i, v[i] + lo, v[i] + hi, nseg[i] > 1 ? slot[i] + r : -1);
+      }
+  for (int e = items + tid; e < Nc + cap; e += 1024) ord[e] = make_int4(-1, 0, 0, -1);
 }
 
 // the list of key cube j: positions of the set bits of its row, ascending (one wavefront per row)
@@ -431,7 +499,7 @@ __global__ __launch_bounds__(256) void k_map_fill(int Nc, int W32, long long row
 }
 
 hipError_t launch_transpose_map(int BH, int Nc, int K, const int32_t* idx, uint32_t* bits, int32_t* row_ptr,
-                                int32_t* col, int32_t* order, hipStream_t s) {
+                                int32_t* col, int32_t* order, int32_t* split, int seg, int cap, hipStream_t s) {
   const int W32 = (Nc + 31) / 32;
   const long long rows = (long long)BH * Nc;
   hipError_t e;
@@ -439,7 +507,7 @@ hipError_t launch_transpose_map(int BH, int Nc, int K, const int32_t* idx, uint3
   if ((e = hipGetLastError()) != hipSuccess) return e;
   k_map_degree<<<(unsigned)((rows + 3) / 4), 256, 0, s>>>(Nc, W32, rows, bits, row_ptr);
   if ((e = hipGetLastError()) != hipSuccess) return e;
-  k_map_scan<<<BH, 1024, 0, s>>>(Nc, row_ptr, order);
+  k_map_scan<<<BH, 1024, 0, s>>>(Nc, seg, cap, row_ptr, order, split);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   k_map_fill<<<(unsigned)((rows + 3) / 4), 256, 0, s>>>(Nc, W32, rows, bits, row_ptr, col, (long long)Nc * K);
   return hipGetLastError();

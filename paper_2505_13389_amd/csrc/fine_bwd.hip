@@ -291,7 +291,8 @@ __global__ __launch_bounds__(256, 1) void k_fine_bwd_dkv(int Nc, int K, float sl
                                                          const uint4* __restrict__ k, const uint4* __restrict__ v,
                                                          const uint4* __restrict__ dof,
                                                          const int32_t* __restrict__ col,
-                                                         const int32_t* __restrict__ order,
+                                                         const int32_t* __restrict__ order, int items_per_bh,
+                                                         float* __restrict__ parts, int cap,
                                                          const uint4* __restrict__ ldb,
                                                          const float* __restrict__ dkc, const float* __restrict__ dvc,
                                                          const uint64_t* __restrict__ mask, uint4* __restrict__ dk,
@@ -303,12 +304,15 @@ __global__ __launch_bounds__(256, 1) void k_fine_bwd_dkv(int Nc, int K, float sl
   constexpr int NLP = 2 * TL::IPW + 1;                  // copies per wave and stage
   __shared__ __attribute__((aligned(16))) unsigned char smem[4 * STAGE];
 
-  // Start-up: one descriptor load (key cube, begin and end of its list; the key cubes of a (b, h)
-  // come longest list first), then the list chunk, the key mask and the resident K, V rows all in
-  // flight together, one wait, then the first copies.
-  const long long bh = blockIdx.x / Nc;
+  // Start-up: one descriptor load (key cube, begin and end of its run of the cube's list, slot; the
+  // items of a (b, h) come longest first), then the list chunk, the key mask and the resident K, V
+  // rows all in flight together, one wait, then the first copies.  A list longer than the split
+  // length is shared by several workgroups, each of which leaves its fp32 partial sums in its slot
+  // (desc.w >= 0) for k_dkv_reduce; unused descriptors carry key cube -1.
+  const long long bh = blockIdx.x / items_per_bh;
   const int4 desc = ((const int4*)order)[blockIdx.x];
-  const int j = desc.x, beg = desc.y, end = desc.z, n = end - beg;
+  if (desc.x < 0) return;
+  const int j = desc.x, beg = desc.y, end = desc.z, n = end - beg, slot = desc.w;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int kh = wave & 1, qh = wave >> 1, l32 = lane & 31, h = lane >> 5;
   const long long rows0 = bh * (long long)Nc * kTile;
@@ -317,7 +321,7 @@ __global__ __launch_bounds__(256, 1) void k_fine_bwd_dkv(int Nc, int K, float sl
   // entry e of the current chunk), so that the loop reads an index with v_readlane and issues
   // no scalar or vector memory load of its own.
   int chunk = 0;
-  int col_v = n > 0 ? my_col[beg + min(lane, n - 1)] : 0;
+  int col_v = n > 0 ? my_col[beg + list_slot(0, lane, n)] : 0;
   const uint64_t kmask = mask[j];
 
   bf16x8 kreg[KS], vreg[KS];
@@ -350,7 +354,7 @@ __global__ __launch_bounds__(256, 1) void k_fine_bwd_dkv(int Nc, int K, float sl
       const int e = min(t, end - 1) - beg;
       if ((e >> 6) != chunk) {
         chunk = e >> 6;
-        col_v = my_col[beg + min((chunk << 6) + lane, n - 1)];
+        col_v = my_col[beg + list_slot(chunk, lane, n)];
         asm volatile("" : "+v"(col_v));  // its wait stays inside this branch
       }
       return __builtin_amdgcn_readlane(col_v, e & 63);
@@ -567,10 +571,10 @@ __global__ __launch_bounds__(256, 1) void k_fine_bwd_dkv(int Nc, int K, float sl
   // merge the two query halves: all four partial results (dK, dV x two query halves) go through LDS at once
   const float inv_cnt = 1.0f / (float)__popcll(kmask);
   static_assert(4 * 64 * OS * 4 <= 4 * STAGE, "merge buffers must fit");
-  float* parts = (float*)smem;  // [dK half 0][dK half 1][dV half 0][dV half 1], each [64][OS]
+  float* parts_lds = (float*)smem;  // [dK half 0][dK half 1][dV half 0][dV half 1], each [64][OS]
 #pragma unroll
   for (int pass = 0; pass < 2; ++pass) {
-    float* Op = parts + (pass * 2 + qh) * 64 * OS + kh * 32 * OS;
+    float* Op = parts_lds + (pass * 2 + qh) * 64 * OS + kh * 32 * OS;
 #pragma unroll
     for (int x = 0; x < DVB; ++x)
 #pragma unroll
@@ -581,6 +585,25 @@ __global__ __launch_bounds__(256, 1) void k_fine_bwd_dkv(int Nc, int K, float sl
       }
   }
   __syncthreads();
+  if (slot >= 0) {  // one run of a split list: raw fp32 sums [dK | dV][64][D], finished by k_dkv_reduce
+    float* dst = parts + ((bh * cap + slot) * 2) * (long long)(64 * D);
+#pragma unroll
+    for (int pass = 0; pass < 2; ++pass) {
+      const float* part0 = parts_lds + pass * 2 * 64 * OS;
+      const float* part1 = part0 + 64 * OS;
+#pragma unroll
+      for (int it = 0; it < LPT; ++it) {
+        const int item = it * 256 + tid, r = item / CPR, ch = item % CPR;
+        const int m0 = merge_offset(r, ch * 8, OS), m1 = merge_offset(r, ch * 8 + 4, OS);
+        const float4 a0 = *(const float4*)(part0 + m0), a1 = *(const float4*)(part0 + m1);
+        const float4 b0 = *(const float4*)(part1 + m0), b1 = *(const float4*)(part1 + m1);
+        float4* o = (float4*)(dst + pass * 64 * D + r * D + ch * 8);
+        o[0] = make_float4(a0.x + b0.x, a0.y + b0.y, a0.z + b0.z, a0.w + b0.w);
+        o[1] = make_float4(a1.x + b1.x, a1.y + b1.y, a1.z + b1.z, a1.w + b1.w);
+      }
+    }
+    return;
+  }
 #pragma unroll
   for (int pass = 0; pass < 2; ++pass) {
     const float4 p0 = pass == 0 ? pk[0] : pv[0], p1 = pass == 0 ? pk[1] : pv[1];
@@ -588,7 +611,7 @@ __global__ __launch_bounds__(256, 1) void k_fine_bwd_dkv(int Nc, int K, float sl
                              p1.x * inv_cnt, p1.y * inv_cnt, p1.z * inv_cnt, p1.w * inv_cnt};
     const float mul = pass == 0 ? scale : 1.0f;
     uint4* dst = pass == 0 ? dk : dv;
-    const float* part0 = parts + pass * 2 * 64 * OS;
+    const float* part0 = parts_lds + pass * 2 * 64 * OS;
     const float* part1 = part0 + 64 * OS;
 #pragma unroll
     for (int it = 0; it < LPT; ++it) {
@@ -609,20 +632,72 @@ __global__ __launch_bounds__(256, 1) void k_fine_bwd_dkv(int Nc, int K, float sl
   }
 }
 
+// Sums the fp32 partial results of the split lists in slot order and finishes them like the dK/dV
+// epilogue does (scale, pooled-gradient term, zero pad rows, one rounding to bf16).  One workgroup
+// per possible split list of a (b, h); those beyond the actual number exit at once.
+template <int D>
+__global__ __launch_bounds__(256) void k_dkv_reduce(int Nc, int cap, float scale, const int32_t* __restrict__ split,
+                                                    const float* __restrict__ parts, const float* __restrict__ dkc,
+                                                    const float* __restrict__ dvc, const uint64_t* __restrict__ mask,
+                                                    uint4* __restrict__ dk, uint4* __restrict__ dv) {
+  constexpr int CPR = D / 8, LPT = kTile * CPR / 256;
+  const int per = cap / 2, r_ = blockIdx.x % per, tid = threadIdx.x;
+  const long long bh = blockIdx.x / per;
+  const int4* sp = (const int4*)split + bh * (per + 1);
+  if (r_ >= sp[0].x) return;
+  const int4 desc = sp[1 + r_];
+  const int j = desc.x, slot0 = desc.y, runs = desc.z;
+  const uint64_t kmask = mask[j];
+  const float inv_cnt = 1.0f / (float)__popcll(kmask);
+  const long long rows0 = bh * (long long)Nc * kTile;
+#pragma unroll
+  for (int pass = 0; pass < 2; ++pass) {
+    const float* pooled_row = (pass == 0 ? dkc : dvc) + (bh * Nc + j) * D + (tid % CPR) * 8;
+    const float4 p0 = *(const float4*)pooled_row, p1 = *(const float4*)(pooled_row + 4);
+    const float pooled[8] = {p0.x * inv_cnt, p0.y * inv_cnt, p0.z * inv_cnt, p0.w * inv_cnt,
+                             p1.x * inv_cnt, p1.y * inv_cnt, p1.z * inv_cnt, p1.w * inv_cnt};
+    const float mul = pass == 0 ? scale : 1.0f;
+    uint4* dst = pass == 0 ? dk : dv;
+#pragma unroll
+    for (int it = 0; it < LPT; ++it) {
+      const int item = it * 256 + tid, r = item / CPR, ch = item % CPR;
+      float sum[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+      for (int s = 0; s < runs; ++s) {
+        const float4* src = (const float4*)(parts + (((bh * cap + slot0 + s) * 2 + pass) * 64 + r) * (long long)D + ch * 8);
+        const float4 a = src[0], b = src[1];
+        sum[0] += a.x; sum[1] += a.y; sum[2] += a.z; sum[3] += a.w;
+        sum[4] += b.x; sum[5] += b.y; sum[6] += b.z; sum[7] += b.w;
+      }
+      uint4 ov = make_uint4(0, 0, 0, 0);
+      if ((kmask >> r) & 1) {
+        float res[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) res[e] = fmaf(sum[e], mul, pooled[e]);
+        ov = pack8(res);
+      }
+      dst[(rows0 + j * kTile + r) * CPR + ch] = ov;
+    }
+  }
+}
+
 hipError_t launch_fine_bwd_dkv(int BH, int Nc, int d, int K, float scale, const void* q, const void* k, const void* v,
-                               const void* dof, const int32_t* col, const int32_t* order,
-                               const void* ldb, const float* dkc, const float* dvc, const uint64_t* mask, void* dk,
-                               void* dv, hipStream_t s) {
+                               const void* dof, const int32_t* col, const int32_t* order, const int32_t* split,
+                               float* parts, int cap, const void* ldb, const float* dkc, const float* dvc,
+                               const uint64_t* mask, void* dk, void* dv, hipStream_t s) {
   const float sl2 = scale * kLog2e;
-  const unsigned grid = (unsigned)(BH * Nc);
-  if (d == 128)
+  const int items = Nc + cap;
+  const unsigned grid = (unsigned)(BH * items), rgrid = (unsigned)(BH * (cap / 2));
+  if (d == 128) {
     k_fine_bwd_dkv<128><<<grid, 256, 0, s>>>(Nc, K, sl2, scale, (const uint4*)q, (const uint4*)k, (const uint4*)v,
-                                             (const uint4*)dof, col, order, (const uint4*)ldb, dkc, dvc, mask, (uint4*)dk,
-                                             (uint4*)dv);
-  else
+                                             (const uint4*)dof, col, order, items, parts, cap, (const uint4*)ldb, dkc,
+                                             dvc, mask, (uint4*)dk, (uint4*)dv);
+    k_dkv_reduce<128><<<rgrid, 256, 0, s>>>(Nc, cap, scale, split, parts, dkc, dvc, mask, (uint4*)dk, (uint4*)dv);
+  } else {
     k_fine_bwd_dkv<64><<<grid, 256, 0, s>>>(Nc, K, sl2, scale, (const uint4*)q, (const uint4*)k, (const uint4*)v,
-                                            (const uint4*)dof, col, order, (const uint4*)ldb, dkc, dvc, mask, (uint4*)dk,
-                                            (uint4*)dv);
+                                            (const uint4*)dof, col, order, items, parts, cap, (const uint4*)ldb, dkc,
+                                            dvc, mask, (uint4*)dk, (uint4*)dv);
+    k_dkv_reduce<64><<<rgrid, 256, 0, s>>>(Nc, cap, scale, split, parts, dkc, dvc, mask, (uint4*)dk, (uint4*)dv);
+  }
   return hipGetLastError();
 }
 

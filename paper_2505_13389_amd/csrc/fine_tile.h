@@ -7,6 +7,7 @@
 //   - transposed reads (ds_read_b64_tr_b16: 4 consecutive rows x 64 contiguous bytes): the
 //     4 rows land in 4 different 64-byte groups of the 256-byte bank line.
 #pragma once
+#include "list_rules.h"
 #include "vsa_common.h"
 
 namespace vsa {
@@ -75,11 +76,11 @@ struct CubeList {
   uint32_t km_v;
   __device__ __forceinline__ void load_indices(int c) {
     chunk = c;
-    idx_v = list[min((c << 6) + lane, n - 1)];
+    idx_v = list[list_slot(c, lane, n)];
     asm volatile("" : "+v"(idx_v));  // consumed at once: the compiler's wait for the load is placed right here
     // a caller-supplied list is not trusted: an entry outside [0, ncubes) must not turn into an
     // out-of-bounds fetch (the result for such a list is unspecified, the access pattern is not)
-    idx_v = min(max(idx_v, 0), ncubes - 1);
+    idx_v = clamp_cube(idx_v, ncubes);
   }
   __device__ __forceinline__ void load_masks() {
     const uint64_t m = mask[idx_v];

@@ -1,0 +1,44 @@
+// Index rules of the block lists, shared by the kernels and by a host-side replay
+// (vsa_host_replay_lists) so that the arithmetic that keeps every access inside its buffer can be
+// checked on the CPU with hostile lists, without a GPU.
+//
+// A caller-supplied list (VSA_FLAG_INDICES_GIVEN) is not validated: entries outside [0, Nc),
+// duplicates and disorder give unspecified VALUES, but no access may leave a buffer.
+#pragma once
+#include <stdint.h>
+
+#if defined(__HIPCC__)
+#include <hip/hip_runtime.h>
+#define VSA_RULE __host__ __device__ __forceinline__
+#else
+#define VSA_RULE inline
+#endif
+
+namespace vsa {
+
+// Forward and dQ pass: the cube whose K/V tile is fetched for list entry `raw`.
+VSA_RULE int clamp_cube(int raw, int ncubes) { return raw < 0 ? 0 : (raw > ncubes - 1 ? ncubes - 1 : raw); }
+
+// Slot of the list read by lane `lane` for 64-entry chunk `chunk` of a list of n entries.
+VSA_RULE int list_slot(int chunk, int lane, int n) {
+  const int e = (chunk << 6) + lane;
+  return e < n - 1 ? e : n - 1;
+}
+
+// Transposed map: an entry takes part iff it names a cube; a (query cube, key cube) pair is one
+// bit, so duplicates collapse and a key cube's list never exceeds Nc entries, all lists of a
+// (b, h) together never Nc * K.
+VSA_RULE bool map_takes(int raw, int ncubes) { return (unsigned)raw < (unsigned)ncubes; }
+
+// A transposed list of `deg` entries is worked off in split_runs(deg, seg) runs; run r covers the
+// entries [run_bound(deg, runs, r), run_bound(deg, runs, r + 1)) of the list.
+VSA_RULE int split_runs(int deg, int seg) { return deg > seg ? (deg + seg - 1) / seg : 1; }
+VSA_RULE int run_bound(int deg, int runs, int r) { return (int)((long long)deg * r / runs); }
+// Partial-result slots a list of `deg` entries wants at split length `seg` (none when it stays whole).
+VSA_RULE int slots_wanted(int deg, int seg) { const int r = split_runs(deg, seg); return r > 1 ? r : 0; }
+// The split length of a (b, h) is chosen so that all wanted slots fit; this is the guard behind it:
+// a list gets its slots iff those wanted by the long lists before it (in cube order) plus its own
+// stay within `cap`.
+VSA_RULE bool split_granted(int runs, int wanted_before, int cap) { return runs > 1 && wanted_before + runs <= cap; }
+
+}  // namespace vsa

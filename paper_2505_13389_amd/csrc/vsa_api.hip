@@ -3,6 +3,9 @@
 #include "../../include/vsa.h"
 
 #include <atomic>
+#include <vector>
+
+#include "list_rules.h"
 
 #include "vsa_kernels.h"
 
@@ -85,10 +88,26 @@ struct BwdWs {
   uint64_t* mask;
   float *qc, *kc, *vc, *ld, *doc, *ac, *dsc, *dqc, *dkc, *dvc;
   void *dof, *ldb;
-  int32_t *row_ptr, *col, *order;
+  int32_t *row_ptr, *col, *order, *split;
   uint32_t* bits;
+  float* parts;
+  int seg, cap;
   size_t bytes;
 };
+// How the dK/dV pass cuts long transposed lists (see k_map_scan): a list longer than `seg` entries
+// is worked off by several workgroups; at most `cap` partial-result slots per (b, h).  `seg` is the
+// smallest split length: it aims at items no longer than half of what a compute unit gets when the
+// work is spread evenly (256 units), but not so short that start-up and the extra pass over the
+// partial sums outweigh the gain; the map scan lengthens it per (b, h) until the slots suffice.
+void split_plan(const vsa_params_t* p, const Geo& g, int* seg, int* cap) {
+  const long long entries = (long long)p->B * p->H * g.Nc * p->topk;
+  long long s = entries / 512;
+  if (s > 4LL * p->topk) s = 4LL * p->topk;
+  if (s < 16) s = 16;
+  *seg = (int)s;
+  int c = g.Nc / 4;
+  *cap = c < 16 ? 16 : (c > 64 ? 64 : c);
+}
 BwdWs carve_bwd(const vsa_params_t* p, const Geo& g, void* ws) {
   Carver c(ws);
   size_t bh = (size_t)p->B * p->H;
@@ -109,7 +128,10 @@ BwdWs carve_bwd(const vsa_params_t* p, const Geo& g, void* ws) {
   w.row_ptr = c.take<int32_t>(bh * (g.Nc + 1));
   w.col = c.take<int32_t>(bh * g.Nc * p->topk);
   w.bits = c.take<uint32_t>(bh * g.Nc * ((g.Nc + 31) / 32));
-  w.order = c.take<int32_t>(4 * bh * g.Nc);  // (cube, list begin, list end, 0) per dK/dV workgroup
+  split_plan(p, g, &w.seg, &w.cap);
+  w.order = c.take<int32_t>(4 * bh * (g.Nc + w.cap));  // (cube, run begin, run end, slot) per dK/dV workgroup
+  w.split = c.take<int32_t>(4 * bh * (w.cap / 2 + 1));
+  w.parts = c.take<float>(bh * w.cap * 2 * vsa::kTile * p->d);
   w.bytes = c.used;
   return w;
 }
@@ -290,12 +312,110 @@ int vsa_backward(const vsa_params_t* p, const void* q, const void* k, const void
                               w.dof, w.ld, w.ldb, scale, w.doc, lse_fine, s));
   VSA_TRY("coarse_bwd", vsa::launch_coarse_bwd(BH, g.Nc, p->d, scale, w.qc, w.kc, w.vc, lse_coarse, w.doc, w.ac, w.dsc, w.dqc, w.dkc,
                                  w.dvc, s));
-  VSA_TRY("transpose_map", vsa::launch_transpose_map(BH, g.Nc, p->topk, block_idx, w.bits, w.row_ptr, w.col, w.order, s));
+  VSA_TRY("transpose_map", vsa::launch_transpose_map(BH, g.Nc, p->topk, block_idx, w.bits, w.row_ptr, w.col, w.order, w.split, w.seg, w.cap, s));
   VSA_TRY("fine_bwd_dq", vsa::launch_fine_bwd_dq(BH, g.Nc, p->d, p->topk, scale, q, k, v, w.dof, block_idx, w.ld,
                                   w.dqc, w.mask, dq, s));
-  VSA_TRY("fine_bwd_dkv", vsa::launch_fine_bwd_dkv(BH, g.Nc, p->d, p->topk, scale, q, k, v, w.dof, w.col, w.order, w.ldb, w.dkc,
-                                   w.dvc, w.mask, dk, dv, s));
+  VSA_TRY("fine_bwd_dkv", vsa::launch_fine_bwd_dkv(BH, g.Nc, p->d, p->topk, scale, q, k, v, w.dof, w.col, w.order, w.split, w.parts,
+                                   w.cap, w.ldb, w.dkc, w.dvc, w.mask, dk, dv, s));
   return VSA_OK;
+}
+
+int vsa_host_replay_lists(const vsa_params_t* p, const int32_t* host_block_idx, int64_t* report) {
+  Geo g;
+  int rc = check_params(p, &g);
+  if (rc != VSA_OK) return rc;
+  if ((rc = check_topk(p, g)) != VSA_OK) return rc;
+  if (!host_block_idx) return VSA_ERR_NULL;
+  const int Nc = g.Nc, K = p->topk;
+  int seg_min, cap;
+  split_plan(p, g, &seg_min, &cap);
+  int64_t bad = 0, max_deg = 0, max_items = 0, max_slots = 0, max_split = 0, max_col = 0;
+  std::vector<unsigned char> bit((size_t)Nc * Nc);
+  std::vector<int> deg(Nc), beg(Nc);
+  for (long long bh = 0; bh < (long long)p->B * p->H; ++bh) {
+    const int32_t* lists = host_block_idx + bh * Nc * K;
+    // forward and dQ pass: every lane of every 64-entry chunk reads a list slot, then fetches a cube
+    for (int c = 0; c < Nc; ++c)
+      for (int chunk = 0; chunk * 64 < K; ++chunk)
+        for (int lane = 0; lane < 64; ++lane) {
+          const int slot = vsa::list_slot(chunk, lane, K);
+          if (slot < 0 || slot >= K) { ++bad; continue; }
+          const int cube = vsa::clamp_cube(lists[(size_t)c * K + slot], Nc);
+          if (cube < 0 || cube >= Nc) ++bad;
+        }
+    // transposed map: one bit per (query cube, key cube) pair that names a cube
+    std::fill(bit.begin(), bit.end(), 0);
+    for (int c = 0; c < Nc; ++c)
+      for (int e = 0; e < K; ++e) {
+        const int raw = lists[(size_t)c * K + e];
+        if (vsa::map_takes(raw, Nc)) {
+          if (raw < 0 || raw >= Nc) { ++bad; continue; }
+          bit[(size_t)raw * Nc + c] = 1;
+        }
+      }
+    long long total = 0;
+    for (int j = 0; j < Nc; ++j) {
+      int dsum = 0;
+      for (int c = 0; c < Nc; ++c) dsum += bit[(size_t)j * Nc + c];
+      deg[j] = dsum;
+      beg[j] = (int)total;
+      total += dsum;
+      if (dsum > max_deg) max_deg = dsum;
+    }
+    if (total > (long long)Nc * K) ++bad;  // capacity of the col array
+    if (total > max_col) max_col = total;
+    // split length of this (b, h): the smallest one >= seg_min at which all wanted slots fit
+    int seg = seg_min;
+    {
+      auto wanted_at = [&](int len) {
+        long long w = 0;
+        for (int j = 0; j < Nc; ++j) w += vsa::slots_wanted(deg[j], len);
+        return w;
+      };
+      while (wanted_at(seg) > cap) ++seg;
+    }
+    // dK/dV items: whole lists and the runs of split lists
+    int wanted = 0, nsplit = 0, items = 0, slots_hi = 0;
+    for (int j = 0; j < Nc; ++j) {
+      int runs = vsa::split_runs(deg[j], seg);
+      const int want = runs > 1 ? runs : 0;
+      const bool granted = vsa::split_granted(runs, wanted, cap);
+      const int slot0 = wanted;
+      wanted += want;
+      if (runs > 1 && !granted) ++bad;  // the split length was chosen so that every long list fits
+      if (!granted) runs = 1;
+      if (runs > 1) {
+        ++nsplit;
+        if (slot0 < 0 || slot0 + runs > cap) ++bad;
+        if (slot0 + runs > slots_hi) slots_hi = slot0 + runs;
+      }
+      int covered = 0;
+      for (int r = 0; r < runs; ++r) {
+        const int lo = vsa::run_bound(deg[j], runs, r), hi = vsa::run_bound(deg[j], runs, r + 1);
+        if (lo != covered || hi < lo || hi > deg[j]) ++bad;
+        covered = hi;
+        // the dK/dV workgroup of this run reads col[beg + lo + list_slot(chunk, lane, hi - lo)]
+        const int n = hi - lo;
+        for (int chunk = 0; chunk * 64 < n; ++chunk)
+          for (int lane = 0; lane < 64; ++lane) {
+            const long long at = (long long)beg[j] + lo + vsa::list_slot(chunk, lane, n);
+            if (at < beg[j] + lo || at >= beg[j] + hi || at >= (long long)Nc * K) ++bad;
+          }
+        ++items;
+      }
+      if (covered != deg[j]) ++bad;
+    }
+    if (items > Nc + cap) ++bad;     // descriptors per (b, h)
+    if (nsplit > cap / 2) ++bad;     // entries of the split-list table
+    if (items > max_items) max_items = items;
+    if (slots_hi > max_slots) max_slots = slots_hi;
+    if (nsplit > max_split) max_split = nsplit;
+  }
+  if (report) {
+    report[0] = bad; report[1] = max_deg; report[2] = max_items; report[3] = max_slots;
+    report[4] = max_split; report[5] = max_col; report[6] = seg_min; report[7] = cap;
+  }
+  return bad ? VSA_ERR_BAD_ARG : VSA_OK;
 }
 
 int vsa_profile_begin(int max_records) {

@@ -26,13 +26,13 @@ hipError_t launch_coarse_bwd(int BH, int Nc, int d, float scale, const float* qc
                              float* dvc,
                              hipStream_t s);
 hipError_t launch_transpose_map(int BH, int Nc, int K, const int32_t* idx, uint32_t* bits, int32_t* row_ptr,
-                                int32_t* col, int32_t* order, hipStream_t s);
+                                int32_t* col, int32_t* order, int32_t* split, int seg, int cap, hipStream_t s);
 hipError_t launch_fine_bwd_dq(int BH, int Nc, int d, int K, float scale, const void* q, const void* k, const void* v,
                               const void* dof, const int32_t* idx, const float* ld,
                               const float* dqc, const uint64_t* mask, void* dq, hipStream_t s);
 hipError_t launch_fine_bwd_dkv(int BH, int Nc, int d, int K, float scale, const void* q, const void* k, const void* v,
-                               const void* dof, const int32_t* col, const int32_t* order,
-                               const void* ldb, const float* dkc, const float* dvc, const uint64_t* mask, void* dk,
-                               void* dv, hipStream_t s);
+                               const void* dof, const int32_t* col, const int32_t* order, const int32_t* split,
+                               float* parts, int cap, const void* ldb, const float* dkc, const float* dvc,
+                               const uint64_t* mask, void* dk, void* dv, hipStream_t s);
 
 }  // namespace vsa

@@ -20,6 +20,8 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--iid", action="store_true", help="i.i.d. N(0,1) inputs instead of planted locality")
+    ap.add_argument("--sinks", type=int, default=0, help="planted inputs: key cubes that every query cube selects")
+    ap.add_argument("--sink-gain", type=float, default=1.0)
     args = ap.parse_args()
     import numpy as np
     import torch
@@ -42,7 +44,8 @@ def main():
     for H in args.heads:
         for d in args.dims:
             wl = synth.Workload(f"sweep_h{H}_d{d}", 2, H, 16, 32, 32, d, 32, planted=not args.iid)
-            raw = synth.make_inputs(wl, 0)
+            raw = (synth.iid_inputs(wl, 0) if args.iid else
+                   synth.planted_inputs(wl, 0, sinks=args.sinks, sink_gain=args.sink_gain))
             base = vsa.Problem(wl.B, wl.H, wl.T, wl.Hh, wl.W, wl.d, wl.topk, wl.cube)
             Np, Nc = vsa.vsa_padded_tokens(base)
             dev = {}
@@ -70,7 +73,7 @@ def main():
                 del buf
             for K, (tf, tb) in res.items():
                 fl = 4.0 * Np * K * 64 * wl.d * wl.H * wl.B
-                line = {"H": H, "d": d, "Nc": Nc, "topk": K, "sparsity": 1.0 - K / Nc, "planted": wl.planted,
+                line = {"H": H, "d": d, "Nc": Nc, "topk": K, "sparsity": 1.0 - K / Nc, "planted": wl.planted, "sinks": args.sinks,
                         "fwd_ms": tf, "fwd_bwd_ms": tb, "fwd_tflops": fl / tf / 1e9,
                         "fwd_bwd_tflops": 3.5 * fl / tb / 1e9,
                         "fwd_speedup_vs_dense": res[Nc][0] / tf, "fwd_bwd_speedup_vs_dense": res[Nc][1] / tb,

@@ -20,7 +20,7 @@ STATUS = {0: "VSA_OK", -1: "VSA_ERR_NULL", -2: "VSA_ERR_BAD_ARG", -3: "VSA_ERR_U
           -5: "VSA_ERR_WORKSPACE", -6: "VSA_ERR_HIP", -7: "VSA_ERR_SCRATCH_LIMIT"}
 EXPORTS = ["vsa_padded_tokens", "vsa_workspace_bytes", "vsa_tile_permute", "vsa_forward", "vsa_backward",
            "vsa_status_string", "vsa_profile_begin", "vsa_profile_count", "vsa_profile_name", "vsa_profile_ms",
-           "vsa_profile_end", "vsa_bench_mfma_rate", "vsa_forward_static", "vsa_static_scratch_bytes"]
+           "vsa_profile_end", "vsa_bench_mfma_rate", "vsa_forward_static", "vsa_static_scratch_bytes", "vsa_host_replay_lists"]
 
 
 class VsaParams(C.Structure):
@@ -59,6 +59,8 @@ def lib():
         L.vsa_forward_static.restype = C.c_int
         L.vsa_static_scratch_bytes.argtypes = []
         L.vsa_static_scratch_bytes.restype = C.c_size_t
+        L.vsa_host_replay_lists.argtypes = [C.POINTER(VsaParams), vp, vp]
+        L.vsa_host_replay_lists.restype = C.c_int
         L.vsa_backward.argtypes = [C.POINTER(VsaParams)] + [vp] * 17 + [C.c_size_t, vp]
         L.vsa_backward.restype = C.c_int
         L.vsa_bench_mfma_rate.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.POINTER(C.c_double), C.c_void_p]
@@ -188,6 +190,17 @@ class Buffers:
         vsa_backward(self.pb, q, k, v, gate_c, gate_f, dout, self.block_idx, self.out_fine, self.lse_fine,
                      self.out_coarse, self.lse_coarse, self.dq, self.dk, self.dv, self.dgate_c, self.dgate_f,
                      self.workspace, workspace_kept=workspace_kept)
+
+
+def vsa_host_replay_lists(pb: Problem, block_idx):
+    """Host-only: replays the kernels' list index arithmetic on a numpy int32 [B,H,Nc,topk] array.
+    Returns (status, report dict)."""
+    import numpy as np
+    idx = np.ascontiguousarray(block_idx, dtype=np.int32)
+    rep = (C.c_int64 * 8)()
+    rc = lib().vsa_host_replay_lists(C.byref(pb.params()), idx.ctypes.data_as(C.c_void_p), rep)
+    names = ("violations", "longest_list", "items", "slots", "split_lists", "col_entries", "seg", "cap")
+    return rc, dict(zip(names, (int(v) for v in rep)))
 
 
 def vsa_bench_mfma_rate(operands: torch.Tensor, sink: torch.Tensor, workgroups: int, iters: int) -> float:

@@ -86,3 +86,30 @@ def test_bench_refuses_more_than_one_gpu():
     assert r.returncode != 0
     assert "ONE GPU" in r.stderr
     assert r.stdout.strip() == ""
+
+
+@pytest.mark.parametrize("shape,topk", [((2, 2, 8, 16, 16), 8), ((1, 2, 12, 16, 20), 6), ((1, 1, 21, 30, 52), 78),
+                                        ((1, 2, 16, 32, 32), 130)])
+def test_list_index_rules_keep_hostile_lists_in_bounds(lib, shape, topk):
+    """The clamp / skip / split arithmetic the kernels apply to block lists, replayed on the CPU through
+    the same functions: lists full of out-of-range entries, duplicates and disorder, lists where every
+    query cube names the same few key cubes (longest possible transposed lists), and ordinary ones."""
+    import numpy as np
+    B, H, T, Hh, W = shape
+    pb = vsa.Problem(B, H, T, Hh, W, 64, topk)
+    _, Nc = vsa.vsa_padded_tokens(pb)
+    rng = np.random.Generator(np.random.PCG64(17))
+    hostile = rng.integers(-9, Nc + 9, size=(B, H, Nc, topk), dtype=np.int64).astype(np.int32)
+    hostile[0, 0, 0, :] = np.iinfo(np.int32).max
+    hostile[0, 0, 1 % Nc, :] = np.iinfo(np.int32).min
+    same = np.broadcast_to(np.arange(topk, dtype=np.int32) % Nc, (B, H, Nc, topk))
+    ordinary = np.sort(np.argsort(rng.random((B, H, Nc, Nc)), axis=-1)[..., :topk], axis=-1).astype(np.int32)
+    for lists in (hostile, same, ordinary):
+        rc, rep = vsa.vsa_host_replay_lists(pb, lists)
+        assert rc == 0 and rep["violations"] == 0, rep
+        assert rep["longest_list"] <= Nc and rep["col_entries"] <= Nc * topk
+        assert rep["items"] <= Nc + rep["cap"] and rep["slots"] <= rep["cap"] and rep["split_lists"] <= rep["cap"] // 2
+    rc, rep = vsa.vsa_host_replay_lists(pb, same)
+    assert rep["longest_list"] == Nc
+    if Nc > rep["seg"] and 2 * topk <= rep["cap"]:  # (more equal long lists than slots: nothing to balance)
+        assert rep["split_lists"] == topk and rep["items"] > Nc  # the sink lists are shared by several workgroups

@@ -218,6 +218,45 @@ def test_backward_on_oracle_indices(vsa, name, with_gate_f):
         assert not bf16_to_np(getattr(buf, name_))[:, :, ~valid].any(), f"{name_}: pad rows must be zero"
 
 
+@pytest.mark.parametrize("grid3,d,topk,sink_gain,pad", [((8, 16, 16), 64, 8, 1.0, False), ((12, 16, 20), 128, 6, 1.0, True),
+                                                       ((11, 15, 19), 64, 9, 0.3, True)])
+def test_backward_with_split_transposed_lists(vsa, grid3, d, topk, sink_gain, pad):
+    """Sink cubes that every query cube selects: their transposed lists (in-degree = all cubes) are far
+    longer than the split length of these small launches (16 entries), so several workgroups share a
+    list and a second kernel sums their fp32 partial dK, dV; with the strong sinks more lists want
+    splitting than there are slots, so some stay whole."""
+    import torch
+    wl = Workload("sinks", 1, 2, *grid3, d, topk, planted=True)
+    bits = tiled_bits(wl, seed=12, sinks=2, sink_gain=sink_gain, pad_garbage=pad)
+    # a sink cube's dK, dV sum over every query token; with dO ~ N(0,1) they reach 20, where the bf16
+    # output spacing alone (0.125) exceeds the absolute bound of the parity bar.  Gradients are linear
+    # in dO: dO / 16 (exact in bf16) brings them back to order one.
+    from paper_2505_13389_amd import synth
+    bits["dout"] = synth.f32_to_bf16_bits(synth.bf16_bits_to_f32(bits["dout"]) / 16.0)
+    x = widen(bits)
+    g = grid_of(wl)
+    fwd = run_oracle_fwd(wl, x)
+    indeg = np.stack([np.bincount(fwd["block_idx"][0, h].ravel(), minlength=g.Nc) for h in range(wl.H)])
+    assert indeg.max() >= 2 * 16 and wl.B * wl.H * g.Nc * topk // 512 < 16
+    ref = orc.backward(g, x["q"], x["k"], x["v"], x["gate_c"], x["gate_f"], x["dout"], fwd["block_idx"], wl.topk,
+                       real="f32")
+    dev = to_dev(bits)
+    buf = run_gpu_fwd(vsa, wl, dev, block_idx=fwd["block_idx"], backward=True)
+    buf.backward(dev["q"], dev["k"], dev["v"], dev["gate_c"], dev["gate_f"], dev["dout"])
+    torch.cuda.synchronize()
+    first = [getattr(buf, n).clone() for n in ("dk", "dv")]
+    for name_ in ("dq", "dk", "dv", "dgate_c", "dgate_f"):
+        assert_close(bf16_to_np(getattr(buf, name_)), ref[name_], name_)
+    valid, _ = orc.valid_mask(g)
+    for name_ in ("dk", "dv"):
+        assert not bf16_to_np(getattr(buf, name_))[:, :, ~valid].any(), f"{name_}: pad rows must be zero"
+    # the partial sums are added in a fixed order: a second run gives the same bits
+    buf.backward(dev["q"], dev["k"], dev["v"], dev["gate_c"], dev["gate_f"], dev["dout"])
+    torch.cuda.synchronize()
+    for a, b_ in zip(first, (buf.dk, buf.dv)):
+        assert torch.equal(a.view(torch.int16), b_.view(torch.int16))
+
+
 def test_backward_with_kept_workspace_is_bit_identical(vsa):
     """VSA_FLAG_WORKSPACE_KEPT only skips recomputing the pooled tensors the forward left behind."""
     import torch
