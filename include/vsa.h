@@ -54,6 +54,11 @@ typedef enum {
                                       call (same parameters, same q, k, v) was given, and nothing has
                                       written to it since: the pooled tensors it still holds are used
                                       instead of being computed again.  Size it for the backward. */
+#define VSA_FLAG_COARSE_FUSED 8u  /* vsa_forward, Nc <= 256 only (ignored above): run the coarse stage as ONE
+                                    launch that keeps the score block in LDS (Sec. 2.4, App. D) instead of
+                                    three launches with the score matrix in the workspace.  Bit-identical
+                                    results; on this chip the three-launch form is the faster one at every
+                                    size measured, so it is the default and this flag is for measuring */
 #define VSA_MAX_CUBES 4096        /* largest supported Nc                                 */
 #define VSA_STATIC_SCRATCH_MIB 40 /* size of the scratch buffer behind vsa_forward_static, MiB */
 

@@ -3,11 +3,13 @@
 // softmax, top-K and mask->index conversion in one kernel; so does k_coarse_rows below).
 //
 // Everything is fp32: the selection must agree with an fp32 reference except on near ties,
-// and the whole stage is < 0.2 % of the attention FLOPs.  Three launches:
+// and the whole stage is < 0.2 % of the attention FLOPs.  Three launches (up to 256 cubes a
+// single-launch form, k_coarse_fused, exists as well; it is the slower one on this chip):
 //   S  = scale * Qc Kc^T          fp32 matrix-core GEMM, S materialised [B*H, Nc, Nc]
 //   k_coarse_rows                 one wavefront per row: log-sum-exp, top-K -> index list,
 //                                 probabilities written back over S
 //   Oc = P Vc                     fp32 matrix-core GEMM
+#include "gemm32_tile.h"
 #include "vsa_kernels.h"
 
 namespace vsa {
@@ -27,14 +29,13 @@ __device__ __forceinline__ float wave_sum(float x) {
   return x;
 }
 
-// One wavefront per row of the score matrix; lane j holds logits j, j+64, ... (NCH per lane).
+// One row of the score matrix worked off by one wavefront; lane j holds logits j, j+64, ... (NCH per
+// lane).  `srow` may point into global memory or into LDS.  Writes the row's probabilities back over
+// the logits, its log-sum-exp to *lse_out (if given) and, with emit_idx, the ascending list of its K
+// largest logits (ties to the lower index) to `out`.
 template <int NCH>
-__global__ __launch_bounds__(256) void k_coarse_rows(int rows, int Nc, int K, float* __restrict__ sc,
-                                                     float* __restrict__ lse_c, int32_t* __restrict__ idx,
-                                                     int emit_idx) {
-  const int row = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
-  if (row >= rows) return;
-  float* srow = sc + (long long)row * Nc;
+__device__ __forceinline__ void coarse_row(float* srow, int Nc, int K, float* lse_out, int32_t* out, int emit_idx,
+                                           int lane) {
   const int nch = (Nc + 63) / 64;
   float s[NCH];
 #pragma unroll
@@ -52,49 +53,143 @@ __global__ __launch_bounds__(256) void k_coarse_rows(int rows, int Nc, int K, fl
 #pragma unroll
   for (int ch = 0; ch < NCH; ++ch)
     if (ch * 64 + lane < Nc) srow[ch * 64 + lane] = fast_exp2((s[ch] - lse) * kLog2e);
-  if (lane == 0 && lse_c) lse_c[row] = lse;
+  if (lane == 0 && lse_out) *lse_out = lse;
 
   if (emit_idx) {
-    // K-th largest key by bitwise binary search: T = max{t : #(key >= t) >= K}, stopped early once a
-    // prefix separates exactly K keys (the count is wave-uniform, so is the exit).
-    uint32_t T = 0;
-    for (int bit = 31; bit >= 0; --bit) {
-      const uint32_t cand = T | (1u << bit);
+    // Order-preserving integer keys; lanes beyond Nc hold key 0 and never count (every threshold
+    // tried is >= 1).  T = the K-th largest key, by bisection of the key range [min, max]:
+    // cnt(x) = #(key >= x) is non-increasing, cnt(lo) >= K > cnt(hi) throughout.  The search stops
+    // as soon as a threshold separates exactly K keys (all counts are wave-uniform, so is the
+    // exit): about log2(range / gap at rank K) steps on spread-out logits, 32 at most.
+    uint32_t key[NCH];
+    uint32_t kmin = 0xffffffffu, kmax = 0u;
+#pragma unroll
+    for (int ch = 0; ch < NCH; ++ch) {
+      const bool valid = ch * 64 + lane < Nc;
+      key[ch] = valid ? sortable_key(s[ch]) : 0u;
+      if (valid) kmin = min(kmin, key[ch]);
+      kmax = max(kmax, key[ch]);
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+      kmin = min(kmin, (uint32_t)__shfl_xor((int)kmin, o));
+      kmax = max(kmax, (uint32_t)__shfl_xor((int)kmax, o));
+    }
+    auto count_ge = [&](uint32_t x) {
       int cnt = 0;
 #pragma unroll
       for (int ch = 0; ch < NCH; ++ch)
-        if (ch < nch) {
-          uint32_t key = (ch * 64 + lane < Nc) ? sortable_key(s[ch]) : 0u;
-          cnt += __popcll(__ballot(key >= cand));
-        }
+        if (ch < nch) cnt += __popcll(__ballot(key[ch] >= x));
+      return cnt;
+    };
+    unsigned long long lo = __builtin_amdgcn_readfirstlane(kmin), hi = (unsigned long long)__builtin_amdgcn_readfirstlane(kmax) + 1ull;
+    uint32_t T = (uint32_t)lo;
+    while (hi - lo > 1ull) {
+      const uint32_t mid = (uint32_t)((lo + hi) >> 1);
+      const int cnt = count_ge(mid);
       if (cnt >= K) {
-        T = cand;
-        if (cnt == K) break;  // exactly K keys at or above this prefix: the lower bits cannot change the set
+        lo = mid;
+        T = mid;
+        if (cnt == K) break;  // exactly K keys at or above mid: they are the set
+      } else {
+        hi = mid;
       }
     }
     int n_gt = 0;
 #pragma unroll
     for (int ch = 0; ch < NCH; ++ch)
-      if (ch < nch) {
-        uint32_t key = (ch * 64 + lane < Nc) ? sortable_key(s[ch]) : 0u;
-        n_gt += __popcll(__ballot(key > T));
-      }
+      if (ch < nch) n_gt += __popcll(__ballot(key[ch] > T));
     const int need = K - n_gt;  // entries equal to the threshold still to take, lowest index first
     int eq_seen = 0, base = 0;
-    int32_t* out = idx + (long long)row * K;
     const uint64_t lt = (1ull << lane) - 1ull;
 #pragma unroll
     for (int ch = 0; ch < NCH; ++ch)
       if (ch < nch) {
-        uint32_t key = (ch * 64 + lane < Nc) ? sortable_key(s[ch]) : 0u;
-        bool eq = (key == T) && (ch * 64 + lane < Nc);
-        uint64_t beq = __ballot(eq);
-        bool take = (key > T) || (eq && (eq_seen + __popcll(beq & lt) < need));
+        const bool eq = (key[ch] == T) && (ch * 64 + lane < Nc);
+        const uint64_t beq = __ballot(eq);
+        const bool take = (key[ch] > T) || (eq && (eq_seen + __popcll(beq & lt) < need));
         eq_seen += __popcll(beq);
-        uint64_t bsel = __ballot(take);
-        if (take) out[base + __popcll(bsel & lt)] = ch * 64 + lane;
+        const uint64_t bsel = __ballot(take);
+        const int pos = base + __popcll(bsel & lt);
+        if (take && pos < K) out[pos] = ch * 64 + lane;  // (pos < K always holds for finite logits)
         base += __popcll(bsel);
       }
+  }
+}
+
+template <int NCH>
+__global__ __launch_bounds__(256) void k_coarse_rows(int rows, int Nc, int K, float* __restrict__ sc,
+                                                     float* __restrict__ lse_c, int32_t* __restrict__ idx,
+                                                     int emit_idx) {
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (row >= rows) return;
+  coarse_row<NCH>(sc + (long long)row * Nc, Nc, K, lse_c ? lse_c + row : nullptr, idx + (long long)row * K, emit_idx,
+                  lane);
+}
+
+// The whole coarse stage of a short sequence (Nc <= 256) in ONE launch, the score block never
+// leaving the chip (Sec. 2.4 fuses softmax, top-K and index conversion; App. D notes that the coarse
+// stage weighs most at short sequences).  One workgroup of 16 wavefronts per (b, h, 64 query cubes):
+//   1. four teams of four wavefronts form the [64 x Nc] block of logits, 64 columns per team, with
+//      fp32 matrix instructions into LDS;
+//   2. the 16 wavefronts take the rows one by one (log-sum-exp, top-K list, probabilities written
+//      back into LDS);
+//   3. a second fp32 product of the probabilities with Vc gives the block's rows of O_c, 64 columns
+//      per team.
+// Same arithmetic, in the same order per element, as the three-launch path: bit-identical results.
+constexpr int kFusedMaxCubes = 256;
+template <int D, int NCH>
+__global__ __launch_bounds__(1024) void k_coarse_fused(int Nc, int K, float scale, const float* __restrict__ qc,
+                                                       const float* __restrict__ kc, const float* __restrict__ vc,
+                                                       float* __restrict__ oc, float* __restrict__ lse_c,
+                                                       int32_t* __restrict__ idx, int emit_idx) {
+  constexpr int LDS_ROW = kFusedMaxCubes + 4;  // + 4: rows start 4 banks apart (conflict-free column reads)
+  constexpr int TEAMS = 4;
+  __shared__ __attribute__((aligned(16))) float S[64 * LDS_ROW];
+  __shared__ __attribute__((aligned(16))) float As[TEAMS][64][36];
+  __shared__ __attribute__((aligned(16))) float Bs[TEAMS][64][36];
+  const int blocks = (Nc + 63) / 64;
+  const int m0 = (blockIdx.x % blocks) * 64;
+  const long long bh = blockIdx.x / blocks;
+  const int team = threadIdx.x >> 8, tid = threadIdx.x & 255, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave & 1, wn = wave >> 1, l32 = lane & 31, h = lane >> 5;
+  const float* qb = qc + (bh * Nc + m0) * D;
+  const float* kb = kc + bh * Nc * D;
+  const float* vb = vc + bh * Nc * D;
+  const int rows_valid = min(64, Nc - m0), kpad = (Nc + 31) & ~31;
+
+  // 1. logits: S[m][n] = scale * Qc[m0 + m] . Kc[n]; columns Nc .. kpad-1 are zero for the second product
+  {
+    const int n0 = team * 64;
+    f32x16g acc;
+    gemm_tile_global(As[team], Bs[team], qb, D, 1, rows_valid, kb + (long long)min(n0, Nc - 1) * D, D, 1,
+                     n0 < Nc ? Nc - n0 : 0, D, tid, acc);
+    const int n = n0 + wn * 32 + l32;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int m = wm * 32 + 8 * (i / 4) + 4 * h + (i % 4);
+      if (n < kpad) S[m * LDS_ROW + n] = n < Nc ? scale * acc[i] : 0.f;
+    }
+  }
+  __syncthreads();
+  // 2. rows: softmax statistics, top-K list, probabilities back into S (rows of the block beyond Nc
+  //    hold the logits of zero queries and are never stored)
+  for (int r = (int)(threadIdx.x >> 6); r < rows_valid; r += 16) {
+    const long long row = bh * Nc + m0 + r;
+    coarse_row<NCH>(S + r * LDS_ROW, Nc, K, lse_c ? lse_c + row : nullptr, idx + row * K, emit_idx, lane);
+  }
+  __syncthreads();
+  // 3. O_c[m0 + m][e] = sum_n P[m][n] Vc[n][e]
+  {
+    const int e0 = team * 64;
+    f32x16g acc;
+    gemm_tile_lds_a(S, LDS_ROW, Bs[team], vb + min(e0, D - 1), 1, D, e0 < D ? D - e0 : 0, Nc, tid, acc);
+    const int e = e0 + wn * 32 + l32;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int m = wm * 32 + 8 * (i / 4) + 4 * h + (i % 4);
+      if (m < rows_valid && e < D) oc[(bh * Nc + m0 + m) * D + e] = acc[i];
+    }
   }
 }
 
@@ -102,14 +197,28 @@ hipError_t gemm32(int batch, int M, int N, int Kd, float alpha, const float* a, 
                   const float* b, long long sbb, int sbk, int sbn, float* c, long long scb, hipStream_t s);
 
 hipError_t launch_coarse(int BH, int Nc, int d, int K, float scale, const float* qc, const float* kc, const float* vc,
-                         float* sc, float* oc, float* lse_c, int32_t* idx, int emit_idx, hipStream_t s) {
+                         float* sc, float* oc, float* lse_c, int32_t* idx, int emit_idx, int fused, hipStream_t s) {
   const long long sx = (long long)Nc * d, ss = (long long)Nc * Nc;
   hipError_t e;
+  if (Nc <= kFusedMaxCubes && fused) {
+    const unsigned fgrid = (unsigned)(BH * ((Nc + 63) / 64));
+#define VSA_FUSED(D_, NCH_) k_coarse_fused<D_, NCH_><<<fgrid, 1024, 0, s>>>(Nc, K, scale, qc, kc, vc, oc, lse_c, idx, emit_idx)
+    // NCH = logits per lane of the row step: the smallest that covers Nc
+    if (d == 128) {
+      if (Nc <= 64) VSA_FUSED(128, 1); else if (Nc <= 128) VSA_FUSED(128, 2); else VSA_FUSED(128, 4);
+    } else {
+      if (Nc <= 64) VSA_FUSED(64, 1); else if (Nc <= 128) VSA_FUSED(64, 2); else VSA_FUSED(64, 4);
+    }
+#undef VSA_FUSED
+    return hipGetLastError();
+  }
   if ((e = gemm32(BH, Nc, Nc, d, scale, qc, sx, d, 1, kc, sx, 1, d, sc, ss, s)) != hipSuccess) return e;
   const int rows = BH * Nc;
   const unsigned grid = (unsigned)((rows + 3) / 4);
   // NCH = logits per lane (compile-time bound of the per-lane loops): the smallest that covers Nc
-  if (Nc <= 128)
+  if (Nc <= 64)
+    k_coarse_rows<1><<<grid, 256, 0, s>>>(rows, Nc, K, sc, lse_c, idx, emit_idx);
+  else if (Nc <= 128)
     k_coarse_rows<2><<<grid, 256, 0, s>>>(rows, Nc, K, sc, lse_c, idx, emit_idx);
   else if (Nc <= 256)
     k_coarse_rows<4><<<grid, 256, 0, s>>>(rows, Nc, K, sc, lse_c, idx, emit_idx);

@@ -52,22 +52,14 @@ hipError_t launch_tile_permute(const Geo& g, int BH, int H_blhd, int d, const vo
   return hipGetLastError();
 }
 
-__global__ void k_cube_masks(Geo g, uint64_t* __restrict__ mask) {
-  int c = blockIdx.x * blockDim.x + threadIdx.x;
-  if (c < g.Nc) mask[c] = cube_valid_mask(g, c);
-}
-
-hipError_t launch_cube_masks(const Geo& g, uint64_t* mask, hipStream_t s) {
-  k_cube_masks<<<(g.Nc + 255) / 256, 256, 0, s>>>(g, mask);
-  return hipGetLastError();
-}
-
 // Mean over the valid tokens of each cube (Sec. 2.2 coarse stage), fp32 result.
 // One workgroup per (tensor, b*h, cube): 64 rows x D bf16 in, D floats out.  Thread t owns
 // 16-byte chunk t % (D/8) of rows t / (D/8), t / (D/8) + 256/(D/8), ...; the partial sums
 // are added across row groups in a fixed order, so the result is deterministic.
+// The cube's validity mask comes from the geometry (one ballot per wavefront) and is also written
+// to mask[c] for the kernels that follow (by the workgroups of the first (b, h) and tensor).
 template <int D>
-__global__ __launch_bounds__(256) void k_pool(int Nc, long long Np, const uint64_t* __restrict__ mask,
+__global__ __launch_bounds__(256) void k_pool(Geo g, long long Np, uint64_t* __restrict__ mask,
                                               const uint4* __restrict__ q, const uint4* __restrict__ k,
                                               const uint4* __restrict__ v, float* __restrict__ qc,
                                               float* __restrict__ kc, float* __restrict__ vc) {
@@ -75,11 +67,13 @@ __global__ __launch_bounds__(256) void k_pool(int Nc, long long Np, const uint64
   constexpr int RG = 256 / CPR;     // row groups
   constexpr int RPT = kTile / RG;   // rows per thread
   __shared__ float part[RG][D + 4];
+  const int Nc = g.Nc;
   const int c = blockIdx.x % Nc;
   const long long bh = blockIdx.x / Nc;
   const uint4* src = blockIdx.y == 0 ? q : (blockIdx.y == 1 ? k : v);
   float* dst = blockIdx.y == 0 ? qc : (blockIdx.y == 1 ? kc : vc);
-  const uint64_t m = mask[c];
+  const uint64_t m = cube_valid_mask_wave(g, c, threadIdx.x & 63);
+  if (blockIdx.x < Nc && blockIdx.y == 0 && threadIdx.x == 0) mask[c] = m;
   const int ch = threadIdx.x % CPR, rg = threadIdx.x / CPR;
   float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
   const uint4* base = src + (bh * Np + (long long)c * kTile) * CPR;
@@ -104,13 +98,13 @@ __global__ __launch_bounds__(256) void k_pool(int Nc, long long Np, const uint64
   }
 }
 
-hipError_t launch_pool(const Geo& g, int BH, int d, const uint64_t* mask, const void* q, const void* k, const void* v,
+hipError_t launch_pool(const Geo& g, int BH, int d, uint64_t* mask, const void* q, const void* k, const void* v,
                        float* qc, float* kc, float* vc, hipStream_t s) {
   dim3 grid((unsigned)(BH * g.Nc), 3);
   if (d == 128)
-    k_pool<128><<<grid, 256, 0, s>>>(g.Nc, g.Np, mask, (const uint4*)q, (const uint4*)k, (const uint4*)v, qc, kc, vc);
+    k_pool<128><<<grid, 256, 0, s>>>(g, g.Np, mask, (const uint4*)q, (const uint4*)k, (const uint4*)v, qc, kc, vc);
   else
-    k_pool<64><<<grid, 256, 0, s>>>(g.Nc, g.Np, mask, (const uint4*)q, (const uint4*)k, (const uint4*)v, qc, kc, vc);
+    k_pool<64><<<grid, 256, 0, s>>>(g, g.Np, mask, (const uint4*)q, (const uint4*)k, (const uint4*)v, qc, kc, vc);
   return hipGetLastError();
 }
 

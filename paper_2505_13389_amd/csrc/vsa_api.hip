@@ -194,9 +194,8 @@ int enqueue_forward(const vsa_params_t* p, const Geo& g, const void* q, const vo
   float* lse_c = lse_coarse ? lse_coarse : w.lse_c;
   int32_t* idx = block_idx ? block_idx : w.idx;
 
-  VSA_TRY("cube_masks", vsa::launch_cube_masks(g, w.mask, s));
   VSA_TRY("pool", vsa::launch_pool(g, BH, p->d, w.mask, q, k, v, w.qc, w.kc, w.vc, s));
-  VSA_TRY("coarse", vsa::launch_coarse(BH, g.Nc, p->d, p->topk, scale, w.qc, w.kc, w.vc, w.sc, oc, lse_c, idx, given ? 0 : 1, s));
+  VSA_TRY("coarse", vsa::launch_coarse(BH, g.Nc, p->d, p->topk, scale, w.qc, w.kc, w.vc, w.sc, oc, lse_c, idx, given ? 0 : 1, (p->flags & VSA_FLAG_COARSE_FUSED) ? 1 : 0, s));
   VSA_TRY("fine_fwd", vsa::launch_fine_fwd(BH, g.Nc, p->d, p->topk, scale, q, k, v, gate_c, gate_f, idx, oc, w.mask, out, out_fine,
                                lse_fine, s));
   return VSA_OK;
@@ -305,7 +304,6 @@ int vsa_backward(const vsa_params_t* p, const void* q, const void* k, const void
 
   // forward and backward carve the cube masks and the pooled tensors at the same offsets
   if (!(p->flags & VSA_FLAG_WORKSPACE_KEPT)) {
-    VSA_TRY("cube_masks", vsa::launch_cube_masks(g, w.mask, s));
     VSA_TRY("pool", vsa::launch_pool(g, BH, p->d, w.mask, q, k, v, w.qc, w.kc, w.vc, s));
   }
   VSA_TRY("bwd_pre", vsa::launch_bwd_pre(BH, g.Nc, p->d, w.mask, dout, gate_c, gate_f, out_fine, out_coarse, dgate_c, dgate_f,

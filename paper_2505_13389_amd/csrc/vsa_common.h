@@ -71,14 +71,11 @@ constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
 // Bit p of a cube's mask is set iff in-cube slot p = (pt*Ch + ph)*Cw + pw holds a valid token.
-__device__ __forceinline__ uint64_t cube_valid_mask(const Geo& g, int c) {
-  int cw = c % g.Nw, ch = (c / g.Nw) % g.Nh, ct = c / (g.Nw * g.Nh);
-  int vt = min(g.Ct, g.T - ct * g.Ct), vh = min(g.Ch, g.Hh - ch * g.Ch), vw = min(g.Cw, g.W - cw * g.Cw);
-  uint64_t m = 0;
-  for (int pt = 0; pt < vt; ++pt)
-    for (int ph = 0; ph < vh; ++ph)
-      for (int pw = 0; pw < vw; ++pw) m |= 1ull << ((pt * g.Ch + ph) * g.Cw + pw);
-  return m;
+// Computed by a whole wavefront: lane p answers for slot p.
+__device__ __forceinline__ uint64_t cube_valid_mask_wave(const Geo& g, int c, int lane) {
+  const int cw = c % g.Nw, ch = (c / g.Nw) % g.Nh, ct = c / (g.Nw * g.Nh);
+  const int pw = lane % g.Cw, ph = (lane / g.Cw) % g.Ch, pt = lane / (g.Cw * g.Ch);
+  return __ballot(ct * g.Ct + pt < g.T && ch * g.Ch + ph < g.Hh && cw * g.Cw + pw < g.W);
 }
 
 }  // namespace vsa

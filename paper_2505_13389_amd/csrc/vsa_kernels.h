@@ -7,12 +7,11 @@ namespace vsa {
 
 hipError_t launch_tile_permute(const Geo& g, int BH, int H_blhd, int d, const void* src, void* dst, bool inverse,
                                hipStream_t s);
-hipError_t launch_cube_masks(const Geo& g, uint64_t* mask, hipStream_t s);
 hipError_t launch_mfma_rate(const void* operands, float* sink, int workgroups, int iters, hipStream_t s);
-hipError_t launch_pool(const Geo& g, int BH, int d, const uint64_t* mask, const void* q, const void* k, const void* v,
+hipError_t launch_pool(const Geo& g, int BH, int d, uint64_t* mask, const void* q, const void* k, const void* v,
                        float* qc, float* kc, float* vc, hipStream_t s);
 hipError_t launch_coarse(int BH, int Nc, int d, int K, float scale, const float* qc, const float* kc, const float* vc,
-                         float* sc, float* oc, float* lse_c, int32_t* idx, int emit_idx, hipStream_t s);
+                         float* sc, float* oc, float* lse_c, int32_t* idx, int emit_idx, int fused, hipStream_t s);
 hipError_t launch_fine_fwd(int BH, int Nc, int d, int K, float scale, const void* q, const void* k, const void* v,
                            const void* gate_c, const void* gate_f, const int32_t* idx, const float* oc,
                            const uint64_t* mask, void* out, void* out_fine, float* lse_f, hipStream_t s);

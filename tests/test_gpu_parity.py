@@ -117,6 +117,23 @@ def test_coarse_stage_and_topk(vsa, name):
     assert len(differ) <= max(1, rows // 50), f"{len(differ)} of {rows} rows differ (near-ties only are expected)"
 
 
+@pytest.mark.parametrize("name", ["tiny", "pad128", "one_cube", "planted_pad128", "k65", "mid_head"])
+def test_single_launch_coarse_stage_equals_the_three_launch_form(vsa, name):
+    """Up to 256 cubes the coarse stage can run as one launch with the score block in LDS (a flag);
+    it must give the same bits as the three-launch form (score matrix through the workspace)."""
+    import dataclasses
+    import torch
+    wl = SMALL[name] if name in SMALL else Workload("mid_head", 1, 2, 16, 32, 32, 128, 32)
+    dev = to_dev(tiled_bits(wl, seed=13))
+    plain = run_gpu_fwd(vsa, wl, dev)
+    pb = dataclasses.replace(problem_of(wl), flags=vsa.VSA_FLAG_COARSE_FUSED)
+    fused = vsa.Buffers(pb, backward=False)
+    fused.forward(dev["q"], dev["k"], dev["v"], dev["gate_c"], dev["gate_f"])
+    torch.cuda.synchronize()
+    for n in ("block_idx", "out_coarse", "lse_coarse", "out", "lse_fine"):
+        assert torch.equal(getattr(fused, n).view(torch.uint8), getattr(plain, n).view(torch.uint8)), n
+
+
 def test_topk_ties_go_to_the_lower_index(vsa):
     wl = SMALL["tiny"]
     bits = tiled_bits(wl, seed=2)
