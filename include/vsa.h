@@ -59,6 +59,12 @@ typedef enum {
                                     three launches with the score matrix in the workspace.  Bit-identical
                                     results; on this chip the three-launch form is the faster one at every
                                     size measured, so it is the default and this flag is for measuring */
+#define VSA_FLAG_OUT_TOKEN_MAJOR 16u /* vsa_forward: `out` is written token-major, bf16 [B,Np,H,d] = [B,Np,H*d]
+                                       in tiled token order: the layout the output projection consumes
+                                       ("b h l d -> b l (h d)", last line of the App. B listing) when
+                                       the activations stay tiled across the transformer (App. B caption),
+                                       so no relayout pass remains.  vsa_backward: `dout` is read in the
+                                       same layout.  All other tensors keep [B,H,Np,d]. */
 #define VSA_MAX_CUBES 4096        /* largest supported Nc                                 */
 #define VSA_STATIC_SCRATCH_MIB 40 /* size of the scratch buffer behind vsa_forward_static, MiB */
 
@@ -97,6 +103,7 @@ int vsa_tile_permute(const vsa_params_t* p, const void* src, void* dst, int inve
  *   gate_c       in   bf16 [B,H,Np,d] tiled (G_c)
  *   gate_f       in   bf16 [B,H,Np,d] tiled (G_f), or NULL = ones (Sec. 2.3)
  *   out          out  bf16 [B,H,Np,d] tiled: O_c[cube]*G_c + O_f*G_f, one rounding to bf16
+ *                     ([B,Np,H,d] with VSA_FLAG_OUT_TOKEN_MAJOR)
  *   block_idx    out  int32 [B,H,Nc,topk]: selected key cubes of each query cube, ascending
  *                     (the topk largest coarse logits, ties to the lower cube index);
  *                in   when flags has VSA_FLAG_INDICES_GIVEN (must be ascending, distinct,
@@ -137,7 +144,8 @@ size_t vsa_static_scratch_bytes(void);
  * gated sum, fine attention recomputed from lse_fine, coarse attention recomputed from
  * the pooled tensors, mean pooling).  No gradient flows through the top-K.
  *   q,k,v,gate_c,gate_f   as given to vsa_forward
- *   dout         in   bf16 [B,H,Np,d] tiled, gradient of the loss w.r.t. `out`
+ *   dout         in   bf16 [B,H,Np,d] tiled, gradient of the loss w.r.t. `out` ([B,Np,H,d] with
+ *                     VSA_FLAG_OUT_TOKEN_MAJOR)
  *   block_idx, out_fine, lse_fine, out_coarse, lse_coarse   as written by vsa_forward
  *   dq,dk,dv,dgate_c      out  bf16 [B,H,Np,d] tiled
  *   dgate_f      out  bf16 [B,H,Np,d], must be NULL iff gate_f is NULL */

@@ -21,7 +21,8 @@ __global__ __launch_bounds__(256) void k_bwd_pre(int Nc, const uint64_t* __restr
                                                  uint4* __restrict__ dgc, uint4* __restrict__ dgf,
                                                  uint4* __restrict__ dof, float* __restrict__ ld,
                                                  uint4* __restrict__ ldb, float inv_sl2, float* __restrict__ doc,
-                                                 const float* __restrict__ lse_f) {
+                                                 const float* __restrict__ lse_f, int H, long long do_head_stride,
+                                                 long long do_row_stride) {
   constexpr int CPR = D / 8, RG = 256 / CPR, RPT = kTile / RG;
   __shared__ float part[RG][D + 4];
   const int c = blockIdx.x % Nc;
@@ -29,6 +30,9 @@ __global__ __launch_bounds__(256) void k_bwd_pre(int Nc, const uint64_t* __restr
   const uint64_t m = mask[c];
   const int ch = threadIdx.x % CPR, rg = threadIdx.x / CPR;
   const long long row0 = (bh * Nc + c) * (long long)kTile;
+  // dout may be head-major [B,H,Np,D] or token-major [B,Np,H,D] (see the forward's `out`)
+  const long long do0 = (bh / H) * ((long long)H * Nc * kTile * CPR) + (bh % H) * do_head_stride +
+                        (long long)c * kTile * do_row_stride;
   float ocv[8];
   {
     const float* p = oc + (bh * Nc + c) * D + ch * 8;
@@ -45,7 +49,7 @@ __global__ __launch_bounds__(256) void k_bwd_pre(int Nc, const uint64_t* __restr
     float dsum = 0.f;
     if (valid) {
       float go[8], gcv[8], gfv[8], ofv[8], t0[8], t1[8], t2[8];
-      unpack8(dout[g], go);
+      unpack8(dout[do0 + r * do_row_stride + ch], go);
       unpack8(gc[g], gcv);
       unpack8(of[g], ofv);
       if (gf) unpack8(gf[g], gfv);
@@ -94,18 +98,20 @@ __global__ __launch_bounds__(256) void k_bwd_pre(int Nc, const uint64_t* __restr
 
 hipError_t launch_bwd_pre(int BH, int Nc, int d, const uint64_t* mask, const void* dout, const void* gate_c,
                           const void* gate_f, const void* out_fine, const float* oc, void* dgate_c, void* dgate_f,
-                          void* dof, float* ld, void* ldb, float scale, float* doc, const float* lse_f,
-                          hipStream_t s) {
+                          void* dof, float* ld, void* ldb, float scale, float* doc, const float* lse_f, int H,
+                          int dout_token_major, hipStream_t s) {
   const unsigned grid = (unsigned)(BH * Nc);
   const float inv_sl2 = 1.0f / (scale * kLog2e);
+  const long long cpr = d / 8, Np = (long long)Nc * kTile;
+  const long long dhs = dout_token_major ? cpr : Np * cpr, drs = dout_token_major ? H * cpr : cpr;
   if (d == 128)
     k_bwd_pre<128><<<grid, 256, 0, s>>>(Nc, mask, (const uint4*)dout, (const uint4*)gate_c, (const uint4*)gate_f,
                                         (const uint4*)out_fine, oc, (uint4*)dgate_c, (uint4*)dgate_f, (uint4*)dof, ld,
-                                        (uint4*)ldb, inv_sl2, doc, lse_f);
+                                        (uint4*)ldb, inv_sl2, doc, lse_f, H, dhs, drs);
   else
     k_bwd_pre<64><<<grid, 256, 0, s>>>(Nc, mask, (const uint4*)dout, (const uint4*)gate_c, (const uint4*)gate_f,
                                        (const uint4*)out_fine, oc, (uint4*)dgate_c, (uint4*)dgate_f, (uint4*)dof, ld,
-                                       (uint4*)ldb, inv_sl2, doc, lse_f);
+                                       (uint4*)ldb, inv_sl2, doc, lse_f, H, dhs, drs);
   return hipGetLastError();
 }
 

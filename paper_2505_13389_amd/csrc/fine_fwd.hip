@@ -36,7 +36,8 @@ __global__ __launch_bounds__(256, 2) void k_fine_fwd(int Nc, int K, float sl2, c
                                                      const uint4* __restrict__ gc, const uint4* __restrict__ gf,
                                                      const int32_t* __restrict__ idx, const float* __restrict__ oc,
                                                      const uint64_t* __restrict__ mask, uint4* __restrict__ out,
-                                                     uint4* __restrict__ out_fine, float* __restrict__ lse_f) {
+                                                     uint4* __restrict__ out_fine, float* __restrict__ lse_f,
+                                                     int H, long long out_head_stride, long long out_row_stride) {
   using TL = Tile<D>;
   constexpr int CPR = TL::CPR, KS = D / 16, DVB = D / 32, LPT = TL::LPT;
   constexpr int OS = D;  // fp32 row stride of the merge buffer
@@ -237,6 +238,9 @@ __global__ __launch_bounds__(256, 2) void k_fine_fwd(int Nc, int K, float sl2, c
   }
   __syncthreads();
 
+  // `out` may be head-major [B,H,Np,D] or token-major [B,Np,H,D] (same batch stride): chunk ch of
+  // tiled row n of head h of batch b sits at b*H*Np*CPR + h*out_head_stride + n*out_row_stride + ch
+  const long long out0 = (bh / H) * ((long long)H * Nc * kTile * CPR) + (bh % H) * out_head_stride;
   // ---- merge the two key halves, normalise, gate, store
   // The gates and the coarse output of this thread's items are requested first: they arrive while
   // the partial results go through LDS.  Pad rows are loaded too (they exist in memory) and ignored.
@@ -303,7 +307,7 @@ __global__ __launch_bounds__(256, 2) void k_fine_fwd(int Nc, int K, float sl2, c
       ov = pack8(res);
       fv = pack8(of);
     }
-    out[g] = ov;
+    out[out0 + (long long)(c * kTile + r) * out_row_stride + ch] = ov;
     if (out_fine) out_fine[g] = fv;
   }
   if (lse_f && tid < kTile) {
@@ -318,17 +322,20 @@ __global__ __launch_bounds__(256, 2) void k_fine_fwd(int Nc, int K, float sl2, c
 
 hipError_t launch_fine_fwd(int BH, int Nc, int d, int K, float scale, const void* q, const void* k, const void* v,
                            const void* gate_c, const void* gate_f, const int32_t* idx, const float* oc,
-                           const uint64_t* mask, void* out, void* out_fine, float* lse_f, hipStream_t s) {
+                           const uint64_t* mask, void* out, void* out_fine, float* lse_f, int H, int out_token_major,
+                           hipStream_t s) {
   const float sl2 = scale * kLog2e;
   const unsigned grid = (unsigned)(BH * Nc);
+  const long long cpr = d / 8, Np = (long long)Nc * kTile;
+  const long long ohs = out_token_major ? cpr : Np * cpr, ors = out_token_major ? H * cpr : cpr;
   if (d == 128)
     k_fine_fwd<128><<<grid, 256, 0, s>>>(Nc, K, sl2, (const uint4*)q, (const uint4*)k, (const uint4*)v,
                                          (const uint4*)gate_c, (const uint4*)gate_f, idx, oc, mask, (uint4*)out,
-                                         (uint4*)out_fine, lse_f);
+                                         (uint4*)out_fine, lse_f, H, ohs, ors);
   else
     k_fine_fwd<64><<<grid, 256, 0, s>>>(Nc, K, sl2, (const uint4*)q, (const uint4*)k, (const uint4*)v,
                                         (const uint4*)gate_c, (const uint4*)gate_f, idx, oc, mask, (uint4*)out,
-                                        (uint4*)out_fine, lse_f);
+                                        (uint4*)out_fine, lse_f, H, ohs, ors);
   return hipGetLastError();
 }
 

@@ -197,7 +197,7 @@ int enqueue_forward(const vsa_params_t* p, const Geo& g, const void* q, const vo
   VSA_TRY("pool", vsa::launch_pool(g, BH, p->d, w.mask, q, k, v, w.qc, w.kc, w.vc, s));
   VSA_TRY("coarse", vsa::launch_coarse(BH, g.Nc, p->d, p->topk, scale, w.qc, w.kc, w.vc, w.sc, oc, lse_c, idx, given ? 0 : 1, (p->flags & VSA_FLAG_COARSE_FUSED) ? 1 : 0, s));
   VSA_TRY("fine_fwd", vsa::launch_fine_fwd(BH, g.Nc, p->d, p->topk, scale, q, k, v, gate_c, gate_f, idx, oc, w.mask, out, out_fine,
-                               lse_fine, s));
+                               lse_fine, p->H, (p->flags & VSA_FLAG_OUT_TOKEN_MAJOR) ? 1 : 0, s));
   return VSA_OK;
 }
 
@@ -307,7 +307,7 @@ int vsa_backward(const vsa_params_t* p, const void* q, const void* k, const void
     VSA_TRY("pool", vsa::launch_pool(g, BH, p->d, w.mask, q, k, v, w.qc, w.kc, w.vc, s));
   }
   VSA_TRY("bwd_pre", vsa::launch_bwd_pre(BH, g.Nc, p->d, w.mask, dout, gate_c, gate_f, out_fine, out_coarse, dgate_c, dgate_f,
-                              w.dof, w.ld, w.ldb, scale, w.doc, lse_fine, s));
+                              w.dof, w.ld, w.ldb, scale, w.doc, lse_fine, p->H, (p->flags & VSA_FLAG_OUT_TOKEN_MAJOR) ? 1 : 0, s));
   VSA_TRY("coarse_bwd", vsa::launch_coarse_bwd(BH, g.Nc, p->d, scale, w.qc, w.kc, w.vc, lse_coarse, w.doc, w.ac, w.dsc, w.dqc, w.dkc,
                                  w.dvc, s));
   VSA_TRY("transpose_map", vsa::launch_transpose_map(BH, g.Nc, p->topk, block_idx, w.bits, w.row_ptr, w.col, w.order, w.split, w.seg, w.cap, s));

@@ -14,12 +14,14 @@ hipError_t launch_coarse(int BH, int Nc, int d, int K, float scale, const float*
                          float* sc, float* oc, float* lse_c, int32_t* idx, int emit_idx, int fused, hipStream_t s);
 hipError_t launch_fine_fwd(int BH, int Nc, int d, int K, float scale, const void* q, const void* k, const void* v,
                            const void* gate_c, const void* gate_f, const int32_t* idx, const float* oc,
-                           const uint64_t* mask, void* out, void* out_fine, float* lse_f, hipStream_t s);
+                           const uint64_t* mask, void* out, void* out_fine, float* lse_f, int H, int out_token_major,
+                           hipStream_t s);
 
 // backward
 hipError_t launch_bwd_pre(int BH, int Nc, int d, const uint64_t* mask, const void* dout, const void* gate_c,
                           const void* gate_f, const void* out_fine, const float* oc, void* dgate_c, void* dgate_f,
-                          void* dof, float* ld, void* ldb, float scale, float* doc, const float* lse_f, hipStream_t s);
+                          void* dof, float* ld, void* ldb, float scale, float* doc, const float* lse_f, int H,
+                          int dout_token_major, hipStream_t s);
 hipError_t launch_coarse_bwd(int BH, int Nc, int d, float scale, const float* qc, const float* kc, const float* vc,
                              const float* lse_c, const float* doc, float* ac, float* dsc, float* dqc, float* dkc,
                              float* dvc,

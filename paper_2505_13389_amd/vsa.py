@@ -17,6 +17,7 @@ VSA_FLAG_INDICES_GIVEN = 1
 VSA_FLAG_RASTER_BLHD = 2
 VSA_FLAG_WORKSPACE_KEPT = 4
 VSA_FLAG_COARSE_FUSED = 8
+VSA_FLAG_OUT_TOKEN_MAJOR = 16
 STATUS = {0: "VSA_OK", -1: "VSA_ERR_NULL", -2: "VSA_ERR_BAD_ARG", -3: "VSA_ERR_UNSUPPORTED", -4: "VSA_ERR_ALIGN",
           -5: "VSA_ERR_WORKSPACE", -6: "VSA_ERR_HIP", -7: "VSA_ERR_SCRATCH_LIMIT"}
 EXPORTS = ["vsa_padded_tokens", "vsa_workspace_bytes", "vsa_tile_permute", "vsa_forward", "vsa_backward",

@@ -308,6 +308,41 @@ def test_backward_is_deterministic(vsa):
         assert torch.equal(getattr(runs[0], name), getattr(runs[1], name)), name
 
 
+# ------------------------------------------------------------------------------ token-major output
+@pytest.mark.parametrize("name", ["pad128", "tiny", "planted_pad128"])
+def test_token_major_out_and_dout(vsa, name):
+    """VSA_FLAG_OUT_TOKEN_MAJOR: the forward stores `out` as [B,Np,H,d] (what the output projection
+    reads when the tiled order is kept across the transformer, App. B), the backward reads `dout` in
+    that layout.  Checked against the oracle and, bit for bit, against the head-major run."""
+    import dataclasses
+    import torch
+    wl = SMALL[name]
+    bits = tiled_bits(wl, seed=14, pad_garbage=True)
+    x = widen(bits)
+    g = grid_of(wl)
+    fwd = run_oracle_fwd(wl, x)
+    ref = orc.backward(g, x["q"], x["k"], x["v"], x["gate_c"], x["gate_f"], x["dout"], fwd["block_idx"], wl.topk,
+                       real="f32")
+    dev = to_dev(bits)
+    a = (dev["q"], dev["k"], dev["v"], dev["gate_c"], dev["gate_f"])
+    plain = run_gpu_fwd(vsa, wl, dev, block_idx=fwd["block_idx"], backward=True)
+    plain.backward(*a, dev["dout"])
+    pb = dataclasses.replace(problem_of(wl), flags=vsa.VSA_FLAG_OUT_TOKEN_MAJOR)
+    tm = vsa.Buffers(pb, backward=True)
+    tm.block_idx.copy_(torch.from_numpy(fwd["block_idx"]))
+    tm.out.fill_(float("nan"))
+    tm.forward(*a, indices_given=True)
+    dout_tm = dev["dout"].permute(0, 2, 1, 3).contiguous()  # [B,Np,H,d]
+    tm.backward(*a, dout_tm)
+    torch.cuda.synchronize()
+    out_tm = tm.out.view(wl.B, tm.Np, wl.H, wl.d)  # the same memory read as [B,Np,H,d]
+    assert_close(bf16_to_np(out_tm.permute(0, 2, 1, 3).contiguous()), fwd["out"], "out (token-major)")
+    assert torch.equal(out_tm.permute(0, 2, 1, 3).contiguous().view(torch.int16), plain.out.view(torch.int16))
+    for n in ("dq", "dk", "dv", "dgate_c", "dgate_f"):
+        assert_close(bf16_to_np(getattr(tm, n)), ref[n], n)
+        assert torch.equal(getattr(tm, n).view(torch.int16), getattr(plain, n).view(torch.int16)), n
+
+
 # ------------------------------------------------------------------------------ error paths
 def test_error_paths_return_status_and_launch_nothing(vsa):
     import torch
