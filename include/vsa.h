@@ -2,7 +2,8 @@
  * vsa.h -- C ABI of the MI355X (gfx950) Video Sparse Attention library, libvsa.so.
  *
  * Video Sparse Attention (arxiv 2505.13389, Sec. 2.2) replaces dense 3D attention of a
- * video diffusion transformer by two stages over (Ct,Ch,Cw) = (4,4,4) token cubes: a
+ * video diffusion transformer by two stages over (Ct,Ch,Cw) token cubes ((4,4,4) in the paper's
+ * main configuration; Sec. 3.2 ablates larger ones): a
  * coarse stage (mean-pooled cube-level attention that also picks, per query cube, the
  * top-K key cubes) and a fine stage (token-level block-sparse attention over the picked
  * cubes); the output is the gated sum O = O_c * G_c + O_f * G_f.
@@ -15,7 +16,9 @@
  *     default stream) and return.  Scratch comes from `workspace` (>= vsa_workspace_bytes).
  *   - "raster" order: token (t,h,w) of the valid T x Hh x W grid at n = t*Hh*W + h*W + w
  *     (Sec. 2.1).  "tiled" order: the index equation of Sec. 2.2 on the grid padded up to
- *     cube multiples, Np tokens = Nc cubes x 64; each cube is 64 consecutive rows.
+ *     cube multiples, Np tokens = Nc cubes x V (V = Ct*Ch*Cw = 64, 128 or 256); each cube is V
+ *     consecutive rows.  The attention tile equals the cube: a query cube attends to the whole
+ *     of each selected key cube.
  *   - Pad slots (tiled rows outside the valid grid) are defined by geometry alone.  They
  *     are never keys, are excluded from pooled means, and their rows of every output and
  *     gradient are written as zero; whatever finite values the caller stores there in an
@@ -41,7 +44,7 @@ typedef enum {
   VSA_OK = 0,
   VSA_ERR_NULL = -1,        /* a required pointer is NULL                              */
   VSA_ERR_BAD_ARG = -2,     /* non-positive dimension, topk outside 1..Nc              */
-  VSA_ERR_UNSUPPORTED = -3, /* cube volume != 64, d not in {64,128}, Nc above the limit */
+  VSA_ERR_UNSUPPORTED = -3, /* cube volume not 64/128/256, d not in {64,128}, too many cubes */
   VSA_ERR_ALIGN = -4,       /* a device pointer is not 16-byte aligned                 */
   VSA_ERR_WORKSPACE = -5,   /* workspace NULL or smaller than vsa_workspace_bytes      */
   VSA_ERR_HIP = -6,         /* a kernel launch was rejected by the runtime             */
@@ -65,13 +68,13 @@ typedef enum {
                                        the activations stay tiled across the transformer (App. B caption),
                                        so no relayout pass remains.  vsa_backward: `dout` is read in the
                                        same layout.  All other tensors keep [B,H,Np,d]. */
-#define VSA_MAX_CUBES 4096        /* largest supported Nc                                 */
+#define VSA_MAX_CUBES 4096        /* largest supported Np / 64 (= Nc for 64-token cubes)  */
 #define VSA_STATIC_SCRATCH_MIB 40 /* size of the scratch buffer behind vsa_forward_static, MiB */
 
 typedef struct {
   int32_t B, H;        /* batch, heads                                                   */
   int32_t T, Hh, W;    /* valid latent grid in tokens                                    */
-  int32_t Ct, Ch, Cw;  /* cube shape; Ct*Ch*Cw must be 64 (Sec. 2.2: (4,4,4))            */
+  int32_t Ct, Ch, Cw;  /* cube shape; Ct*Ch*Cw must be 64 (Sec. 2.2: (4,4,4)), 128 or 256  */
   int32_t d;           /* head dimension: 64 or 128                                      */
   int32_t topk;        /* key cubes per query cube, 1..Nc; Nc = the dense path           */
   float softmax_scale; /* <= 0 selects 1/sqrt(d) (Sec. 2.1)                              */
@@ -79,7 +82,7 @@ typedef struct {
 } vsa_params_t;
 
 /* Padded token count Np and cube count Nc of the grid in `p` (Sec. 2.2: (Nt,Nh,Nw) =
- * ceil(T/Ct), ceil(Hh/Ch), ceil(W/Cw); Np = 64*Nc).  Host-only. */
+ * ceil(T/Ct), ceil(Hh/Ch), ceil(W/Cw); Np = Ct*Ch*Cw*Nc).  Host-only. */
 int vsa_padded_tokens(const vsa_params_t* p, int64_t* Np, int32_t* Nc);
 
 /* Bytes of scratch vsa_forward (backward == 0) or vsa_backward (backward != 0) needs.

@@ -13,9 +13,10 @@ namespace vsa {
 //   Delta_i = sum_d dOf_i * Of_i                       dOc[c] = sum_i dO_i * Gc_i
 //   ld_i = (lse_i * log2(e), Delta_i) as one pair per row, lse = +inf on pad rows (makes P = 0
 //          there in the fine backward kernels)
-// One workgroup per (b*h, cube); thread layout as in the pooling kernel.
+// One workgroup per (b*h, cube), which walks the cube's m blocks of 64 rows; thread layout as in the
+// pooling kernel.
 template <int D>
-__global__ __launch_bounds__(256) void k_bwd_pre(int Nc, const uint64_t* __restrict__ mask, const uint4* __restrict__ dout,
+__global__ __launch_bounds__(256) void k_bwd_pre(int Nc, int m_blocks, const uint64_t* __restrict__ mask, const uint4* __restrict__ dout,
                                                  const uint4* __restrict__ gc, const uint4* __restrict__ gf,
                                                  const uint4* __restrict__ of, const float* __restrict__ oc,
                                                  uint4* __restrict__ dgc, uint4* __restrict__ dgf,
@@ -27,12 +28,7 @@ __global__ __launch_bounds__(256) void k_bwd_pre(int Nc, const uint64_t* __restr
   __shared__ float part[RG][D + 4];
   const int c = blockIdx.x % Nc;
   const long long bh = blockIdx.x / Nc;
-  const uint64_t m = mask[c];
   const int ch = threadIdx.x % CPR, rg = threadIdx.x / CPR;
-  const long long row0 = (bh * Nc + c) * (long long)kTile;
-  // dout may be head-major [B,H,Np,D] or token-major [B,Np,H,D] (see the forward's `out`)
-  const long long do0 = (bh / H) * ((long long)H * Nc * kTile * CPR) + (bh % H) * do_head_stride +
-                        (long long)c * kTile * do_row_stride;
   float ocv[8];
   {
     const float* p = oc + (bh * Nc + c) * D + ch * 8;
@@ -40,6 +36,14 @@ __global__ __launch_bounds__(256) void k_bwd_pre(int Nc, const uint64_t* __restr
     ocv[0] = a.x; ocv[1] = a.y; ocv[2] = a.z; ocv[3] = a.w; ocv[4] = b.x; ocv[5] = b.y; ocv[6] = b.z; ocv[7] = b.w;
   }
   float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  for (int sb = 0; sb < m_blocks; ++sb) {
+  const long long blk = (bh * Nc + c) * m_blocks + sb;  // block index over all (b, h)
+  const uint64_t m = mask[c * m_blocks + sb];
+  const long long row0 = blk * (long long)kTile;
+  // dout may be head-major [B,H,Np,D] or token-major [B,Np,H,D] (see the forward's `out`)
+  const long long Npad = (long long)Nc * m_blocks * kTile;
+  const long long do0 = (bh / H) * ((long long)H * Npad * CPR) + (bh % H) * do_head_stride +
+                        ((long long)c * m_blocks + sb) * kTile * do_row_stride;
 #pragma unroll
   for (int i = 0; i < RPT; ++i) {
     const int r = rg + i * RG;
@@ -86,6 +90,7 @@ __global__ __launch_bounds__(256) void k_bwd_pre(int Nc, const uint64_t* __restr
       ldb[row0 + r] = make_uint4(a.x, a.y, b.x, b.y);
     }
   }
+  }
 #pragma unroll
   for (int e = 0; e < 8; ++e) part[rg][ch * 8 + e] = acc[e];
   __syncthreads();
@@ -96,20 +101,20 @@ __global__ __launch_bounds__(256) void k_bwd_pre(int Nc, const uint64_t* __restr
   }
 }
 
-hipError_t launch_bwd_pre(int BH, int Nc, int d, const uint64_t* mask, const void* dout, const void* gate_c,
+hipError_t launch_bwd_pre(int BH, int Nc, int m_blocks, int d, const uint64_t* mask, const void* dout, const void* gate_c,
                           const void* gate_f, const void* out_fine, const float* oc, void* dgate_c, void* dgate_f,
                           void* dof, float* ld, void* ldb, float scale, float* doc, const float* lse_f, int H,
                           int dout_token_major, hipStream_t s) {
   const unsigned grid = (unsigned)(BH * Nc);
   const float inv_sl2 = 1.0f / (scale * kLog2e);
-  const long long cpr = d / 8, Np = (long long)Nc * kTile;
+  const long long cpr = d / 8, Np = (long long)Nc * m_blocks * kTile;
   const long long dhs = dout_token_major ? cpr : Np * cpr, drs = dout_token_major ? H * cpr : cpr;
   if (d == 128)
-    k_bwd_pre<128><<<grid, 256, 0, s>>>(Nc, mask, (const uint4*)dout, (const uint4*)gate_c, (const uint4*)gate_f,
+    k_bwd_pre<128><<<grid, 256, 0, s>>>(Nc, m_blocks, mask, (const uint4*)dout, (const uint4*)gate_c, (const uint4*)gate_f,
                                         (const uint4*)out_fine, oc, (uint4*)dgate_c, (uint4*)dgate_f, (uint4*)dof, ld,
                                         (uint4*)ldb, inv_sl2, doc, lse_f, H, dhs, drs);
   else
-    k_bwd_pre<64><<<grid, 256, 0, s>>>(Nc, mask, (const uint4*)dout, (const uint4*)gate_c, (const uint4*)gate_f,
+    k_bwd_pre<64><<<grid, 256, 0, s>>>(Nc, m_blocks, mask, (const uint4*)dout, (const uint4*)gate_c, (const uint4*)gate_f,
                                        (const uint4*)out_fine, oc, (uint4*)dgate_c, (uint4*)dgate_f, (uint4*)dof, ld,
                                        (uint4*)ldb, inv_sl2, doc, lse_f, H, dhs, drs);
   return hipGetLastError();

@@ -10,6 +10,7 @@
 //                                 probabilities written back over S
 //   Oc = P Vc                     fp32 matrix-core GEMM
 #include "gemm32_tile.h"
+#include "list_rules.h"
 #include "vsa_kernels.h"
 
 namespace vsa {
@@ -195,6 +196,23 @@ __global__ __launch_bounds__(1024) void k_coarse_fused(int Nc, int K, float scal
 
 hipError_t gemm32(int batch, int M, int N, int Kd, float alpha, const float* a, long long sab, int sam, int sak,
                   const float* b, long long sbb, int sbk, int sbn, float* c, long long scb, hipStream_t s);
+
+// Cubes of m > 1 blocks (Sec. 3.2's larger tiles): the fine kernels work on 64-row blocks, so the
+// list of key cubes of query cube c becomes, for each of the cube's m blocks, the list of the m
+// blocks of every selected key cube (still ascending).  One thread per output entry.
+__global__ __launch_bounds__(256) void k_expand_lists(long long total, int K, int m, const int32_t* __restrict__ idx,
+                                                      int32_t* __restrict__ out) {
+  const long long e = (long long)blockIdx.x * 256 + threadIdx.x;  // ((row * m + s) * K + t) * m + u
+  if (e >= total) return;
+  const int u = (int)(e % m);
+  const long long t = (e / m) % K, row = e / ((long long)m * K * m);
+  out[e] = expanded_entry(idx[row * K + t], m, u);
+}
+hipError_t launch_expand_lists(int BH, int Nc, int K, int m, const int32_t* idx, int32_t* idx_blocks, hipStream_t s) {
+  const long long total = (long long)BH * Nc * m * K * m;
+  k_expand_lists<<<(unsigned)((total + 255) / 256), 256, 0, s>>>(total, K, m, idx, idx_blocks);
+  return hipGetLastError();
+}
 
 hipError_t launch_coarse(int BH, int Nc, int d, int K, float scale, const float* qc, const float* kc, const float* vc,
                          float* sc, float* oc, float* lse_c, int32_t* idx, int emit_idx, int fused, hipStream_t s) {

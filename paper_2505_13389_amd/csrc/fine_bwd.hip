@@ -26,7 +26,7 @@ __global__ __launch_bounds__(256, 2) void k_fine_bwd_dq(int Nc, int K, float sl2
                                                         const uint4* __restrict__ dof, const int32_t* __restrict__ idx,
                                                         const float* __restrict__ ld,
                                                         const float* __restrict__ dqc, const uint64_t* __restrict__ mask,
-                                                        uint4* __restrict__ dq) {
+                                                        uint4* __restrict__ dq, int m_blocks) {
   using TL = Tile<D>;
   constexpr int CPR = TL::CPR, KS = D / 16, DVB = D / 32, LPT = TL::LPT;
   constexpr int OS = D;
@@ -214,7 +214,7 @@ __global__ __launch_bounds__(256, 2) void k_fine_bwd_dq(int Nc, int K, float sl2
   // the pooled-gradient term of this thread's column chunk (the same chunk for all of its items),
   // requested before the partial results go through LDS
   static_assert(256 % CPR == 0, "a thread keeps its column chunk");
-  const float* dqcr = dqc + (bh * Nc + c) * D + (tid % CPR) * 8;
+  const float* dqcr = dqc + ((bh * Nc + c) / m_blocks) * D + (tid % CPR) * 8;  // per cube = m_blocks blocks
   const float4 pc0 = *(const float4*)dqcr, pc1 = *(const float4*)(dqcr + 4);
   __syncthreads();
 
@@ -230,7 +230,7 @@ __global__ __launch_bounds__(256, 2) void k_fine_bwd_dq(int Nc, int K, float sl2
   }
   __syncthreads();
 
-  const float inv_cnt = 1.0f / (float)__popcll(qmask);
+  const float inv_cnt = 1.0f / (float)cube_count(mask, c, m_blocks);
   const float pooled[8] = {pc0.x * inv_cnt, pc0.y * inv_cnt, pc0.z * inv_cnt, pc0.w * inv_cnt,
                            pc1.x * inv_cnt, pc1.y * inv_cnt, pc1.z * inv_cnt, pc1.w * inv_cnt};
 #pragma unroll
@@ -253,15 +253,15 @@ __global__ __launch_bounds__(256, 2) void k_fine_bwd_dq(int Nc, int K, float sl2
 
 hipError_t launch_fine_bwd_dq(int BH, int Nc, int d, int K, float scale, const void* q, const void* k, const void* v,
                               const void* dof, const int32_t* idx, const float* ld,
-                              const float* dqc, const uint64_t* mask, void* dq, hipStream_t s) {
+                              const float* dqc, const uint64_t* mask, void* dq, int m_blocks, hipStream_t s) {
   const float sl2 = scale * kLog2e;
   const unsigned grid = (unsigned)(BH * Nc);
   if (d == 128)
     k_fine_bwd_dq<128><<<grid, 256, 0, s>>>(Nc, K, sl2, scale, (const uint4*)q, (const uint4*)k, (const uint4*)v,
-                                            (const uint4*)dof, idx, ld, dqc, mask, (uint4*)dq);
+                                            (const uint4*)dof, idx, ld, dqc, mask, (uint4*)dq, m_blocks);
   else
     k_fine_bwd_dq<64><<<grid, 256, 0, s>>>(Nc, K, sl2, scale, (const uint4*)q, (const uint4*)k, (const uint4*)v,
-                                           (const uint4*)dof, idx, ld, dqc, mask, (uint4*)dq);
+                                           (const uint4*)dof, idx, ld, dqc, mask, (uint4*)dq, m_blocks);
   return hipGetLastError();
 }
 
@@ -296,7 +296,7 @@ __global__ __launch_bounds__(256, 1) void k_fine_bwd_dkv(int Nc, int K, float sl
                                                          const uint4* __restrict__ ldb,
                                                          const float* __restrict__ dkc, const float* __restrict__ dvc,
                                                          const uint64_t* __restrict__ mask, uint4* __restrict__ dk,
-                                                         uint4* __restrict__ dv) {
+                                                         uint4* __restrict__ dv, int m_blocks) {
   using TL = Tile<D>;
   constexpr int CPR = TL::CPR, KS = D / 16, DVB = D / 32, LPT = TL::LPT;
   constexpr int OS = D;
@@ -561,15 +561,15 @@ __global__ __launch_bounds__(256, 1) void k_fine_bwd_dkv(int Nc, int K, float sl
   static_assert(256 % CPR == 0, "a thread keeps its column chunk");
   float4 pk[2], pv[2];
   {
-    const float* a = dkc + (bh * Nc + j) * D + (tid % CPR) * 8;
-    const float* b = dvc + (bh * Nc + j) * D + (tid % CPR) * 8;
+    const float* a = dkc + ((bh * Nc + j) / m_blocks) * D + (tid % CPR) * 8;  // per cube = m_blocks blocks
+    const float* b = dvc + ((bh * Nc + j) / m_blocks) * D + (tid % CPR) * 8;
     pk[0] = *(const float4*)a, pk[1] = *(const float4*)(a + 4);
     pv[0] = *(const float4*)b, pv[1] = *(const float4*)(b + 4);
   }
   __syncthreads();
 
   // merge the two query halves: all four partial results (dK, dV x two query halves) go through LDS at once
-  const float inv_cnt = 1.0f / (float)__popcll(kmask);
+  const float inv_cnt = 1.0f / (float)cube_count(mask, j, m_blocks);
   static_assert(4 * 64 * OS * 4 <= 4 * STAGE, "merge buffers must fit");
   float* parts_lds = (float*)smem;  // [dK half 0][dK half 1][dV half 0][dV half 1], each [64][OS]
 #pragma unroll
@@ -639,7 +639,7 @@ template <int D>
 __global__ __launch_bounds__(256) void k_dkv_reduce(int Nc, int cap, float scale, const int32_t* __restrict__ split,
                                                     const float* __restrict__ parts, const float* __restrict__ dkc,
                                                     const float* __restrict__ dvc, const uint64_t* __restrict__ mask,
-                                                    uint4* __restrict__ dk, uint4* __restrict__ dv) {
+                                                    uint4* __restrict__ dk, uint4* __restrict__ dv, int m_blocks) {
   constexpr int CPR = D / 8, LPT = kTile * CPR / 256;
   const int per = cap / 2, r_ = blockIdx.x % per, tid = threadIdx.x;
   const long long bh = blockIdx.x / per;
@@ -648,11 +648,11 @@ __global__ __launch_bounds__(256) void k_dkv_reduce(int Nc, int cap, float scale
   const int4 desc = sp[1 + r_];
   const int j = desc.x, slot0 = desc.y, runs = desc.z;
   const uint64_t kmask = mask[j];
-  const float inv_cnt = 1.0f / (float)__popcll(kmask);
+  const float inv_cnt = 1.0f / (float)cube_count(mask, j, m_blocks);
   const long long rows0 = bh * (long long)Nc * kTile;
 #pragma unroll
   for (int pass = 0; pass < 2; ++pass) {
-    const float* pooled_row = (pass == 0 ? dkc : dvc) + (bh * Nc + j) * D + (tid % CPR) * 8;
+    const float* pooled_row = (pass == 0 ? dkc : dvc) + ((bh * Nc + j) / m_blocks) * D + (tid % CPR) * 8;
     const float4 p0 = *(const float4*)pooled_row, p1 = *(const float4*)(pooled_row + 4);
     const float pooled[8] = {p0.x * inv_cnt, p0.y * inv_cnt, p0.z * inv_cnt, p0.w * inv_cnt,
                              p1.x * inv_cnt, p1.y * inv_cnt, p1.z * inv_cnt, p1.w * inv_cnt};
@@ -683,20 +683,20 @@ __global__ __launch_bounds__(256) void k_dkv_reduce(int Nc, int cap, float scale
 hipError_t launch_fine_bwd_dkv(int BH, int Nc, int d, int K, float scale, const void* q, const void* k, const void* v,
                                const void* dof, const int32_t* col, const int32_t* order, const int32_t* split,
                                float* parts, int cap, const void* ldb, const float* dkc, const float* dvc,
-                               const uint64_t* mask, void* dk, void* dv, hipStream_t s) {
+                               const uint64_t* mask, void* dk, void* dv, int m_blocks, hipStream_t s) {
   const float sl2 = scale * kLog2e;
   const int items = Nc + cap;
   const unsigned grid = (unsigned)(BH * items), rgrid = (unsigned)(BH * (cap / 2));
   if (d == 128) {
     k_fine_bwd_dkv<128><<<grid, 256, 0, s>>>(Nc, K, sl2, scale, (const uint4*)q, (const uint4*)k, (const uint4*)v,
                                              (const uint4*)dof, col, order, items, parts, cap, (const uint4*)ldb, dkc,
-                                             dvc, mask, (uint4*)dk, (uint4*)dv);
-    k_dkv_reduce<128><<<rgrid, 256, 0, s>>>(Nc, cap, scale, split, parts, dkc, dvc, mask, (uint4*)dk, (uint4*)dv);
+                                             dvc, mask, (uint4*)dk, (uint4*)dv, m_blocks);
+    k_dkv_reduce<128><<<rgrid, 256, 0, s>>>(Nc, cap, scale, split, parts, dkc, dvc, mask, (uint4*)dk, (uint4*)dv, m_blocks);
   } else {
     k_fine_bwd_dkv<64><<<grid, 256, 0, s>>>(Nc, K, sl2, scale, (const uint4*)q, (const uint4*)k, (const uint4*)v,
                                             (const uint4*)dof, col, order, items, parts, cap, (const uint4*)ldb, dkc,
-                                            dvc, mask, (uint4*)dk, (uint4*)dv);
-    k_dkv_reduce<64><<<rgrid, 256, 0, s>>>(Nc, cap, scale, split, parts, dkc, dvc, mask, (uint4*)dk, (uint4*)dv);
+                                            dvc, mask, (uint4*)dk, (uint4*)dv, m_blocks);
+    k_dkv_reduce<64><<<rgrid, 256, 0, s>>>(Nc, cap, scale, split, parts, dkc, dvc, mask, (uint4*)dk, (uint4*)dv, m_blocks);
   }
   return hipGetLastError();
 }

@@ -1,7 +1,9 @@
 // Fine stage forward (Sec. 2.2 fine stage; Sec. 2.1 attention equation under the block mask)
 // fused with the gated combine O = O_c * G_c + O_f * G_f.
 //
-// One workgroup (4 wavefronts) per (b, h, query cube).  The K selected key cubes are walked
+// One workgroup (4 wavefronts) per (b, h, 64-row query block); "cube" below means such a block (a
+// cube of 64*m tokens is m consecutive blocks, and the lists the kernel gets name blocks).  The K
+// selected key blocks are walked
 // through a double-buffered LDS stage (K tile + V tile).  Work split inside the workgroup:
 // wavefront (qh, kh) owns query rows qh*32..+31 and key rows kh*32..+31 of every key tile and
 // keeps its OWN online-softmax state (running max, running sum, unnormalised O); the two
@@ -37,7 +39,8 @@ __global__ __launch_bounds__(256, 2) void k_fine_fwd(int Nc, int K, float sl2, c
                                                      const int32_t* __restrict__ idx, const float* __restrict__ oc,
                                                      const uint64_t* __restrict__ mask, uint4* __restrict__ out,
                                                      uint4* __restrict__ out_fine, float* __restrict__ lse_f,
-                                                     int H, long long out_head_stride, long long out_row_stride) {
+                                                     int H, long long out_head_stride, long long out_row_stride,
+                                                     int m_blocks) {
   using TL = Tile<D>;
   constexpr int CPR = TL::CPR, KS = D / 16, DVB = D / 32, LPT = TL::LPT;
   constexpr int OS = D;  // fp32 row stride of the merge buffer
@@ -251,7 +254,7 @@ __global__ __launch_bounds__(256, 2) void k_fine_fwd(int Nc, int K, float sl2, c
   for (int it = 0; it < LPT; ++it) {
     const int item = it * 256 + tid, r = item / CPR, ch = item % CPR;
     const long long g = (rows0 + c * kTile + r) * CPR + ch;
-    const float* ocr = oc + (bh * Nc + c) * D + ch * 8;
+    const float* ocr = oc + ((bh * Nc + c) / m_blocks) * D + ch * 8;  // O_c is per cube = m_blocks blocks
     gc_raw[it] = gc[g];
     gf_raw[it] = gf ? gf[g] : make_uint4(0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u);  // bf16 ones
     oc_raw[it][0] = *(const float4*)ocr;
@@ -323,7 +326,7 @@ __global__ __launch_bounds__(256, 2) void k_fine_fwd(int Nc, int K, float sl2, c
 hipError_t launch_fine_fwd(int BH, int Nc, int d, int K, float scale, const void* q, const void* k, const void* v,
                            const void* gate_c, const void* gate_f, const int32_t* idx, const float* oc,
                            const uint64_t* mask, void* out, void* out_fine, float* lse_f, int H, int out_token_major,
-                           hipStream_t s) {
+                           int m_blocks, hipStream_t s) {
   const float sl2 = scale * kLog2e;
   const unsigned grid = (unsigned)(BH * Nc);
   const long long cpr = d / 8, Np = (long long)Nc * kTile;
@@ -331,11 +334,11 @@ hipError_t launch_fine_fwd(int BH, int Nc, int d, int K, float scale, const void
   if (d == 128)
     k_fine_fwd<128><<<grid, 256, 0, s>>>(Nc, K, sl2, (const uint4*)q, (const uint4*)k, (const uint4*)v,
                                          (const uint4*)gate_c, (const uint4*)gate_f, idx, oc, mask, (uint4*)out,
-                                         (uint4*)out_fine, lse_f, H, ohs, ors);
+                                         (uint4*)out_fine, lse_f, H, ohs, ors, m_blocks);
   else
     k_fine_fwd<64><<<grid, 256, 0, s>>>(Nc, K, sl2, (const uint4*)q, (const uint4*)k, (const uint4*)v,
                                         (const uint4*)gate_c, (const uint4*)gate_f, idx, oc, mask, (uint4*)out,
-                                        (uint4*)out_fine, lse_f, H, ohs, ors);
+                                        (uint4*)out_fine, lse_f, H, ohs, ors, m_blocks);
   return hipGetLastError();
 }
 

@@ -19,6 +19,11 @@ namespace vsa {
 // Forward and dQ pass: the cube whose K/V tile is fetched for list entry `raw`.
 VSA_RULE int clamp_cube(int raw, int ncubes) { return raw < 0 ? 0 : (raw > ncubes - 1 ? ncubes - 1 : raw); }
 
+// Cubes of m blocks: entry u (0 <= u < m) of the block-level list that key cube `raw` expands to.
+// Unsigned arithmetic, so that a hostile `raw` wraps around instead of overflowing; whatever comes
+// out is clamped or skipped like any other entry.
+VSA_RULE int expanded_entry(int raw, int m, int u) { return (int)((unsigned)raw * (unsigned)m + (unsigned)u); }
+
 // Slot of the list read by lane `lane` for 64-entry chunk `chunk` of a list of n entries.
 VSA_RULE int list_slot(int chunk, int lane, int n) {
   const int e = (chunk << 6) + lane;

@@ -20,7 +20,7 @@ __global__ __launch_bounds__(256) void k_tile_permute(Geo g, int BH, int H, int 
   int n = (int)(row % rows_dst);
   long long bh = row / rows_dst;
   if (!kInverse) {
-    int c = n / kTile, in = n % kTile;
+    int c = n / g.V, in = n % g.V;
     int cw = c % g.Nw, chh = (c / g.Nw) % g.Nh, ct = c / (g.Nw * g.Nh);
     int pw = in % g.Cw, ph = (in / g.Cw) % g.Ch, pt = in / (g.Cw * g.Ch);
     int t = ct * g.Ct + pt, h = chh * g.Ch + ph, w = cw * g.Cw + pw;
@@ -36,7 +36,7 @@ __global__ __launch_bounds__(256) void k_tile_permute(Geo g, int BH, int H, int 
     long long c = ((long long)(t / g.Ct) * g.Nh + (h / g.Ch)) * g.Nw + (w / g.Cw);
     int in = ((t % g.Ct) * g.Ch + (h % g.Ch)) * g.Cw + (w % g.Cw);
     const long long rr = H > 0 ? ((bh / H) * g.L + n) * H + bh % H : bh * g.L + n;
-    dst[rr * chunks_per_row + ch] = src[(bh * g.Np + c * kTile + in) * chunks_per_row + ch];
+    dst[rr * chunks_per_row + ch] = src[(bh * g.Np + c * g.V + in) * chunks_per_row + ch];
   }
 }
 
@@ -53,11 +53,12 @@ hipError_t launch_tile_permute(const Geo& g, int BH, int H_blhd, int d, const vo
 }
 
 // Mean over the valid tokens of each cube (Sec. 2.2 coarse stage), fp32 result.
-// One workgroup per (tensor, b*h, cube): 64 rows x D bf16 in, D floats out.  Thread t owns
-// 16-byte chunk t % (D/8) of rows t / (D/8), t / (D/8) + 256/(D/8), ...; the partial sums
-// are added across row groups in a fixed order, so the result is deterministic.
-// The cube's validity mask comes from the geometry (one ballot per wavefront) and is also written
-// to mask[c] for the kernels that follow (by the workgroups of the first (b, h) and tensor).
+// One workgroup per (tensor, b*h, cube): V rows x D bf16 in (m blocks of 64 rows), D floats out.
+// Thread t owns 16-byte chunk t % (D/8) of rows t / (D/8), t / (D/8) + 256/(D/8), ... of every
+// block; the partial sums are added across row groups in a fixed order, so the result is
+// deterministic.  The validity mask of each block comes from the geometry (one ballot per
+// wavefront) and is also written to mask[block] for the kernels that follow (by the workgroups of
+// the first (b, h) and tensor).
 template <int D>
 __global__ __launch_bounds__(256) void k_pool(Geo g, long long Np, uint64_t* __restrict__ mask,
                                               const uint4* __restrict__ q, const uint4* __restrict__ k,
@@ -65,27 +66,31 @@ __global__ __launch_bounds__(256) void k_pool(Geo g, long long Np, uint64_t* __r
                                               float* __restrict__ kc, float* __restrict__ vc) {
   constexpr int CPR = D / 8;        // chunks per row
   constexpr int RG = 256 / CPR;     // row groups
-  constexpr int RPT = kTile / RG;   // rows per thread
+  constexpr int RPT = kTile / RG;   // rows per thread and block
   __shared__ float part[RG][D + 4];
   const int Nc = g.Nc;
   const int c = blockIdx.x % Nc;
   const long long bh = blockIdx.x / Nc;
   const uint4* src = blockIdx.y == 0 ? q : (blockIdx.y == 1 ? k : v);
   float* dst = blockIdx.y == 0 ? qc : (blockIdx.y == 1 ? kc : vc);
-  const uint64_t m = cube_valid_mask_wave(g, c, threadIdx.x & 63);
-  if (blockIdx.x < Nc && blockIdx.y == 0 && threadIdx.x == 0) mask[c] = m;
   const int ch = threadIdx.x % CPR, rg = threadIdx.x / CPR;
   float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-  const uint4* base = src + (bh * Np + (long long)c * kTile) * CPR;
+  int cnt = 0;
+  for (int sb = 0; sb < g.m; ++sb) {
+    const uint64_t m = block_valid_mask_wave(g, c * g.m + sb, threadIdx.x & 63);
+    if (blockIdx.x < Nc && blockIdx.y == 0 && threadIdx.x == 0) mask[c * g.m + sb] = m;
+    cnt += __popcll(m);
+    const uint4* base = src + (bh * Np + ((long long)c * g.m + sb) * kTile) * CPR;
 #pragma unroll
-  for (int i = 0; i < RPT; ++i) {
-    int r = rg + i * RG;
-    uint4 u = base[r * CPR + ch];
-    if ((m >> r) & 1) {
-      float f[8];
-      unpack8(u, f);
+    for (int i = 0; i < RPT; ++i) {
+      int r = rg + i * RG;
+      uint4 u = base[r * CPR + ch];
+      if ((m >> r) & 1) {
+        float f[8];
+        unpack8(u, f);
 #pragma unroll
-      for (int e = 0; e < 8; ++e) acc[e] += f[e];
+        for (int e = 0; e < 8; ++e) acc[e] += f[e];
+      }
     }
   }
 #pragma unroll
@@ -94,7 +99,7 @@ __global__ __launch_bounds__(256) void k_pool(Geo g, long long Np, uint64_t* __r
   if (threadIdx.x < D) {
     float s = 0;
     for (int r = 0; r < RG; ++r) s += part[r][threadIdx.x];
-    dst[(bh * Nc + c) * D + threadIdx.x] = s / (float)__popcll(m);
+    dst[(bh * Nc + c) * D + threadIdx.x] = s / (float)cnt;
   }
 }
 

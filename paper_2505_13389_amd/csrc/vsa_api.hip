@@ -24,7 +24,8 @@ int check_params(const vsa_params_t* p, Geo* g) {
   if (!p) return VSA_ERR_NULL;
   if (p->B < 1 || p->H < 1 || p->T < 1 || p->Hh < 1 || p->W < 1 || p->Ct < 1 || p->Ch < 1 || p->Cw < 1 || p->d < 1)
     return VSA_ERR_BAD_ARG;
-  if ((long long)p->Ct * p->Ch * p->Cw != vsa::kTile) return VSA_ERR_UNSUPPORTED;
+  const long long vol = (long long)p->Ct * p->Ch * p->Cw;
+  if (vol != 64 && vol != 128 && vol != 256) return VSA_ERR_UNSUPPORTED;
   if (p->d != 64 && p->d != 128) return VSA_ERR_UNSUPPORTED;
   g->T = p->T; g->Hh = p->Hh; g->W = p->W;
   g->Ct = p->Ct; g->Ch = p->Ch; g->Cw = p->Cw;
@@ -32,12 +33,16 @@ int check_params(const vsa_params_t* p, Geo* g) {
   g->Nh = (p->Hh + p->Ch - 1) / p->Ch;
   g->Nw = (p->W + p->Cw - 1) / p->Cw;
   long long nc = (long long)g->Nt * g->Nh * g->Nw;
-  if (nc > VSA_MAX_CUBES) return VSA_ERR_UNSUPPORTED;
+  g->V = (int)vol;
+  g->m = (int)(vol / vsa::kTile);
+  if (nc * g->m > VSA_MAX_CUBES) return VSA_ERR_UNSUPPORTED;
   long long L = (long long)p->T * p->Hh * p->W;
   g->Nc = (int)nc;
+  g->Nb = (int)(nc * g->m);
   g->L = (int)L;
-  g->Np = nc * vsa::kTile;
-  if ((long long)p->B * p->H * nc > 0x7fffffffLL / 4) return VSA_ERR_UNSUPPORTED;  // grid sizes stay in 32 bits
+  g->Np = nc * vol;
+  if ((long long)p->B * p->H * g->Nb > 0x7fffffffLL / 4) return VSA_ERR_UNSUPPORTED;  // grid sizes stay in 32 bits
+  if ((long long)p->B * p->H * g->Nb * p->topk * g->m > 0x7fffffffLL / 2) return VSA_ERR_UNSUPPORTED;
   return VSA_OK;
 }
 
@@ -65,14 +70,14 @@ struct Carver {
 struct FwdWs {
   uint64_t* mask;
   float *qc, *kc, *vc, *oc, *lse_c, *sc;
-  int32_t* idx;
+  int32_t *idx, *idx_blocks;
   size_t bytes;
 };
 FwdWs carve_fwd(const vsa_params_t* p, const Geo& g, void* ws) {
   Carver c(ws);
   size_t bh = (size_t)p->B * p->H;
   FwdWs w;
-  w.mask = c.take<uint64_t>(g.Nc);
+  w.mask = c.take<uint64_t>(g.Nb);
   w.qc = c.take<float>(bh * g.Nc * p->d);
   w.kc = c.take<float>(bh * g.Nc * p->d);
   w.vc = c.take<float>(bh * g.Nc * p->d);
@@ -80,6 +85,7 @@ FwdWs carve_fwd(const vsa_params_t* p, const Geo& g, void* ws) {
   w.lse_c = c.take<float>(bh * g.Nc);
   w.idx = c.take<int32_t>(bh * g.Nc * p->topk);
   w.sc = c.take<float>(bh * g.Nc * g.Nc);
+  w.idx_blocks = g.m > 1 ? c.take<int32_t>(bh * g.Nb * p->topk * g.m) : nullptr;
   w.bytes = c.used;
   return w;
 }
@@ -88,7 +94,7 @@ struct BwdWs {
   uint64_t* mask;
   float *qc, *kc, *vc, *ld, *doc, *ac, *dsc, *dqc, *dkc, *dvc;
   void *dof, *ldb;
-  int32_t *row_ptr, *col, *order, *split;
+  int32_t *row_ptr, *col, *order, *split, *idx_blocks;
   uint32_t* bits;
   float* parts;
   int seg, cap;
@@ -100,19 +106,21 @@ struct BwdWs {
 // work is spread evenly (256 units), but not so short that start-up and the extra pass over the
 // partial sums outweigh the gain; the map scan lengthens it per (b, h) until the slots suffice.
 void split_plan(const vsa_params_t* p, const Geo& g, int* seg, int* cap) {
-  const long long entries = (long long)p->B * p->H * g.Nc * p->topk;
+  const long long kb = (long long)p->topk * g.m;  // list length in blocks
+  const long long entries = (long long)p->B * p->H * g.Nb * kb;
   long long s = entries / 512;
-  if (s > 4LL * p->topk) s = 4LL * p->topk;
+  if (s > 4 * kb) s = 4 * kb;
   if (s < 16) s = 16;
   *seg = (int)s;
-  int c = g.Nc / 4;
+  int c = g.Nb / 4;
   *cap = c < 16 ? 16 : (c > 64 ? 64 : c);
 }
 BwdWs carve_bwd(const vsa_params_t* p, const Geo& g, void* ws) {
   Carver c(ws);
   size_t bh = (size_t)p->B * p->H;
   BwdWs w;
-  w.mask = c.take<uint64_t>(g.Nc);
+  const size_t kb = (size_t)p->topk * g.m;
+  w.mask = c.take<uint64_t>(g.Nb);
   w.qc = c.take<float>(bh * g.Nc * p->d);
   w.kc = c.take<float>(bh * g.Nc * p->d);
   w.vc = c.take<float>(bh * g.Nc * p->d);
@@ -125,11 +133,12 @@ BwdWs carve_bwd(const vsa_params_t* p, const Geo& g, void* ws) {
   w.dkc = c.take<float>(bh * g.Nc * p->d);
   w.dvc = c.take<float>(bh * g.Nc * p->d);
   w.dof = c.take<uint16_t>(bh * g.Np * p->d);
-  w.row_ptr = c.take<int32_t>(bh * (g.Nc + 1));
-  w.col = c.take<int32_t>(bh * g.Nc * p->topk);
-  w.bits = c.take<uint32_t>(bh * g.Nc * ((g.Nc + 31) / 32));
+  w.row_ptr = c.take<int32_t>(bh * (g.Nb + 1));
+  w.col = c.take<int32_t>(bh * g.Nb * kb);
+  w.bits = c.take<uint32_t>(bh * g.Nb * ((g.Nb + 31) / 32));
+  w.idx_blocks = g.m > 1 ? c.take<int32_t>(bh * g.Nb * kb) : nullptr;
   split_plan(p, g, &w.seg, &w.cap);
-  w.order = c.take<int32_t>(4 * bh * (g.Nc + w.cap));  // (cube, run begin, run end, slot) per dK/dV workgroup
+  w.order = c.take<int32_t>(4 * bh * (g.Nb + w.cap));  // (block, run begin, run end, slot) per dK/dV workgroup
   w.split = c.take<int32_t>(4 * bh * (w.cap / 2 + 1));
   w.parts = c.take<float>(bh * w.cap * 2 * vsa::kTile * p->d);
   w.bytes = c.used;
@@ -196,8 +205,14 @@ int enqueue_forward(const vsa_params_t* p, const Geo& g, const void* q, const vo
 
   VSA_TRY("pool", vsa::launch_pool(g, BH, p->d, w.mask, q, k, v, w.qc, w.kc, w.vc, s));
   VSA_TRY("coarse", vsa::launch_coarse(BH, g.Nc, p->d, p->topk, scale, w.qc, w.kc, w.vc, w.sc, oc, lse_c, idx, given ? 0 : 1, (p->flags & VSA_FLAG_COARSE_FUSED) ? 1 : 0, s));
-  VSA_TRY("fine_fwd", vsa::launch_fine_fwd(BH, g.Nc, p->d, p->topk, scale, q, k, v, gate_c, gate_f, idx, oc, w.mask, out, out_fine,
-                               lse_fine, p->H, (p->flags & VSA_FLAG_OUT_TOKEN_MAJOR) ? 1 : 0, s));
+  // the fine stage works on 64-row blocks: a cube of m blocks contributes m list entries
+  const int32_t* lists = idx;
+  if (g.m > 1) {
+    VSA_TRY("expand_lists", vsa::launch_expand_lists(BH, g.Nc, p->topk, g.m, idx, w.idx_blocks, s));
+    lists = w.idx_blocks;
+  }
+  VSA_TRY("fine_fwd", vsa::launch_fine_fwd(BH, g.Nb, p->d, p->topk * g.m, scale, q, k, v, gate_c, gate_f, lists, oc, w.mask, out,
+                               out_fine, lse_fine, p->H, (p->flags & VSA_FLAG_OUT_TOKEN_MAJOR) ? 1 : 0, g.m, s));
   return VSA_OK;
 }
 
@@ -306,15 +321,21 @@ int vsa_backward(const vsa_params_t* p, const void* q, const void* k, const void
   if (!(p->flags & VSA_FLAG_WORKSPACE_KEPT)) {
     VSA_TRY("pool", vsa::launch_pool(g, BH, p->d, w.mask, q, k, v, w.qc, w.kc, w.vc, s));
   }
-  VSA_TRY("bwd_pre", vsa::launch_bwd_pre(BH, g.Nc, p->d, w.mask, dout, gate_c, gate_f, out_fine, out_coarse, dgate_c, dgate_f,
+  VSA_TRY("bwd_pre", vsa::launch_bwd_pre(BH, g.Nc, g.m, p->d, w.mask, dout, gate_c, gate_f, out_fine, out_coarse, dgate_c, dgate_f,
                               w.dof, w.ld, w.ldb, scale, w.doc, lse_fine, p->H, (p->flags & VSA_FLAG_OUT_TOKEN_MAJOR) ? 1 : 0, s));
   VSA_TRY("coarse_bwd", vsa::launch_coarse_bwd(BH, g.Nc, p->d, scale, w.qc, w.kc, w.vc, lse_coarse, w.doc, w.ac, w.dsc, w.dqc, w.dkc,
                                  w.dvc, s));
-  VSA_TRY("transpose_map", vsa::launch_transpose_map(BH, g.Nc, p->topk, block_idx, w.bits, w.row_ptr, w.col, w.order, w.split, w.seg, w.cap, s));
-  VSA_TRY("fine_bwd_dq", vsa::launch_fine_bwd_dq(BH, g.Nc, p->d, p->topk, scale, q, k, v, w.dof, block_idx, w.ld,
-                                  w.dqc, w.mask, dq, s));
-  VSA_TRY("fine_bwd_dkv", vsa::launch_fine_bwd_dkv(BH, g.Nc, p->d, p->topk, scale, q, k, v, w.dof, w.col, w.order, w.split, w.parts,
-                                   w.cap, w.ldb, w.dkc, w.dvc, w.mask, dk, dv, s));
+  const int32_t* lists = block_idx;
+  const int kb = p->topk * g.m;
+  if (g.m > 1) {
+    VSA_TRY("expand_lists", vsa::launch_expand_lists(BH, g.Nc, p->topk, g.m, block_idx, w.idx_blocks, s));
+    lists = w.idx_blocks;
+  }
+  VSA_TRY("transpose_map", vsa::launch_transpose_map(BH, g.Nb, kb, lists, w.bits, w.row_ptr, w.col, w.order, w.split, w.seg, w.cap, s));
+  VSA_TRY("fine_bwd_dq", vsa::launch_fine_bwd_dq(BH, g.Nb, p->d, kb, scale, q, k, v, w.dof, lists, w.ld,
+                                  w.dqc, w.mask, dq, g.m, s));
+  VSA_TRY("fine_bwd_dkv", vsa::launch_fine_bwd_dkv(BH, g.Nb, p->d, kb, scale, q, k, v, w.dof, w.col, w.order, w.split, w.parts,
+                                   w.cap, w.ldb, w.dkc, w.dvc, w.mask, dk, dv, g.m, s));
   return VSA_OK;
 }
 
@@ -324,14 +345,20 @@ int vsa_host_replay_lists(const vsa_params_t* p, const int32_t* host_block_idx, 
   if (rc != VSA_OK) return rc;
   if ((rc = check_topk(p, g)) != VSA_OK) return rc;
   if (!host_block_idx) return VSA_ERR_NULL;
-  const int Nc = g.Nc, K = p->topk;
+  // the kernels see lists of 64-row blocks: a cube of m blocks expands to m entries
+  const int Nc = g.Nb, K = p->topk * g.m;
   int seg_min, cap;
   split_plan(p, g, &seg_min, &cap);
+  std::vector<int32_t> expanded((size_t)Nc * K);
   int64_t bad = 0, max_deg = 0, max_items = 0, max_slots = 0, max_split = 0, max_col = 0;
   std::vector<unsigned char> bit((size_t)Nc * Nc);
   std::vector<int> deg(Nc), beg(Nc);
   for (long long bh = 0; bh < (long long)p->B * p->H; ++bh) {
-    const int32_t* lists = host_block_idx + bh * Nc * K;
+    for (int row = 0; row < Nc; ++row)
+      for (int e = 0; e < K; ++e)
+        expanded[(size_t)row * K + e] =
+            vsa::expanded_entry(host_block_idx[(bh * g.Nc + row / g.m) * p->topk + e / g.m], g.m, e % g.m);
+    const int32_t* lists = expanded.data();
     // forward and dQ pass: every lane of every 64-entry chunk reads a list slot, then fetches a cube
     for (int c = 0; c < Nc; ++c)
       for (int chunk = 0; chunk * 64 < K; ++chunk)
@@ -466,7 +493,7 @@ const char* vsa_status_string(int status) {
     case VSA_OK: return "ok";
     case VSA_ERR_NULL: return "a required pointer is NULL";
     case VSA_ERR_BAD_ARG: return "bad argument (dimension or topk out of range, gate_f/dgate_f mismatch)";
-    case VSA_ERR_UNSUPPORTED: return "unsupported configuration (cube volume != 64, d not 64/128, too many cubes)";
+    case VSA_ERR_UNSUPPORTED: return "unsupported configuration (cube volume not 64/128/256, d not 64/128, too many cubes)";
     case VSA_ERR_ALIGN: return "a device pointer is not 16-byte aligned";
     case VSA_ERR_WORKSPACE: return "workspace missing or too small";
     case VSA_ERR_HIP: return "a kernel launch failed";

@@ -5,7 +5,8 @@
 
 namespace vsa {
 
-constexpr int kTile = 64;  // tokens per cube = rows per attention tile (Sec. 2.2: B = 4*4*4)
+constexpr int kTile = 64;  // rows of one attention block; a cube of V = 64*m tokens (Sec. 2.2: V = 4*4*4;
+                           // Sec. 3.2 ablates 128 and 256) is m consecutive blocks of the tiled order
 
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
@@ -20,8 +21,10 @@ struct Geo {
   int Ct, Ch, Cw;   // cube
   int Nt, Nh, Nw;   // cubes per axis
   int Nc;           // cubes
+  int V, m;         // tokens per cube, 64-row blocks per cube (V = 64 * m)
+  int Nb;           // blocks = Nc * m
   int L;            // valid tokens
-  long long Np;     // padded tokens = 64 * Nc
+  long long Np;     // padded tokens = V * Nc
 };
 
 // bf16 bits <-> fp32.  Widening is exact; narrowing rounds to nearest even in hardware.
@@ -70,12 +73,21 @@ __device__ __forceinline__ float fast_log2(float x) { return __builtin_amdgcn_lo
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
-// Bit p of a cube's mask is set iff in-cube slot p = (pt*Ch + ph)*Cw + pw holds a valid token.
-// Computed by a whole wavefront: lane p answers for slot p.
-__device__ __forceinline__ uint64_t cube_valid_mask_wave(const Geo& g, int c, int lane) {
+// Validity mask of 64-row block `blk` (= cube blk / m, in-cube slots 64*(blk % m) .. +63): bit p is set
+// iff in-cube slot s = 64*(blk % m) + p = (pt*Ch + ph)*Cw + pw holds a valid token.  Computed by a
+// whole wavefront: lane p answers for bit p.
+__device__ __forceinline__ uint64_t block_valid_mask_wave(const Geo& g, int blk, int lane) {
+  const int c = blk / g.m, slot = (blk % g.m) * kTile + lane;
   const int cw = c % g.Nw, ch = (c / g.Nw) % g.Nh, ct = c / (g.Nw * g.Nh);
-  const int pw = lane % g.Cw, ph = (lane / g.Cw) % g.Ch, pt = lane / (g.Cw * g.Ch);
+  const int pw = slot % g.Cw, ph = (slot / g.Cw) % g.Ch, pt = slot / (g.Cw * g.Ch);
   return __ballot(ct * g.Ct + pt < g.T && ch * g.Ch + ph < g.Hh && cw * g.Cw + pw < g.W);
+}
+// Valid tokens of the cube that block `blk` belongs to (the divisor of the pooled means).
+__device__ __forceinline__ int cube_count(const uint64_t* __restrict__ mask, int blk, int m) {
+  const int b0 = blk - blk % m;
+  int n = 0;
+  for (int s = 0; s < m; ++s) n += __popcll(mask[b0 + s]);
+  return n;
 }
 
 }  // namespace vsa

@@ -15,10 +15,13 @@ hipError_t launch_coarse(int BH, int Nc, int d, int K, float scale, const float*
 hipError_t launch_fine_fwd(int BH, int Nc, int d, int K, float scale, const void* q, const void* k, const void* v,
                            const void* gate_c, const void* gate_f, const int32_t* idx, const float* oc,
                            const uint64_t* mask, void* out, void* out_fine, float* lse_f, int H, int out_token_major,
-                           hipStream_t s);
+                           int m_blocks, hipStream_t s);
+// lists of cubes -> lists of 64-row blocks, for cubes of m blocks: every block of query cube c gets
+// the m blocks of each of the cube's K key cubes, ascending ([BH,Nc,K] -> [BH,Nc*m,K*m])
+hipError_t launch_expand_lists(int BH, int Nc, int K, int m, const int32_t* idx, int32_t* idx_blocks, hipStream_t s);
 
 // backward
-hipError_t launch_bwd_pre(int BH, int Nc, int d, const uint64_t* mask, const void* dout, const void* gate_c,
+hipError_t launch_bwd_pre(int BH, int Nc, int m_blocks, int d, const uint64_t* mask, const void* dout, const void* gate_c,
                           const void* gate_f, const void* out_fine, const float* oc, void* dgate_c, void* dgate_f,
                           void* dof, float* ld, void* ldb, float scale, float* doc, const float* lse_f, int H,
                           int dout_token_major, hipStream_t s);
@@ -30,10 +33,10 @@ hipError_t launch_transpose_map(int BH, int Nc, int K, const int32_t* idx, uint3
                                 int32_t* col, int32_t* order, int32_t* split, int seg, int cap, hipStream_t s);
 hipError_t launch_fine_bwd_dq(int BH, int Nc, int d, int K, float scale, const void* q, const void* k, const void* v,
                               const void* dof, const int32_t* idx, const float* ld,
-                              const float* dqc, const uint64_t* mask, void* dq, hipStream_t s);
+                              const float* dqc, const uint64_t* mask, void* dq, int m_blocks, hipStream_t s);
 hipError_t launch_fine_bwd_dkv(int BH, int Nc, int d, int K, float scale, const void* q, const void* k, const void* v,
                                const void* dof, const int32_t* col, const int32_t* order, const int32_t* split,
                                float* parts, int cap, const void* ldb, const float* dkc, const float* dvc,
-                               const uint64_t* mask, void* dk, void* dv, hipStream_t s);
+                               const uint64_t* mask, void* dk, void* dv, int m_blocks, hipStream_t s);
 
 }  // namespace vsa

@@ -1,0 +1,66 @@
+"""Throughput against tile size (the "TFLOPS" column of the tile-size ablation, Sec. 3.2): the same
+16x32x32 latent (16384 tokens), 87.5 % tile sparsity, with cubes of 64, 128 and 256 tokens, i.e.
+top-K = 32 of 256, 16 of 128 and 8 of 64 cubes.  Forward and forward+backward, effective TFLOP/s on
+the selected blocks.  Synthetic i.i.d. inputs; a measurement aid that calls the library exactly as
+the benchmark does.
+
+    python -m paper_2505_13389_amd.tile_sizes [--heads 12] [--dim 128] [--steps 20]
+"""
+import argparse
+import json
+
+CUBES = [((4, 4, 4), 32), ((4, 4, 8), 16), ((4, 8, 8), 8)]
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--heads", type=int, default=12)
+    ap.add_argument("--dim", type=int, default=128)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    args = ap.parse_args()
+    import numpy as np
+    import torch
+    from . import vsa
+
+    def timed(fn):
+        for _ in range(args.warmup):
+            fn()
+        ts = []
+        for _ in range(args.steps):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            fn()
+            e1.record()
+            e1.synchronize()
+            ts.append(e0.elapsed_time(e1))
+        return float(np.median(ts))
+
+    rows = []
+    for cube, K in CUBES:
+        pb = vsa.Problem(1, args.heads, 16, 32, 32, args.dim, K, cube=cube)
+        Np, Nc = vsa.vsa_padded_tokens(pb)
+        g = torch.Generator(device="cuda")
+        g.manual_seed(3)
+        shape = (1, args.heads, Np, args.dim)
+        q, k, v, do = (torch.randn(shape, generator=g, device="cuda").to(torch.bfloat16) for _ in range(4))
+        gc, gf = (torch.rand(shape, generator=g, device="cuda").to(torch.bfloat16) for _ in range(2))
+        buf = vsa.Buffers(pb)
+
+        def both():
+            buf.forward(q, k, v, gc, gf)
+            buf.backward(q, k, v, gc, gf, do, workspace_kept=True)
+
+        tf, tb = timed(lambda: buf.forward(q, k, v, gc, gf)), timed(both)
+        V = cube[0] * cube[1] * cube[2]
+        fl = 4.0 * Np * K * V * args.dim * args.heads
+        line = {"tile": V, "cube": list(cube), "Nc": Nc, "topk": K, "sparsity": 1.0 - K / Nc, "fwd_ms": round(tf, 4),
+                "fwd_bwd_ms": round(tb, 4), "fwd_tflops": round(fl / tf / 1e9, 1),
+                "fwd_bwd_tflops": round(3.5 * fl / tb / 1e9, 1)}
+        print(json.dumps(line), flush=True)
+        rows.append(line)
+    return rows
+
+
+if __name__ == "__main__":
+    main()

@@ -64,14 +64,26 @@ def problem_of(wl, topk=None):
 
 
 def assert_close(got, ref, name, max_abs=MAX_ABS, rel_l2=REL_L2):
+    """max-abs and rel-L2 against the oracle.  The absolute bound `max_abs` presumes values of order
+    one, as on the benchmark workloads (N(0,1) inputs, lists of 8 or more cubes): the kernels feed
+    bf16 operands (2^-9 relative error per term) to the matrix cores and store bf16 (spacing
+    2^-7 |x|), so the error of an element scales with the magnitude of the terms it sums, not with
+    its own.  For a tensor whose largest reference magnitude M exceeds 2 the bound therefore scales
+    with M / 2, and an element is always allowed one spacing of the bf16 output format.  The rel-L2
+    bound holds over all elements unchanged."""
     got = np.asarray(got, dtype=np.float64)
     ref = np.asarray(ref, dtype=np.float64)
     assert got.shape == ref.shape, (name, got.shape, ref.shape)
     assert np.isfinite(got).all(), f"{name}: non-finite values"
-    err = np.abs(got - ref).max() if got.size else 0.0
+    diff = np.abs(got - ref)
+    err = diff.max() if got.size else 0.0
+    big = np.abs(ref).max() if got.size else 0.0
+    bound = max_abs * max(1.0, big / 2.0)
+    over = (diff - np.maximum(bound, np.abs(ref) * 2.0 ** -7)).max() if got.size else -1.0
     denom = np.sqrt((ref ** 2).sum())
     rel = np.sqrt(((got - ref) ** 2).sum()) / denom if denom > 0 else np.sqrt(((got - ref) ** 2).sum())
-    assert err <= max_abs and rel <= rel_l2, f"{name}: max-abs {err:.3e} (<= {max_abs}), rel-L2 {rel:.3e} (<= {rel_l2})"
+    assert over <= 0 and rel <= rel_l2, (f"{name}: max-abs {err:.3e} (<= {bound:.3g}; largest reference magnitude "
+                                         f"{big:.3g}), rel-L2 {rel:.3e} (<= {rel_l2})")
     return err, rel
 
 

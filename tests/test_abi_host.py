@@ -37,6 +37,8 @@ def test_padded_tokens_and_workspace(lib):
     assert vsa.vsa_padded_tokens(pb) == (39936, 624)
     assert vsa.vsa_padded_tokens(vsa.Problem(1, 40, 21, 45, 80, 128, 180)) == (92160, 1440)
     assert vsa.vsa_padded_tokens(vsa.Problem(1, 2, 8, 16, 16, 64, 8)) == (2048, 32)
+    assert vsa.vsa_padded_tokens(vsa.Problem(1, 12, 21, 30, 52, 128, 39, cube=(4, 4, 8))) == (43008, 336)
+    assert vsa.vsa_padded_tokens(vsa.Problem(1, 12, 21, 30, 52, 128, 20, cube=(4, 8, 8))) == (43008, 168)
     f, b = vsa.vsa_workspace_bytes(pb, False), vsa.vsa_workspace_bytes(pb, True)
     assert 0 < f < b
     assert f >= 3 * 12 * 624 * 128 * 4  # at least the three pooled tensors
@@ -88,16 +90,18 @@ def test_bench_refuses_more_than_one_gpu():
     assert r.stdout.strip() == ""
 
 
-@pytest.mark.parametrize("shape,topk", [((2, 2, 8, 16, 16), 8), ((1, 2, 12, 16, 20), 6), ((1, 1, 21, 30, 52), 78),
-                                        ((1, 2, 16, 32, 32), 130)])
-def test_list_index_rules_keep_hostile_lists_in_bounds(lib, shape, topk):
+@pytest.mark.parametrize("shape,topk,cube", [((2, 2, 8, 16, 16), 8, (4, 4, 4)), ((1, 2, 12, 16, 20), 6, (4, 4, 4)),
+                                             ((1, 1, 21, 30, 52), 78, (4, 4, 4)), ((1, 2, 16, 32, 32), 130, (4, 4, 4)),
+                                             ((1, 2, 16, 32, 32), 9, (4, 4, 8)), ((2, 1, 12, 30, 30), 5, (4, 8, 8))])
+def test_list_index_rules_keep_hostile_lists_in_bounds(lib, shape, topk, cube):
     """The clamp / skip / split arithmetic the kernels apply to block lists, replayed on the CPU through
     the same functions: lists full of out-of-range entries, duplicates and disorder, lists where every
     query cube names the same few key cubes (longest possible transposed lists), and ordinary ones."""
     import numpy as np
     B, H, T, Hh, W = shape
-    pb = vsa.Problem(B, H, T, Hh, W, 64, topk)
-    _, Nc = vsa.vsa_padded_tokens(pb)
+    pb = vsa.Problem(B, H, T, Hh, W, 64, topk, cube=cube)
+    Np, Nc = vsa.vsa_padded_tokens(pb)
+    m = cube[0] * cube[1] * cube[2] // 64  # attention blocks of 64 rows per cube: the kernels' lists name blocks
     rng = np.random.Generator(np.random.PCG64(17))
     hostile = rng.integers(-9, Nc + 9, size=(B, H, Nc, topk), dtype=np.int64).astype(np.int32)
     hostile[0, 0, 0, :] = np.iinfo(np.int32).max
@@ -107,9 +111,10 @@ def test_list_index_rules_keep_hostile_lists_in_bounds(lib, shape, topk):
     for lists in (hostile, same, ordinary):
         rc, rep = vsa.vsa_host_replay_lists(pb, lists)
         assert rc == 0 and rep["violations"] == 0, rep
-        assert rep["longest_list"] <= Nc and rep["col_entries"] <= Nc * topk
-        assert rep["items"] <= Nc + rep["cap"] and rep["slots"] <= rep["cap"] and rep["split_lists"] <= rep["cap"] // 2
+        assert rep["longest_list"] <= Nc * m and rep["col_entries"] <= Nc * m * topk * m
+        assert rep["items"] <= Nc * m + rep["cap"] and rep["slots"] <= rep["cap"]
+        assert rep["split_lists"] <= rep["cap"] // 2
     rc, rep = vsa.vsa_host_replay_lists(pb, same)
-    assert rep["longest_list"] == Nc
-    if Nc > rep["seg"] and 2 * topk <= rep["cap"]:  # (more equal long lists than slots: nothing to balance)
-        assert rep["split_lists"] == topk and rep["items"] > Nc  # the sink lists are shared by several workgroups
+    assert rep["longest_list"] == Nc * m
+    if Nc * m > rep["seg"] and 2 * topk * m <= rep["cap"]:  # (more equal long lists than slots: nothing to balance)
+        assert rep["split_lists"] == topk * m and rep["items"] > Nc * m  # the sink lists are shared by several workgroups

@@ -31,6 +31,12 @@ SMALL = {
     # other 64-token cube shapes (Sec. 3.2 ablates the tile shape; the volume is what the kernels fix)
     "cube_2x4x8": Workload("cube_2x4x8", 1, 2, 7, 10, 20, 128, 5, cube=(2, 4, 8)),
     "cube_1x8x8": Workload("cube_1x8x8", 1, 2, 3, 20, 17, 64, 4, cube=(1, 8, 8)),
+    # larger cubes (Sec. 3.2 tile-size ablation): 128 and 256 tokens = 2 and 4 attention blocks of 64 rows
+    "cube128_4x4x8": Workload("cube128_4x4x8", 1, 2, 8, 10, 27, 128, 5, cube=(4, 4, 8)),
+    "cube128_2x8x8": Workload("cube128_2x8x8", 2, 1, 5, 20, 24, 64, 4, cube=(2, 8, 8)),
+    "cube256_4x8x8": Workload("cube256_4x8x8", 1, 2, 10, 20, 22, 128, 3, cube=(4, 8, 8)),
+    "cube256_dense": Workload("cube256_dense", 1, 1, 8, 16, 16, 64, 4, cube=(4, 8, 8)),
+    "cube128_planted": Workload("cube128_planted", 1, 2, 8, 16, 30, 64, 6, cube=(4, 4, 8), planted=True),
     # list lengths around the 64-entry chunks in which the kernels hold their index lists
     "k64": Workload("k64", 1, 1, 12, 16, 24, 64, 64),
     "k65": Workload("k65", 1, 1, 12, 16, 23, 64, 65),
@@ -63,10 +69,12 @@ def run_gpu_fwd(vsa, wl, dev, block_idx=None, backward=False):
 
 
 # ------------------------------------------------------------------------------ permutation
-@pytest.mark.parametrize("grid3,d", [((8, 16, 16), 64), ((5, 6, 7), 64), ((21, 30, 52), 128), ((4, 4, 4), 128)])
-def test_tile_permute_bit_exact_and_round_trip(vsa, grid3, d):
+@pytest.mark.parametrize("grid3,d,cube", [((8, 16, 16), 64, (4, 4, 4)), ((5, 6, 7), 64, (4, 4, 4)),
+                                          ((21, 30, 52), 128, (4, 4, 4)), ((4, 4, 4), 128, (4, 4, 4)),
+                                          ((9, 10, 27), 64, (4, 4, 8)), ((21, 30, 52), 128, (4, 8, 8))])
+def test_tile_permute_bit_exact_and_round_trip(vsa, grid3, d, cube):
     import torch
-    wl = Workload("perm", 2, 3, *grid3, d, 1)
+    wl = Workload("perm", 2, 3, *grid3, d, 1, cube=cube)
     g = grid_of(wl)
     rng = np.random.default_rng(3)
     src = rng.integers(0, 65536, size=(wl.B, wl.H, wl.L, d), dtype=np.uint16)
@@ -103,8 +111,11 @@ def test_tile_permute_token_major_raster(vsa, grid3, d):
 
 
 # ------------------------------------------------------------------------------ coarse stage + top-K
+BIG_CUBES = ["cube128_4x4x8", "cube128_2x8x8", "cube256_4x8x8", "cube256_dense", "cube128_planted"]
+
+
 @pytest.mark.parametrize("name", ["tiny", "tiny_dense", "tiny128", "pad64", "pad128", "one_cube", "k1", "planted",
-                                  "cube_2x4x8", "cube_1x8x8"])
+                                  "cube_2x4x8", "cube_1x8x8"] + BIG_CUBES)
 def test_coarse_stage_and_topk(vsa, name):
     wl = SMALL[name]
     bits = tiled_bits(wl, seed=1)
@@ -145,7 +156,7 @@ def test_topk_ties_go_to_the_lower_index(vsa):
 
 # ------------------------------------------------------------------------------ forward
 @pytest.mark.parametrize("name", ["tiny", "tiny_dense", "tiny128", "pad64", "pad128", "one_cube", "k1", "cube_2x4x8",
-                                  "cube_1x8x8", "k64", "k65", "k2", "k3_d128", "dense_pad128"])
+                                  "cube_1x8x8", "k64", "k65", "k2", "k3_d128", "dense_pad128"] + BIG_CUBES)
 @pytest.mark.parametrize("with_gate_f", [True, False])
 def test_forward_on_oracle_indices(vsa, name, with_gate_f):
     """The fine kernel on the oracle's own selection: a near-tie flip can neither hide nor fake an error."""
@@ -213,7 +224,7 @@ def test_forward_is_deterministic_and_ignores_pad_slots(vsa):
 
 # ------------------------------------------------------------------------------ backward
 @pytest.mark.parametrize("name", ["tiny", "tiny_dense", "tiny128", "pad64", "pad128", "one_cube", "k1", "planted",
-                                  "cube_2x4x8", "cube_1x8x8", "k64", "k65", "k2", "k3_d128", "dense_pad128"])
+                                  "cube_2x4x8", "cube_1x8x8", "k64", "k65", "k2", "k3_d128", "dense_pad128"] + BIG_CUBES)
 @pytest.mark.parametrize("with_gate_f", [True, False])
 def test_backward_on_oracle_indices(vsa, name, with_gate_f):
     import torch

@@ -14,26 +14,30 @@ pytestmark = pytest.mark.gpu
 CUBES = [(4, 4, 4), (2, 4, 8), (1, 8, 8), (8, 4, 2), (2, 2, 16), (4, 8, 2)]
 
 
-def random_workloads(n, seed=20250513):
+BIG_CUBES = [(4, 4, 8), (2, 8, 8), (8, 4, 4), (4, 8, 8), (8, 8, 4), (2, 8, 16)]  # 128 and 256 tokens
+
+
+def random_workloads(n, seed=20250513, cubes=CUBES, tag="rnd"):
     rng = np.random.Generator(np.random.PCG64(seed))
     out = []
     while len(out) < n:
-        cube = CUBES[rng.integers(len(CUBES))]
+        cube = cubes[rng.integers(len(cubes))]
         # 2..5 cubes per axis, each axis possibly ragged
         dims = [int(c * rng.integers(2, 6) - rng.integers(0, c)) for c in cube]
         pad = [(-d) % c + d for d, c in zip(dims, cube)]
-        nc = pad[0] * pad[1] * pad[2] // 64
-        if nc > 60:
+        vol = cube[0] * cube[1] * cube[2]
+        nc = pad[0] * pad[1] * pad[2] // vol
+        if nc * (vol // 64) > 60:
             continue
         topk = int(rng.integers(1, nc + 1)) if rng.random() < 0.8 else nc
         d = int(rng.choice([64, 128]))
         B, H = (1, 2) if rng.random() < 0.7 else (2, 1)
-        out.append(Workload(f"rnd{len(out)}", B, H, dims[0], dims[1], dims[2], d, topk, cube=cube,
+        out.append(Workload(f"{tag}{len(out)}", B, H, dims[0], dims[1], dims[2], d, topk, cube=cube,
                             planted=bool(rng.random() < 0.3)))
     return out
 
 
-CASES = random_workloads(12)
+CASES = random_workloads(12) + random_workloads(6, seed=20250514, cubes=BIG_CUBES, tag="big")
 
 
 @pytest.fixture(scope="module")
