@@ -43,7 +43,7 @@ extern "C" {
 typedef enum {
   VSA_OK = 0,
   VSA_ERR_NULL = -1,        /* a required pointer is NULL                              */
-  VSA_ERR_BAD_ARG = -2,     /* non-positive dimension, topk outside 1..Nc              */
+  VSA_ERR_BAD_ARG = -2,     /* non-positive dimension, topk outside 1..Nc, scale too small */
   VSA_ERR_UNSUPPORTED = -3, /* cube volume not 64/128/256, d not in {64,128}, too many cubes */
   VSA_ERR_ALIGN = -4,       /* a device pointer is not 16-byte aligned                 */
   VSA_ERR_WORKSPACE = -5,   /* workspace NULL or smaller than vsa_workspace_bytes      */
@@ -68,6 +68,8 @@ typedef enum {
                                        the activations stay tiled across the transformer (App. B caption),
                                        so no relayout pass remains.  vsa_backward: `dout` is read in the
                                        same layout.  All other tensors keep [B,H,Np,d]. */
+#define VSA_MIN_SOFTMAX_SCALE (1.0f / 64.0f) /* smallest explicit softmax_scale accepted (the pad-key bias of
+                                               -30000 must still underflow the exponential once scaled) */
 #define VSA_MAX_CUBES 4096        /* largest supported Np / 64 (= Nc for 64-token cubes)  */
 #define VSA_STATIC_SCRATCH_MIB 40 /* size of the scratch buffer behind vsa_forward_static, MiB */
 
@@ -77,7 +79,7 @@ typedef struct {
   int32_t Ct, Ch, Cw;  /* cube shape; Ct*Ch*Cw must be 64 (Sec. 2.2: (4,4,4)), 128 or 256  */
   int32_t d;           /* head dimension: 64 or 128                                      */
   int32_t topk;        /* key cubes per query cube, 1..Nc; Nc = the dense path           */
-  float softmax_scale; /* <= 0 selects 1/sqrt(d) (Sec. 2.1)                              */
+  float softmax_scale; /* <= 0 selects 1/sqrt(d) (Sec. 2.1); else >= VSA_MIN_SOFTMAX_SCALE       */
   uint32_t flags;      /* VSA_FLAG_*                                                     */
 } vsa_params_t;
 

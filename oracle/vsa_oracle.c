@@ -310,6 +310,53 @@ int vsa_oracle_forward(int B, int H, int T, int Hh, int W, int Ct, int Ch, int C
 }
 
 /* ------------------------------------------------------------------------------------ */
+/* Selection-quality diagnostic [Sec. 3.5]                                              */
+/* ------------------------------------------------------------------------------------ */
+/*
+ * Sec. 3.5 asks how much of the dense attention a set of key cubes captures: the sum of the dense
+ * attention scores that fall inside the cubes, averaged over query tokens.  For ONE (b, h) slice
+ * this returns the whole cube-by-cube table
+ *   mass[c][j] = (1 / cnt_c) sum_{valid i in cube c} sum_{valid n in cube j} A_in,
+ *   A = softmax over all valid keys of q_i . k_n * scale            [Sec. 2.1 attention equation]
+ * so that rows sum to 1 and the mass captured by any selection is a sum of K entries of a row.
+ * q, k: [Np, d] tiled.  Plain token loops.
+ */
+int vsa_oracle_block_mass(int T, int Hh, int W, int Ct, int Ch, int Cw, int d, double scale_, const real* q,
+                          const real* k, real* mass) {
+  grid_t g = make_grid(T, Hh, W, Ct, Ch, Cw);
+  if (d < 1 || !q || !k || !mass) return -1;
+  real scale = (real)scale_;
+  uint8_t* valid = (uint8_t*)malloc((size_t)g.Np);
+  int32_t* cnt = (int32_t*)malloc(sizeof(int32_t) * (size_t)g.Nc);
+  vsa_oracle_valid(T, Hh, W, Ct, Ch, Cw, valid, cnt);
+  const int Nc = g.Nc, Bk = g.Bk;
+  for (int64_t x = 0; x < (int64_t)Nc * Nc; ++x) mass[x] = 0;
+#pragma omp parallel for schedule(dynamic, 1)
+  for (int c = 0; c < Nc; ++c) {
+    real* s = (real*)malloc(sizeof(real) * (size_t)g.Np);
+    for (int p = 0; p < Bk; ++p) {
+      int64_t i = (int64_t)c * Bk + p;
+      if (!valid[i]) continue;
+      real m = -INFINITY, l = 0;
+      for (int64_t n = 0; n < g.Np; ++n) {
+        if (!valid[n]) continue;
+        real acc = 0;
+        for (int e = 0; e < d; ++e) acc += q[i * d + e] * k[n * d + e];
+        s[n] = acc * scale;
+        if (s[n] > m) m = s[n];
+      }
+      for (int64_t n = 0; n < g.Np; ++n)
+        if (valid[n]) { s[n] = EXP(s[n] - m); l += s[n]; }
+      for (int64_t n = 0; n < g.Np; ++n)
+        if (valid[n]) mass[(int64_t)c * Nc + n / Bk] += s[n] / l / (real)cnt[c];
+    }
+    free(s);
+  }
+  free(valid); free(cnt);
+  return 0;
+}
+
+/* ------------------------------------------------------------------------------------ */
 /* Backward                                                                             */
 /* ------------------------------------------------------------------------------------ */
 /*

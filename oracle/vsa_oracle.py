@@ -153,6 +153,23 @@ def backward(grid: Grid, q, k, v, gate_c, gate_f, dout, block_idx, topk: int, sc
     return res
 
 
+def block_mass(grid: Grid, q, k, scale: float = None, real: str = "f64"):
+    """One (b,h) slice, q and k [Np,d] tiled: table [Nc,Nc] of the dense attention mass that the tokens
+    of query cube c put on key cube j, averaged over the cube's valid tokens [Sec. 3.5]."""
+    dt = _np_real(real)
+    q, k = _as(q, dt), _as(k, dt)
+    Np, d = q.shape
+    Np_, Nc, _ = grid.dims()
+    assert Np == Np_ and k.shape == q.shape
+    if scale is None:
+        scale = 1.0 / np.sqrt(d)
+    mass = np.zeros((Nc, Nc), dt)
+    rc = _lib(real).vsa_oracle_block_mass(*grid.args(), d, C.c_double(scale), _ptr(q), _ptr(k), _ptr(mass))
+    if rc != 0:
+        raise ValueError("vsa_oracle_block_mass: bad argument")
+    return mass
+
+
 def attention_flops(n_query_tokens, n_key_tokens_per_query, d, heads, batch=1, with_backward=False) -> float:
     return float(_lib("f64").vsa_oracle_attention_flops(
         float(n_query_tokens), float(n_key_tokens_per_query), float(d), float(heads), float(batch),

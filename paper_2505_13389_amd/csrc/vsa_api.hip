@@ -27,6 +27,10 @@ int check_params(const vsa_params_t* p, Geo* g) {
   const long long vol = (long long)p->Ct * p->Ch * p->Cw;
   if (vol != 64 && vol != 128 && vol != 256) return VSA_ERR_UNSUPPORTED;
   if (p->d != 64 && p->d != 128) return VSA_ERR_UNSUPPORTED;
+  // pad keys are removed by a bias of -30000 on their raw logits: below this scale the bias, once
+  // scaled, no longer drives exp2 to zero against every admissible logit
+  if (p->softmax_scale > 0.f && p->softmax_scale < VSA_MIN_SOFTMAX_SCALE) return VSA_ERR_BAD_ARG;
+  if (p->softmax_scale != p->softmax_scale) return VSA_ERR_BAD_ARG;
   g->T = p->T; g->Hh = p->Hh; g->W = p->W;
   g->Ct = p->Ct; g->Ch = p->Ch; g->Cw = p->Cw;
   g->Nt = (p->T + p->Ct - 1) / p->Ct;

@@ -47,6 +47,8 @@ def test_padded_tokens_and_workspace(lib):
 @pytest.mark.parametrize("kwargs,status", [
     (dict(cube=(2, 2, 2)), -3), (dict(d=96), -3), (dict(T=0), -2), (dict(B=0), -2),
     (dict(T=256, Hh=256, W=256), -3),  # more cubes than VSA_MAX_CUBES
+    (dict(softmax_scale=1e-3), -2),    # the pad-key bias would no longer mask
+    (dict(cube=(4, 8, 16)), -3),       # 512-token cubes
 ])
 def test_bad_parameters_are_rejected(lib, kwargs, status):
     base = dict(B=1, H=2, T=8, Hh=16, W=16, d=64, topk=8)

@@ -353,6 +353,34 @@ def test_fp32_build_stays_close_to_fp64_build():
         assert np.abs(ga[name] - gb[name]).max() < 2e-5, name
 
 
+# ----------------------------------------------------------------------------- selection quality
+def test_block_mass_is_the_dense_attention_matrix_summed_over_cubes():
+    """[Sec. 3.5] the mass table is the dense attention matrix (numpy brute force over the valid keys)
+    summed over key cubes and averaged over the valid tokens of each query cube: rows sum to 1; for
+    the unit cube it IS the attention matrix; q = 0 gives each key cube its share of the valid tokens."""
+    g = Grid(5, 6, 7, 4, 4, 4)  # ragged on every axis
+    valid, cnt = orc.valid_mask(g)
+    Np, Nc, Bk = g.dims()
+    d = 16
+    q, k = rand(Np, d), rand(Np, d)
+    mass = orc.block_mass(g, q, k)
+    s = (q @ k.T) / np.sqrt(d)
+    s = np.where(valid[None, :], s, -np.inf)
+    p = np.exp(s - s.max(-1, keepdims=True))
+    p /= p.sum(-1, keepdims=True)
+    p = p * valid[:, None]
+    want = p.reshape(Nc, Bk, Nc, Bk).sum(axis=(1, 3)) / cnt[:, None]
+    assert np.abs(mass - want).max() < 1e-12
+    assert np.abs(mass.sum(-1) - 1.0).max() < 1e-12
+    uniform = orc.block_mass(g, np.zeros_like(q), k)
+    assert np.abs(uniform - (cnt / cnt.sum())[None, :]).max() < 1e-12
+    g1 = Grid(2, 3, 4, 1, 1, 1)
+    q1, k1 = rand(24, 8), rand(24, 8)
+    s1 = (q1 @ k1.T) / np.sqrt(8)
+    p1 = np.exp(s1 - s1.max(-1, keepdims=True))
+    assert np.abs(orc.block_mass(g1, q1, k1) - p1 / p1.sum(-1, keepdims=True)).max() < 1e-12
+
+
 def test_paper_anchors():
     path = os.path.join(os.path.dirname(__file__), "golden", "paper_anchors.txt")
     gold = {}
