@@ -68,6 +68,17 @@ typedef enum {
                                        the activations stay tiled across the transformer (App. B caption),
                                        so no relayout pass remains.  vsa_backward: `dout` is read in the
                                        same layout.  All other tensors keep [B,H,Np,d]. */
+#define VSA_FLAG_SELECT_POOLED_2X2 32u /* mismatched granularity (Sec. 3.2): the coarse stage pools over the
+                                         (Ct,Ch,Cw) cubes (64 tokens), the fine stage attends in tiles of
+                                         (1,2,2) cubes = 256 tokens.  The coarse attention map is averaged
+                                         over the 2x2 cubes of the query tile and of the key tile, and the
+                                         topk largest entries of each row of the pooled map select key
+                                         TILES: block_idx is then int32 [B,H,Ns,topk], Ns = Nc/4 tiles,
+                                         tile (st,sh,sw) = (st*Nh/2 + sh)*Nw/2 + sw holding cubes
+                                         (st, 2sh+a, 2sw+b); 1 <= topk <= Ns.  Needs 64-token cubes and
+                                         even numbers of cubes along h and w (else VSA_ERR_UNSUPPORTED).
+                                         Pass the flag to vsa_forward, vsa_backward and
+                                         vsa_workspace_bytes alike. */
 #define VSA_MIN_SOFTMAX_SCALE (1.0f / 64.0f) /* smallest explicit softmax_scale accepted (the pad-key bias of
                                                -30000 must still underflow the exponential once scaled) */
 #define VSA_MAX_CUBES 4096        /* largest supported Np / 64 (= Nc for 64-token cubes)  */

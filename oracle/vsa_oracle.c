@@ -310,6 +310,78 @@ int vsa_oracle_forward(int B, int H, int T, int Hh, int W, int Ct, int Ch, int C
 }
 
 /* ------------------------------------------------------------------------------------ */
+/* Mismatched granularity [Sec. 3.2, paragraph after the tile-size tables]              */
+/* ------------------------------------------------------------------------------------ */
+/*
+ * The coarse stage pools over (Ct,Ch,Cw) cubes while the fine stage attends in tiles of (1,2,2)
+ * cubes, i.e. (Ct,2Ch,2Cw) tokens: the coarse stage's attention map A_c [Nc x Nc] is average-pooled
+ * over the 2x2 groups of cubes, on the query and on the key axis, and the top-K is taken on the
+ * pooled map [Ns x Ns] (ties to the lower tile index).  Everything else (pooled tensors, O_c, the
+ * gated sum) stays at cube granularity.  Needs even numbers of cubes along h and w.
+ *
+ * Per (b,h):  tile_idx [Ns, topk]      the selected key tiles of every query tile, ascending;
+ *             cube_idx [Nc, 4*topk]    the same selection as a list of key cubes for every query
+ *                                      cube (all four cubes of each selected tile), ascending: the
+ *                                      form vsa_oracle_forward / _backward take as block_idx;
+ *             pooled   [Ns, Ns]        the pooled map (may be NULL).
+ * Tile (st,sh,sw) has index (st*Nh/2 + sh)*Nw/2 + sw and holds cubes (st, 2sh+a, 2sw+b), a,b in {0,1}.
+ */
+int vsa_oracle_select_pooled(int B, int H, int T, int Hh, int W, int Ct, int Ch, int Cw, int d, int topk, double scale_,
+                             const real* q, const real* k, int32_t* tile_idx, int32_t* cube_idx, real* pooled) {
+  grid_t g = make_grid(T, Hh, W, Ct, Ch, Cw);
+  if (g.Nh % 2 || g.Nw % 2) return -1;
+  const int Nc = g.Nc, Sh = g.Nh / 2, Sw = g.Nw / 2, Ns = g.Nt * Sh * Sw;
+  if (B < 1 || H < 1 || d < 1 || topk < 1 || topk > Ns || !tile_idx || !cube_idx) return -1;
+  real scale = (real)scale_;
+  uint8_t* valid = (uint8_t*)malloc((size_t)g.Np);
+  int32_t* cnt = (int32_t*)malloc(sizeof(int32_t) * (size_t)Nc);
+  vsa_oracle_valid(T, Hh, W, Ct, Ch, Cw, valid, cnt);
+  for (int bh = 0; bh < B * H; ++bh) {
+    const real* qh = q + (int64_t)bh * g.Np * d;
+    const real* kh = k + (int64_t)bh * g.Np * d;
+    real* Qc = (real*)malloc(sizeof(real) * (size_t)Nc * d);
+    real* Kc = (real*)malloc(sizeof(real) * (size_t)Nc * d);
+    real* Ac = (real*)malloc(sizeof(real) * (size_t)Nc * Nc);
+    real* Ps = (real*)calloc((size_t)Ns * Ns, sizeof(real));
+    real* row = (real*)malloc(sizeof(real) * (size_t)Nc);
+    pool_mean(&g, d, valid, cnt, qh, Qc);
+    pool_mean(&g, d, valid, cnt, kh, Kc);
+    for (int c = 0; c < Nc; ++c) {
+      coarse_logits_row(&g, d, scale, Qc, Kc, c, row);
+      softmax_row(Nc, row, Ac + (int64_t)c * Nc);
+    }
+    /* average over the 2x2 cubes of the query tile and the 2x2 cubes of the key tile */
+    for (int c = 0; c < Nc; ++c) {
+      int cw = c % g.Nw, ch = (c / g.Nw) % g.Nh, ct = c / (g.Nw * g.Nh);
+      int sq = (ct * Sh + ch / 2) * Sw + cw / 2;
+      for (int j = 0; j < Nc; ++j) {
+        int jw = j % g.Nw, jh = (j / g.Nw) % g.Nh, jt = j / (g.Nw * g.Nh);
+        int sk = (jt * Sh + jh / 2) * Sw + jw / 2;
+        Ps[(int64_t)sq * Ns + sk] += Ac[(int64_t)c * Nc + j] / (real)16;
+      }
+    }
+    int32_t* tl = tile_idx + (int64_t)bh * Ns * topk;
+    for (int s = 0; s < Ns; ++s) topk_row(Ns, Ps + (int64_t)s * Ns, topk, tl + (int64_t)s * topk);
+    for (int c = 0; c < Nc; ++c) {
+      int cw = c % g.Nw, ch = (c / g.Nw) % g.Nh, ct = c / (g.Nw * g.Nh);
+      int sq = (ct * Sh + ch / 2) * Sw + cw / 2;
+      int32_t* out = cube_idx + ((int64_t)bh * Nc + c) * 4 * topk;
+      for (int r = 0; r < topk; ++r) {
+        int s = tl[(int64_t)sq * topk + r];
+        int sw = s % Sw, sh = (s / Sw) % Sh, st = s / (Sw * Sh);
+        for (int a = 0; a < 2; ++a)
+          for (int b = 0; b < 2; ++b) out[4 * r + 2 * a + b] = (st * g.Nh + 2 * sh + a) * g.Nw + 2 * sw + b;
+      }
+      qsort(out, (size_t)(4 * topk), sizeof(int32_t), cmp_i32);
+    }
+    if (pooled) memcpy(pooled + (int64_t)bh * Ns * Ns, Ps, sizeof(real) * (size_t)Ns * Ns);
+    free(Qc); free(Kc); free(Ac); free(Ps); free(row);
+  }
+  free(valid); free(cnt);
+  return 0;
+}
+
+/* ------------------------------------------------------------------------------------ */
 /* Selection-quality diagnostic [Sec. 3.5]                                              */
 /* ------------------------------------------------------------------------------------ */
 /*

@@ -153,6 +153,27 @@ def backward(grid: Grid, q, k, v, gate_c, gate_f, dout, block_idx, topk: int, sc
     return res
 
 
+def select_pooled(grid: Grid, q, k, topk: int, scale: float = None, real: str = "f64"):
+    """Mismatched granularity [Sec. 3.2]: top-K of the coarse attention map average-pooled over (1,2,2)
+    cubes.  Returns dict(tile_idx [B,H,Ns,topk], cube_idx [B,H,Nc,4*topk], pooled [B,H,Ns,Ns])."""
+    dt = _np_real(real)
+    q, k = _as(q, dt), _as(k, dt)
+    B, H, Np, d = q.shape
+    Np_, Nc, _ = grid.dims()
+    assert Np == Np_
+    if scale is None:
+        scale = 1.0 / np.sqrt(d)
+    up = lambda a, b: (a + b - 1) // b
+    Ns = up(grid.T, grid.Ct) * (up(grid.Hh, grid.Ch) // 2) * (up(grid.W, grid.Cw) // 2)
+    res = dict(tile_idx=np.zeros((B, H, Ns, topk), np.int32), cube_idx=np.zeros((B, H, Nc, 4 * topk), np.int32),
+               pooled=np.zeros((B, H, Ns, Ns), dt))
+    rc = _lib(real).vsa_oracle_select_pooled(B, H, *grid.args(), d, topk, C.c_double(scale), _ptr(q), _ptr(k),
+                                             _ptr(res["tile_idx"]), _ptr(res["cube_idx"]), _ptr(res["pooled"]))
+    if rc != 0:
+        raise ValueError("vsa_oracle_select_pooled: bad argument (odd number of cubes along h or w?)")
+    return res
+
+
 def block_mass(grid: Grid, q, k, scale: float = None, real: str = "f64"):
     """One (b,h) slice, q and k [Np,d] tiled: table [Nc,Nc] of the dense attention mass that the tokens
     of query cube c put on key cube j, averaged over the cube's valid tokens [Sec. 3.5]."""

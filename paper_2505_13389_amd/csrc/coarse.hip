@@ -208,6 +208,47 @@ __global__ __launch_bounds__(256) void k_expand_lists(long long total, int K, in
   const long long t = (e / m) % K, row = e / ((long long)m * K * m);
   out[e] = expanded_entry(idx[row * K + t], m, u);
 }
+// Mismatched granularity (Sec. 3.2: coarse stage on cubes, fine stage on tiles of (1,2,2) cubes): the
+// coarse attention map P [Nc x Nc] is averaged over the 2x2 cubes of the query tile and the 2x2
+// cubes of the key tile; the top-K is then taken per row of the pooled map (k_coarse_rows).  One
+// thread per pooled entry; the 16 terms are added in a fixed order (query cubes ascending, key cubes
+// ascending within each), every term scaled by 1/16 first.
+__global__ __launch_bounds__(256) void k_pool_scores(long long total, int Nt, int Nh, int Nw, const float* __restrict__ P,
+                                                     float* __restrict__ Ps) {
+  const long long e = (long long)blockIdx.x * 256 + threadIdx.x;  // (bh * Ns + sq) * Ns + sk
+  if (e >= total) return;
+  const int Nc = Nt * Nh * Nw, Ns = Nc / 4;
+  const int sk = (int)(e % Ns), sq = (int)((e / Ns) % Ns);
+  const long long bh = e / ((long long)Ns * Ns);
+  const float* Pb = P + bh * Nc * Nc;
+  float acc = 0.f;
+#pragma unroll
+  for (int xq = 0; xq < 4; ++xq) {
+    const int c = tile_member_cube(sq, xq, Nt, Nh, Nw);
+#pragma unroll
+    for (int xk = 0; xk < 4; ++xk) acc += Pb[(long long)c * Nc + tile_member_cube(sk, xk, Nt, Nh, Nw)] * 0.0625f;
+  }
+  Ps[e] = acc;
+}
+// tile lists [BH,Ns,K] -> lists of 64-row blocks (= cubes) for every query cube, [BH,Nc,4K]
+__global__ __launch_bounds__(256) void k_expand_tiles(long long total, int K, int Nt, int Nh, int Nw,
+                                                      const int32_t* __restrict__ tile_idx, int32_t* __restrict__ out) {
+  const long long e = (long long)blockIdx.x * 256 + threadIdx.x;  // ((bh * Nc + c) * K + t) * 4 + x
+  if (e >= total) return;
+  const int Nc = Nt * Nh * Nw, Ns = Nc / 4;
+  const int x = (int)(e & 3), t = (int)((e >> 2) % K);
+  const long long row = e / (4LL * K);
+  const int c = (int)(row % Nc);
+  const long long bh = row / Nc;
+  out[e] = tile_member_cube(tile_idx[(bh * Ns + tile_of_cube(c, Nh, Nw)) * K + t], x, Nt, Nh, Nw);
+}
+hipError_t launch_expand_tiles(int BH, int Nt, int Nh, int Nw, int K, const int32_t* tile_idx, int32_t* idx_blocks,
+                               hipStream_t s) {
+  const long long total = (long long)BH * Nt * Nh * Nw * K * 4;
+  k_expand_tiles<<<(unsigned)((total + 255) / 256), 256, 0, s>>>(total, K, Nt, Nh, Nw, tile_idx, idx_blocks);
+  return hipGetLastError();
+}
+
 hipError_t launch_expand_lists(int BH, int Nc, int K, int m, const int32_t* idx, int32_t* idx_blocks, hipStream_t s) {
   const long long total = (long long)BH * Nc * m * K * m;
   k_expand_lists<<<(unsigned)((total + 255) / 256), 256, 0, s>>>(total, K, m, idx, idx_blocks);
@@ -252,6 +293,25 @@ hipError_t launch_coarse(int BH, int Nc, int d, int K, float scale, const float*
     k_coarse_rows<64><<<grid, 256, 0, s>>>(rows, Nc, K, sc, lse_c, idx, emit_idx);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   return gemm32(BH, Nc, d, Nc, 1.f, sc, ss, Nc, 1, vc, sx, d, 1, oc, sx, s);
+}
+
+// Top-K on the pooled coarse map: P [BH,Nc,Nc] (probabilities, as launch_coarse leaves them in its
+// score buffer) -> pooled map `ps` [BH,Ns,Ns] -> ascending tile lists [BH,Ns,K].
+hipError_t launch_pooled_select(int BH, int Nt, int Nh, int Nw, int K, const float* P, float* ps, int32_t* tile_idx,
+                                hipStream_t s) {
+  const int Ns = Nt * Nh * Nw / 4;
+  const long long total = (long long)BH * Ns * Ns;
+  k_pool_scores<<<(unsigned)((total + 255) / 256), 256, 0, s>>>(total, Nt, Nh, Nw, P, ps);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  const int rows = BH * Ns;
+  const unsigned grid = (unsigned)((rows + 3) / 4);
+  if (Ns <= 64) k_coarse_rows<1><<<grid, 256, 0, s>>>(rows, Ns, K, ps, nullptr, tile_idx, 1);
+  else if (Ns <= 128) k_coarse_rows<2><<<grid, 256, 0, s>>>(rows, Ns, K, ps, nullptr, tile_idx, 1);
+  else if (Ns <= 256) k_coarse_rows<4><<<grid, 256, 0, s>>>(rows, Ns, K, ps, nullptr, tile_idx, 1);
+  else if (Ns <= 512) k_coarse_rows<8><<<grid, 256, 0, s>>>(rows, Ns, K, ps, nullptr, tile_idx, 1);
+  else k_coarse_rows<16><<<grid, 256, 0, s>>>(rows, Ns, K, ps, nullptr, tile_idx, 1);
+  return hipGetLastError();
 }
 
 }  // namespace vsa

@@ -24,6 +24,21 @@ VSA_RULE int clamp_cube(int raw, int ncubes) { return raw < 0 ? 0 : (raw > ncube
 // out is clamped or skipped like any other entry.
 VSA_RULE int expanded_entry(int raw, int m, int u) { return (int)((unsigned)raw * (unsigned)m + (unsigned)u); }
 
+// Mismatched granularity: lists name tiles of (1,2,2) cubes.  Tile s = (st*Sh + sh)*Sw + sw (Sh = Nh/2,
+// Sw = Nw/2) holds cubes (st, 2sh+a, 2sw+b); x = 2a + b in 0..3.  `s` is clamped first, so that a
+// hostile entry still names a cube of the grid.
+VSA_RULE int tile_member_cube(int s, int x, int Nt, int Nh, int Nw) {
+  const int Sh = Nh / 2, Sw = Nw / 2, ns = Nt * Sh * Sw;
+  s = s < 0 ? 0 : (s > ns - 1 ? ns - 1 : s);
+  const int sw = s % Sw, sh = (s / Sw) % Sh, st = s / (Sw * Sh);
+  return (st * Nh + 2 * sh + (x >> 1)) * Nw + 2 * sw + (x & 1);
+}
+// ... and the tile a cube belongs to
+VSA_RULE int tile_of_cube(int c, int Nh, int Nw) {
+  const int cw = c % Nw, ch = (c / Nw) % Nh, ct = c / (Nw * Nh);
+  return (ct * (Nh / 2) + ch / 2) * (Nw / 2) + cw / 2;
+}
+
 // Slot of the list read by lane `lane` for 64-entry chunk `chunk` of a list of n entries.
 VSA_RULE int list_slot(int chunk, int lane, int n) {
   const int e = (chunk << 6) + lane;

@@ -50,8 +50,14 @@ int check_params(const vsa_params_t* p, Geo* g) {
   return VSA_OK;
 }
 
+// Mismatched granularity (VSA_FLAG_SELECT_POOLED_2X2): the lists name tiles of (1,2,2) cubes.
+bool pooled_select(const vsa_params_t* p) { return (p->flags & VSA_FLAG_SELECT_POOLED_2X2) != 0; }
+int list_rows(const vsa_params_t* p, const Geo& g) { return pooled_select(p) ? g.Nc / 4 : g.Nc; }  // rows of block_idx per (b,h)
+int blocks_per_entry(const vsa_params_t* p, const Geo& g) { return pooled_select(p) ? 4 : g.m; }    // 64-row blocks a list entry stands for
+
 int check_topk(const vsa_params_t* p, const Geo& g) {
-  return (p->topk < 1 || p->topk > g.Nc) ? VSA_ERR_BAD_ARG : VSA_OK;
+  if (pooled_select(p) && (g.m != 1 || g.Nh % 2 || g.Nw % 2)) return VSA_ERR_UNSUPPORTED;
+  return (p->topk < 1 || p->topk > list_rows(p, g)) ? VSA_ERR_BAD_ARG : VSA_OK;
 }
 
 bool misaligned(const void* ptr) { return ptr && ((uintptr_t)ptr & 15u); }
@@ -73,7 +79,7 @@ struct Carver {
 
 struct FwdWs {
   uint64_t* mask;
-  float *qc, *kc, *vc, *oc, *lse_c, *sc;
+  float *qc, *kc, *vc, *oc, *lse_c, *sc, *ps;
   int32_t *idx, *idx_blocks;
   size_t bytes;
 };
@@ -87,9 +93,11 @@ FwdWs carve_fwd(const vsa_params_t* p, const Geo& g, void* ws) {
   w.vc = c.take<float>(bh * g.Nc * p->d);
   w.oc = c.take<float>(bh * g.Nc * p->d);
   w.lse_c = c.take<float>(bh * g.Nc);
-  w.idx = c.take<int32_t>(bh * g.Nc * p->topk);
+  const size_t bpe = (size_t)blocks_per_entry(p, g), rows = (size_t)list_rows(p, g);
+  w.idx = c.take<int32_t>(bh * rows * p->topk);
   w.sc = c.take<float>(bh * g.Nc * g.Nc);
-  w.idx_blocks = g.m > 1 ? c.take<int32_t>(bh * g.Nb * p->topk * g.m) : nullptr;
+  w.idx_blocks = bpe > 1 ? c.take<int32_t>(bh * g.Nb * p->topk * bpe) : nullptr;
+  w.ps = pooled_select(p) ? c.take<float>(bh * rows * rows) : nullptr;
   w.bytes = c.used;
   return w;
 }
@@ -110,7 +118,7 @@ struct BwdWs {
 // work is spread evenly (256 units), but not so short that start-up and the extra pass over the
 // partial sums outweigh the gain; the map scan lengthens it per (b, h) until the slots suffice.
 void split_plan(const vsa_params_t* p, const Geo& g, int* seg, int* cap) {
-  const long long kb = (long long)p->topk * g.m;  // list length in blocks
+  const long long kb = (long long)p->topk * blocks_per_entry(p, g);  // list length in blocks
   const long long entries = (long long)p->B * p->H * g.Nb * kb;
   long long s = entries / 512;
   if (s > 4 * kb) s = 4 * kb;
@@ -123,7 +131,7 @@ BwdWs carve_bwd(const vsa_params_t* p, const Geo& g, void* ws) {
   Carver c(ws);
   size_t bh = (size_t)p->B * p->H;
   BwdWs w;
-  const size_t kb = (size_t)p->topk * g.m;
+  const size_t kb = (size_t)p->topk * blocks_per_entry(p, g);
   w.mask = c.take<uint64_t>(g.Nb);
   w.qc = c.take<float>(bh * g.Nc * p->d);
   w.kc = c.take<float>(bh * g.Nc * p->d);
@@ -140,7 +148,7 @@ BwdWs carve_bwd(const vsa_params_t* p, const Geo& g, void* ws) {
   w.row_ptr = c.take<int32_t>(bh * (g.Nb + 1));
   w.col = c.take<int32_t>(bh * g.Nb * kb);
   w.bits = c.take<uint32_t>(bh * g.Nb * ((g.Nb + 31) / 32));
-  w.idx_blocks = g.m > 1 ? c.take<int32_t>(bh * g.Nb * kb) : nullptr;
+  w.idx_blocks = blocks_per_entry(p, g) > 1 ? c.take<int32_t>(bh * g.Nb * kb) : nullptr;
   split_plan(p, g, &w.seg, &w.cap);
   w.order = c.take<int32_t>(4 * bh * (g.Nb + w.cap));  // (block, run begin, run end, slot) per dK/dV workgroup
   w.split = c.take<int32_t>(4 * bh * (w.cap / 2 + 1));
@@ -208,14 +216,21 @@ int enqueue_forward(const vsa_params_t* p, const Geo& g, const void* q, const vo
   int32_t* idx = block_idx ? block_idx : w.idx;
 
   VSA_TRY("pool", vsa::launch_pool(g, BH, p->d, w.mask, q, k, v, w.qc, w.kc, w.vc, s));
-  VSA_TRY("coarse", vsa::launch_coarse(BH, g.Nc, p->d, p->topk, scale, w.qc, w.kc, w.vc, w.sc, oc, lse_c, idx, given ? 0 : 1, (p->flags & VSA_FLAG_COARSE_FUSED) ? 1 : 0, s));
-  // the fine stage works on 64-row blocks: a cube of m blocks contributes m list entries
+  const bool pooled = pooled_select(p);
+  VSA_TRY("coarse", vsa::launch_coarse(BH, g.Nc, p->d, p->topk, scale, w.qc, w.kc, w.vc, w.sc, oc, lse_c, idx, (given || pooled) ? 0 : 1,
+                            (!pooled && (p->flags & VSA_FLAG_COARSE_FUSED)) ? 1 : 0, s));
+  // the fine stage works on 64-row blocks: a cube of m blocks contributes m list entries, a tile of
+  // (1,2,2) cubes its four cubes
   const int32_t* lists = idx;
-  if (g.m > 1) {
+  if (pooled) {
+    if (!given) VSA_TRY("pooled_select", vsa::launch_pooled_select(BH, g.Nt, g.Nh, g.Nw, p->topk, w.sc, w.ps, idx, s));
+    VSA_TRY("expand_lists", vsa::launch_expand_tiles(BH, g.Nt, g.Nh, g.Nw, p->topk, idx, w.idx_blocks, s));
+    lists = w.idx_blocks;
+  } else if (g.m > 1) {
     VSA_TRY("expand_lists", vsa::launch_expand_lists(BH, g.Nc, p->topk, g.m, idx, w.idx_blocks, s));
     lists = w.idx_blocks;
   }
-  VSA_TRY("fine_fwd", vsa::launch_fine_fwd(BH, g.Nb, p->d, p->topk * g.m, scale, q, k, v, gate_c, gate_f, lists, oc, w.mask, out,
+  VSA_TRY("fine_fwd", vsa::launch_fine_fwd(BH, g.Nb, p->d, p->topk * blocks_per_entry(p, g), scale, q, k, v, gate_c, gate_f, lists, oc, w.mask, out,
                                out_fine, lse_fine, p->H, (p->flags & VSA_FLAG_OUT_TOKEN_MAJOR) ? 1 : 0, g.m, s));
   return VSA_OK;
 }
@@ -330,8 +345,11 @@ int vsa_backward(const vsa_params_t* p, const void* q, const void* k, const void
   VSA_TRY("coarse_bwd", vsa::launch_coarse_bwd(BH, g.Nc, p->d, scale, w.qc, w.kc, w.vc, lse_coarse, w.doc, w.ac, w.dsc, w.dqc, w.dkc,
                                  w.dvc, s));
   const int32_t* lists = block_idx;
-  const int kb = p->topk * g.m;
-  if (g.m > 1) {
+  const int kb = p->topk * blocks_per_entry(p, g);
+  if (pooled_select(p)) {
+    VSA_TRY("expand_lists", vsa::launch_expand_tiles(BH, g.Nt, g.Nh, g.Nw, p->topk, block_idx, w.idx_blocks, s));
+    lists = w.idx_blocks;
+  } else if (g.m > 1) {
     VSA_TRY("expand_lists", vsa::launch_expand_lists(BH, g.Nc, p->topk, g.m, block_idx, w.idx_blocks, s));
     lists = w.idx_blocks;
   }
@@ -350,7 +368,7 @@ int vsa_host_replay_lists(const vsa_params_t* p, const int32_t* host_block_idx, 
   if ((rc = check_topk(p, g)) != VSA_OK) return rc;
   if (!host_block_idx) return VSA_ERR_NULL;
   // the kernels see lists of 64-row blocks: a cube of m blocks expands to m entries
-  const int Nc = g.Nb, K = p->topk * g.m;
+  const int Nc = g.Nb, bpe = blocks_per_entry(p, g), K = p->topk * bpe;
   int seg_min, cap;
   split_plan(p, g, &seg_min, &cap);
   std::vector<int32_t> expanded((size_t)Nc * K);
@@ -361,7 +379,10 @@ int vsa_host_replay_lists(const vsa_params_t* p, const int32_t* host_block_idx, 
     for (int row = 0; row < Nc; ++row)
       for (int e = 0; e < K; ++e)
         expanded[(size_t)row * K + e] =
-            vsa::expanded_entry(host_block_idx[(bh * g.Nc + row / g.m) * p->topk + e / g.m], g.m, e % g.m);
+            pooled_select(p)
+                ? vsa::tile_member_cube(host_block_idx[(bh * (g.Nc / 4) + vsa::tile_of_cube(row, g.Nh, g.Nw)) * p->topk + e / 4],
+                                        e % 4, g.Nt, g.Nh, g.Nw)
+                : vsa::expanded_entry(host_block_idx[(bh * g.Nc + row / g.m) * p->topk + e / g.m], g.m, e % g.m);
     const int32_t* lists = expanded.data();
     // forward and dQ pass: every lane of every 64-entry chunk reads a list slot, then fetches a cube
     for (int c = 0; c < Nc; ++c)

@@ -18,6 +18,12 @@ hipError_t launch_fine_fwd(int BH, int Nc, int d, int K, float scale, const void
                            int m_blocks, hipStream_t s);
 // lists of cubes -> lists of 64-row blocks, for cubes of m blocks: every block of query cube c gets
 // the m blocks of each of the cube's K key cubes, ascending ([BH,Nc,K] -> [BH,Nc*m,K*m])
+// mismatched granularity: top-K on the coarse map pooled over (1,2,2) cubes, and its lists of tiles
+// turned into lists of cubes for every query cube ([BH,Ns,K] -> [BH,Nc,4K])
+hipError_t launch_pooled_select(int BH, int Nt, int Nh, int Nw, int K, const float* P, float* ps, int32_t* tile_idx,
+                                hipStream_t s);
+hipError_t launch_expand_tiles(int BH, int Nt, int Nh, int Nw, int K, const int32_t* tile_idx, int32_t* idx_blocks,
+                               hipStream_t s);
 hipError_t launch_expand_lists(int BH, int Nc, int K, int m, const int32_t* idx, int32_t* idx_blocks, hipStream_t s);
 
 // backward

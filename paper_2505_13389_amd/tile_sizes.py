@@ -1,6 +1,7 @@
 """Throughput against tile size (the "TFLOPS" column of the tile-size ablation, Sec. 3.2): the same
 16x32x32 latent (16384 tokens), 87.5 % tile sparsity, with cubes of 64, 128 and 256 tokens, i.e.
-top-K = 32 of 256, 16 of 128 and 8 of 64 cubes.  Forward and forward+backward, effective TFLOP/s on
+top-K = 32 of 256, 16 of 128 and 8 of 64 cubes, and the mismatched setting of that section (coarse
+stage on 64-token cubes, fine stage on 256-token tiles, top-K = 8 of 64 tiles on the pooled map).  Forward and forward+backward, effective TFLOP/s on
 the selected blocks.  Synthetic i.i.d. inputs; a measurement aid that calls the library exactly as
 the benchmark does.
 
@@ -9,7 +10,7 @@ the benchmark does.
 import argparse
 import json
 
-CUBES = [((4, 4, 4), 32), ((4, 4, 8), 16), ((4, 8, 8), 8)]
+CUBES = [((4, 4, 4), 32, False), ((4, 4, 8), 16, False), ((4, 8, 8), 8, False), ((4, 4, 4), 8, True)]
 
 
 def main():
@@ -37,8 +38,9 @@ def main():
         return float(np.median(ts))
 
     rows = []
-    for cube, K in CUBES:
-        pb = vsa.Problem(1, args.heads, 16, 32, 32, args.dim, K, cube=cube)
+    for cube, K, mismatched in CUBES:
+        pb = vsa.Problem(1, args.heads, 16, 32, 32, args.dim, K, cube=cube,
+                         flags=vsa.VSA_FLAG_SELECT_POOLED_2X2 if mismatched else 0)
         Np, Nc = vsa.vsa_padded_tokens(pb)
         g = torch.Generator(device="cuda")
         g.manual_seed(3)
@@ -52,9 +54,9 @@ def main():
             buf.backward(q, k, v, gc, gf, do, workspace_kept=True)
 
         tf, tb = timed(lambda: buf.forward(q, k, v, gc, gf)), timed(both)
-        V = cube[0] * cube[1] * cube[2]
+        V = cube[0] * cube[1] * cube[2] * (4 if mismatched else 1)  # tokens per fine tile
         fl = 4.0 * Np * K * V * args.dim * args.heads
-        line = {"tile": V, "cube": list(cube), "Nc": Nc, "topk": K, "sparsity": 1.0 - K / Nc, "fwd_ms": round(tf, 4),
+        line = {"tile": V, "coarse_cube": list(cube), "tiles": Np // V, "topk": K, "sparsity": 1.0 - K * V / Np, "fwd_ms": round(tf, 4),
                 "fwd_bwd_ms": round(tb, 4), "fwd_tflops": round(fl / tf / 1e9, 1),
                 "fwd_bwd_tflops": round(3.5 * fl / tb / 1e9, 1)}
         print(json.dumps(line), flush=True)

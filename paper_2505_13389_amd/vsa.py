@@ -18,6 +18,7 @@ VSA_FLAG_RASTER_BLHD = 2
 VSA_FLAG_WORKSPACE_KEPT = 4
 VSA_FLAG_COARSE_FUSED = 8
 VSA_FLAG_OUT_TOKEN_MAJOR = 16
+VSA_FLAG_SELECT_POOLED_2X2 = 32
 STATUS = {0: "VSA_OK", -1: "VSA_ERR_NULL", -2: "VSA_ERR_BAD_ARG", -3: "VSA_ERR_UNSUPPORTED", -4: "VSA_ERR_ALIGN",
           -5: "VSA_ERR_WORKSPACE", -6: "VSA_ERR_HIP", -7: "VSA_ERR_SCRATCH_LIMIT"}
 EXPORTS = ["vsa_padded_tokens", "vsa_workspace_bytes", "vsa_tile_permute", "vsa_forward", "vsa_backward",
@@ -175,7 +176,8 @@ class Buffers:
         self.lse_fine = torch.empty((pb.B, pb.H, Np), **f32)
         self.out_coarse = torch.empty((pb.B, pb.H, Nc, pb.d), **f32)
         self.lse_coarse = torch.empty((pb.B, pb.H, Nc), **f32)
-        self.block_idx = torch.empty((pb.B, pb.H, Nc, pb.topk), dtype=torch.int32, device=device)
+        rows = Nc // 4 if pb.flags & VSA_FLAG_SELECT_POOLED_2X2 else Nc  # that flag's lists are per tile of 4 cubes
+        self.block_idx = torch.empty((pb.B, pb.H, rows, pb.topk), dtype=torch.int32, device=device)
         nbytes = max(vsa_workspace_bytes(pb, False), vsa_workspace_bytes(pb, True) if backward else 0)
         self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=device)
         if backward:

@@ -70,6 +70,22 @@ def test_null_and_topk_validation_happens_before_any_launch(lib):
     assert vsa.vsa_workspace_bytes(vsa.Problem(1, 2, 8, 16, 16, 64, 33), False) == 0
 
 
+def test_list_index_rules_with_tile_lists(lib):
+    """Mismatched granularity: the lists name tiles of (1,2,2) cubes; hostile tile lists stay in bounds too."""
+    import dataclasses
+    import numpy as np
+    pb = dataclasses.replace(vsa.Problem(1, 2, 8, 16, 32, 64, 5), flags=vsa.VSA_FLAG_SELECT_POOLED_2X2)
+    _, Nc = vsa.vsa_padded_tokens(pb)
+    Ns = Nc // 4
+    rng = np.random.Generator(np.random.PCG64(3))
+    hostile = rng.integers(-5, Ns + 5, size=(1, 2, Ns, 5), dtype=np.int64).astype(np.int32)
+    hostile[0, 0, 0, :] = np.iinfo(np.int32).min
+    for lists in (hostile, np.broadcast_to(np.arange(5, dtype=np.int32), (1, 2, Ns, 5))):
+        rc, rep = vsa.vsa_host_replay_lists(pb, lists)
+        assert rc == 0 and rep["violations"] == 0, rep
+        assert rep["longest_list"] <= Nc and rep["col_entries"] <= Nc * 20
+
+
 def test_status_strings(lib):
     seen = set()
     for s in range(0, -8, -1):

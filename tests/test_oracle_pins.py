@@ -381,6 +381,42 @@ def test_block_mass_is_the_dense_attention_matrix_summed_over_cubes():
     assert np.abs(orc.block_mass(g1, q1, k1) - p1 / p1.sum(-1, keepdims=True)).max() < 1e-12
 
 
+# ----------------------------------------------------------------------------- mismatched granularity
+def test_pooled_selection_is_topk_of_the_block_averaged_attention_map():
+    """[Sec. 3.2] numpy restatement: softmax of the pooled logits, mean over the 2x2 groups of cubes on
+    both axes by reshape, stable argsort; the expanded cube lists hold exactly the four cubes of each
+    selected tile.  With q = 0 the map is flat and the first K tiles win (ties to the lower index)."""
+    g = Grid(8, 14, 15, 4, 4, 4)  # 2 x 4 x 4 cubes, ragged in h and w
+    valid, cnt = orc.valid_mask(g)
+    Np, Nc, Bk = g.dims()
+    d, K = 16, 3
+    Nt, Nh, Nw = 2, 4, 4
+    q, k = rand(1, 2, Np, d), rand(1, 2, Np, d)
+    got = orc.select_pooled(g, q, k, K)
+    for h in range(2):
+        pool = lambda x: (x[0, h] * valid[:, None]).reshape(Nc, Bk, d).sum(1) / cnt[:, None]
+        s = pool(q) @ pool(k).T / np.sqrt(d)
+        p = np.exp(s - s.max(-1, keepdims=True))
+        p /= p.sum(-1, keepdims=True)
+        ps = p.reshape(Nt, Nh // 2, 2, Nw // 2, 2, Nt, Nh // 2, 2, Nw // 2, 2).mean(axis=(2, 4, 7, 9)).reshape(8, 8)
+        assert np.abs(got["pooled"][0, h] - ps).max() < 1e-14
+        want = np.sort(np.argsort(-ps, axis=-1, kind="stable")[:, :K], axis=-1)
+        assert np.array_equal(got["tile_idx"][0, h], want)
+        for c in range(Nc):
+            ct, ch, cw = c // (Nh * Nw), (c // Nw) % Nh, c % Nw
+            sq = (ct * (Nh // 2) + ch // 2) * (Nw // 2) + cw // 2
+            cubes = set()
+            for s_ in want[sq]:
+                st, sh, sw = s_ // 4, (s_ // 2) % 2, s_ % 2
+                cubes |= {(st * Nh + 2 * sh + a) * Nw + 2 * sw + b for a in (0, 1) for b in (0, 1)}
+            assert set(got["cube_idx"][0, h, c]) == cubes and len(cubes) == 4 * K
+            assert (np.diff(got["cube_idx"][0, h, c]) > 0).all()
+    flat = orc.select_pooled(g, np.zeros_like(q), k, K)
+    assert np.array_equal(flat["tile_idx"], np.broadcast_to(np.arange(K, dtype=np.int32), flat["tile_idx"].shape))
+    with pytest.raises(ValueError):
+        orc.select_pooled(Grid(8, 12, 16, 4, 4, 4), rand(1, 1, 1536, 8), rand(1, 1, 1536, 8), 2)  # 3 cubes along h
+
+
 def test_paper_anchors():
     path = os.path.join(os.path.dirname(__file__), "golden", "paper_anchors.txt")
     gold = {}
