@@ -46,6 +46,7 @@ def parse():
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--no-configs", action="store_true", help="skip the other named configurations")
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--heads", type=int, default=0, help="override the workload's head count (experiments)")
     return ap.parse_args()
 
 
@@ -177,6 +178,8 @@ def main():
     vsa.lib()  # fail loudly if the HIP library is missing
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     wl = WORKLOADS[args.workload]
+    if args.heads > 0:
+        wl = Workload(f"{wl.name}_h{args.heads}", wl.B, args.heads, wl.T, wl.Hh, wl.W, wl.d, wl.topk, wl.cube, wl.planted)
     dev = device_inputs(wl, args.seed, torch)
     pb = problem_of(wl)
     buf = vsa.Buffers(pb)
