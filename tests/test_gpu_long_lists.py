@@ -67,6 +67,15 @@ def test_sweep_shape_topk128_with_sinks(vsa, d, H, b, h):
     assert (indeg > 160).sum() >= 8 and (indeg < 100).sum() >= 8, "in-degrees must spread to both sides of 128"
 
 
+@pytest.mark.parametrize("cube,topk", [((4, 4, 8), 16), ((4, 8, 8), 8)])
+def test_mid_shape_with_larger_cubes(vsa, cube, topk):
+    """The Mid latent (16x32x32, 12 heads, d=128, 87.5 % sparse) with 128- and 256-token cubes (Sec. 3.2
+    tile sizes), as tile_sizes.py times it: one head of the 12-head launch against the oracle."""
+    wl = Workload("mid_big_cubes", 1, 12, 16, 32, 32, 128, topk, cube=cube)
+    dev = synth.device_iid_inputs(wl, seed=8, tiled_rows=wl.Np)
+    compare_slice(vsa, wl, dev, 0, 7, own_selection_rows_equal=0.85)
+
+
 def test_wan14b_head_topk180_backward(vsa):
     wl = Workload("wan14b_two_heads", 1, 2, 21, 45, 80, 128, 180)
     dev = synth.device_iid_inputs(wl, seed=7, tiled_rows=wl.Np)
