@@ -108,7 +108,8 @@ def mfma_rate(torch, vsa):
 
 def other_configs(torch, vsa, WORKLOADS, Workload, time_steps):
     """The other named configurations, through the same entry points (inputs drawn on the device):
-    mid forward+backward, the Wan-14B-shaped forward at top-K 180 and at top-K = all 1440 cubes."""
+    mid forward+backward, the Wan-14B-shaped forward and forward+backward at top-K 180, and its forward at
+    top-K = all 1440 cubes."""
     from paper_2505_13389_amd import synth
     out = {}
 
@@ -132,6 +133,7 @@ def other_configs(torch, vsa, WORKLOADS, Workload, time_steps):
     run("mid_fwd_bwd", WORKLOADS["mid"], True, 20)
     w14 = WORKLOADS["wan14b"]
     run("wan14b_fwd", w14, False, 5)
+    run("wan14b_fwd_bwd", w14, True, 3)
     run("wan14b_dense_fwd", Workload("wan14b_dense", w14.B, w14.H, w14.T, w14.Hh, w14.W, w14.d, w14.Nc), False, 2)
     out["wan14b_fwd_speedup_vs_dense"] = round(out["wan14b_dense_fwd"]["ms"] / out["wan14b_fwd"]["ms"], 2)
     return out

@@ -380,11 +380,12 @@ def test_error_paths_return_status_and_launch_nothing(vsa):
 
 
 # ------------------------------------------------------------------------------ HIP graph replay
-def test_forward_backward_replay_from_hip_graph(vsa):
+@pytest.mark.parametrize("name", ["pad128", "cube128_4x4x8"])
+def test_forward_backward_replay_from_hip_graph(vsa, name):
     """The entry points only enqueue kernels (no allocation, no synchronisation, no memset nodes), so
     a caller may capture them: every replay must reproduce the eager result bit for bit."""
     import torch
-    wl = SMALL["pad128"]
+    wl = SMALL[name]
     dev = to_dev(tiled_bits(wl, seed=3))
     buf = vsa.Buffers(problem_of(wl), backward=True)
     args = (dev["q"], dev["k"], dev["v"], dev["gate_c"], dev["gate_f"])
