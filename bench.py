@@ -106,6 +106,22 @@ def mfma_rate(torch, vsa):
     return fl / (ms * 1e-3) / 1e12
 
 
+def hbm_rates(wl, buf, kern, ms_perm):
+    tensor = wl.B * wl.H * buf.Np * wl.d * 2           # one tiled bf16 tensor
+    raster = wl.B * wl.H * wl.L * wl.d * 2             # one raster bf16 tensor
+    pooled = wl.B * wl.H * buf.Nc * wl.d * 4
+    rows = wl.B * wl.H * buf.Np
+    steps = {"pool": (3 * tensor + 3 * pooled, kern.get("pool")),
+             "bwd_pre": (4 * tensor + 3 * tensor + rows * (4 + 8 + 16) + 2 * pooled, kern.get("bwd_pre")),
+             "tile_permute_12_tensors": (12 * (tensor + raster), ms_perm)}
+    out = {}
+    for name, (nbytes, ms_) in steps.items():
+        if ms_:
+            gbs = nbytes / (ms_ * 1e-3) / 1e9
+            out[name] = {"bytes": nbytes, "ms": round(ms_, 4), "GBps": round(gbs, 1), "frac_of_hbm_peak": round(gbs / PEAK_HBM_GBS, 3)}
+    return out
+
+
 def other_configs(torch, vsa, WORKLOADS, Workload, time_steps):
     """The other named configurations, through the same entry points (inputs drawn on the device):
     mid forward+backward, the Wan-14B-shaped forward and forward+backward at top-K 180, and its forward at
@@ -293,6 +309,8 @@ def main():
         "ms_per_step_profiled": round(ms_profiled, 4),
         "kernel_ms": {n: round(t, 4) for n, t in sorted(kern.items(), key=lambda kv: -kv[1])},
         "roofline": roofline,
+        # the HBM-bound steps: algorithmic bytes (every tensor once) / launch time, against 8 TB/s
+        "hbm_bound_kernels": hbm_rates(wl, buf, kern, ms_perm),
     }
     if not args.no_configs:
         del buf, dev
