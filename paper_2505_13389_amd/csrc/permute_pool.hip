@@ -4,51 +4,76 @@
 
 namespace vsa {
 
-// One thread per 16-byte chunk of a destination row.
-// Forward: destination = tiled row; its source is the raster row of the same (t,h,w), or
-// zeros for a pad slot.  Inverse: destination = raster row.  (Sec. 2.2 index equation.)
-// H > 0: the raster tensor is [B, L, H, d] (token-major); H == 0: [B, H, L, d].
+// One workgroup per 64 destination rows of one (b, h).  The first wavefront works out, one row per
+// lane, where each destination row comes from (the index arithmetic of the Sec. 2.2 equation, with
+// its integer divisions, once per row instead of once per 16-byte chunk); then all 256 threads copy,
+// several 16-byte chunks in flight per thread.
+// Forward: destination = tiled row; its source is the raster row of the same (t,h,w), or zeros for
+// a pad slot.  Inverse: destination = raster row.  H > 0: the raster tensor is [B, L, H, d]
+// (token-major); H == 0: [B, H, L, d].
 template <bool kInverse>
-__global__ __launch_bounds__(256) void k_tile_permute(Geo g, int BH, int H, int chunks_per_row,
+__global__ __launch_bounds__(256) void k_tile_permute(Geo g, int H, int chunks_per_row,
                                                       const uint4* __restrict__ src, uint4* __restrict__ dst) {
+  __shared__ long long from[kTile], to[kTile];  // row numbers in units of rows; from < 0: a pad slot (zeros)
   const long long rows_dst = kInverse ? (long long)g.L : g.Np;
-  const long long total = (long long)BH * rows_dst * chunks_per_row;
-  long long gid = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-  if (gid >= total) return;
-  int ch = (int)(gid % chunks_per_row);
-  long long row = gid / chunks_per_row;
-  int n = (int)(row % rows_dst);
-  long long bh = row / rows_dst;
-  if (!kInverse) {
-    int c = n / g.V, in = n % g.V;
-    int cw = c % g.Nw, chh = (c / g.Nw) % g.Nh, ct = c / (g.Nw * g.Nh);
-    int pw = in % g.Cw, ph = (in / g.Cw) % g.Ch, pt = in / (g.Cw * g.Ch);
-    int t = ct * g.Ct + pt, h = chh * g.Ch + ph, w = cw * g.Cw + pw;
-    uint4 val = make_uint4(0, 0, 0, 0);
-    if (t < g.T && h < g.Hh && w < g.W) {
-      long long nr = ((long long)t * g.Hh + h) * g.W + w;
-      const long long rr = H > 0 ? ((bh / H) * g.L + nr) * H + bh % H : bh * g.L + nr;
-      val = src[rr * chunks_per_row + ch];
+  const long long bh = blockIdx.y;
+  const long long n0 = (long long)blockIdx.x * kTile;
+  if (threadIdx.x < kTile) {
+    const long long nn = n0 + threadIdx.x;
+    long long f = -1, t_ = -1;
+    if (nn < rows_dst) {
+      const int n = (int)nn;
+      if (!kInverse) {
+        const int c = n / g.V, in = n % g.V;
+        const int cw = c % g.Nw, chh = (c / g.Nw) % g.Nh, ct = c / (g.Nw * g.Nh);
+        const int pw = in % g.Cw, ph = (in / g.Cw) % g.Ch, pt = in / (g.Cw * g.Ch);
+        const int t = ct * g.Ct + pt, h = chh * g.Ch + ph, w = cw * g.Cw + pw;
+        t_ = bh * g.Np + n;
+        if (t < g.T && h < g.Hh && w < g.W) {
+          const long long nr = ((long long)t * g.Hh + h) * g.W + w;
+          f = H > 0 ? ((bh / H) * g.L + nr) * H + bh % H : bh * g.L + nr;
+        }
+      } else {
+        const int w = n % g.W, h = (n / g.W) % g.Hh, t = n / (g.W * g.Hh);
+        const long long c = ((long long)(t / g.Ct) * g.Nh + (h / g.Ch)) * g.Nw + (w / g.Cw);
+        const int in = ((t % g.Ct) * g.Ch + (h % g.Ch)) * g.Cw + (w % g.Cw);
+        t_ = H > 0 ? ((bh / H) * g.L + n) * H + bh % H : bh * g.L + n;
+        f = bh * g.Np + c * g.V + in;
+      }
     }
-    dst[gid] = val;
-  } else {
-    int w = n % g.W, h = (n / g.W) % g.Hh, t = n / (g.W * g.Hh);
-    long long c = ((long long)(t / g.Ct) * g.Nh + (h / g.Ch)) * g.Nw + (w / g.Cw);
-    int in = ((t % g.Ct) * g.Ch + (h % g.Ch)) * g.Cw + (w % g.Cw);
-    const long long rr = H > 0 ? ((bh / H) * g.L + n) * H + bh % H : bh * g.L + n;
-    dst[rr * chunks_per_row + ch] = src[(bh * g.Np + c * g.V + in) * chunks_per_row + ch];
+    from[threadIdx.x] = f;
+    to[threadIdx.x] = t_;
+  }
+  __syncthreads();
+  const int items = kTile * chunks_per_row;
+  for (int i0 = 0; i0 < items; i0 += 4 * 256) {
+    uint4 val[4];
+    long long dsta[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int item = i0 + u * 256 + threadIdx.x, r = item / chunks_per_row, ch = item % chunks_per_row;
+      dsta[u] = -1;
+      val[u] = make_uint4(0, 0, 0, 0);
+      if (item < items && to[r] >= 0) {
+        dsta[u] = to[r] * chunks_per_row + ch;
+        if (from[r] >= 0) val[u] = src[from[r] * chunks_per_row + ch];
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+      if (dsta[u] >= 0) dst[dsta[u]] = val[u];
   }
 }
 
 hipError_t launch_tile_permute(const Geo& g, int BH, int H_blhd, int d, const void* src, void* dst, bool inverse,
                                hipStream_t s) {
-  int cpr = d / 8;
-  long long total = (long long)BH * (inverse ? (long long)g.L : g.Np) * cpr;
-  unsigned blocks = (unsigned)((total + 255) / 256);
+  const int cpr = d / 8;
+  const long long rows_dst = inverse ? (long long)g.L : g.Np;
+  dim3 grid((unsigned)((rows_dst + kTile - 1) / kTile), (unsigned)BH);
   if (inverse)
-    k_tile_permute<true><<<blocks, 256, 0, s>>>(g, BH, H_blhd, cpr, (const uint4*)src, (uint4*)dst);
+    k_tile_permute<true><<<grid, 256, 0, s>>>(g, H_blhd, cpr, (const uint4*)src, (uint4*)dst);
   else
-    k_tile_permute<false><<<blocks, 256, 0, s>>>(g, BH, H_blhd, cpr, (const uint4*)src, (uint4*)dst);
+    k_tile_permute<false><<<grid, 256, 0, s>>>(g, H_blhd, cpr, (const uint4*)src, (uint4*)dst);
   return hipGetLastError();
 }
 
