@@ -152,6 +152,36 @@ def other_configs(torch, vsa, WORKLOADS, Workload, time_steps):
     run("wan14b_fwd_bwd", w14, True, 3)
     run("wan14b_dense_fwd", Workload("wan14b_dense", w14.B, w14.H, w14.T, w14.Hh, w14.W, w14.d, w14.Nc), False, 2)
     out["wan14b_fwd_speedup_vs_dense"] = round(out["wan14b_dense_fwd"]["ms"] / out["wan14b_fwd"]["ms"], 2)
+    # the pretraining sweep shape (B=2, 256 cubes), planted-locality inputs drawn on the host, at two
+    # sparsities and both head dims, with the dense setting of the same shape as the reference
+    for H, d in ((16, 128), (8, 64)):
+        base = Workload(f"sweep_h{H}_d{d}", 2, H, 16, 32, 32, d, 32, planted=True)
+        raw = synth.planted_inputs(base, 0)
+        pb0 = vsa.problem_of(base)
+        dev = {}
+        for n, b in raw.items():
+            src = torch.from_numpy(b.view("int16")).cuda().view(torch.bfloat16)
+            dev[n] = torch.empty((base.B, base.H, base.Np, base.d), dtype=torch.bfloat16, device="cuda")
+            vsa.vsa_tile_permute(pb0, src, dev[n])
+        del raw
+        a = (dev["q"], dev["k"], dev["v"], dev["gate_c"], dev["gate_f"])
+        ms_by_k = {}
+        for K in (32, 128, base.Nc):
+            buf = vsa.Buffers(vsa.problem_of(base, topk=K))
+
+            def step():
+                buf.forward(*a)
+                buf.backward(*a, dev["dout"], workspace_kept=True)
+            ms_by_k[K] = time_steps(step, 10 if K < base.Nc else 3, 2, torch)
+            del buf
+        for K in (32, 128):
+            fl = 3.5 * 4.0 * base.Np * K * 64 * d * H * 2
+            out[f"sweep_h{H}_d{d}_k{K}_fwd_bwd"] = {
+                "ms": round(ms_by_k[K], 4), "tflops": round(fl / (ms_by_k[K] * 1e-3) / 1e12, 1),
+                "speedup_vs_dense": round(ms_by_k[base.Nc] / ms_by_k[K], 2), "ideal_speedup": base.Nc / K,
+                "what": f"forward+backward, B=2 H={H} Nc=256 d={d} topk={K}, planted locality"}
+        del dev
+        torch.cuda.empty_cache()
     return out
 
 
