@@ -19,16 +19,34 @@ __device__ __forceinline__ uint32_t sortable_key(float s) {
   uint32_t b = __float_as_uint(s);
   return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
 }
+// Reductions over the 64 lanes of a wavefront, result in every lane: four data-parallel-primitive
+// steps inside each row of 16 lanes (quad swaps, half-row mirror, row mirror: register-to-register,
+// no trip through the LDS permute path), then the four row results are combined through scalar
+// registers.  The order of the additions is fixed.
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_move(uint32_t x) {
+  return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, CTRL, 0xF, 0xF, true);
+}
+template <class Op>
+__device__ __forceinline__ uint32_t wave_reduce_bits(uint32_t x, Op op) {
+  x = op(x, dpp_move<0xB1>(x));   // quad_perm [1,0,3,2]
+  x = op(x, dpp_move<0x4E>(x));   // quad_perm [2,3,0,1]
+  x = op(x, dpp_move<0x141>(x));  // row_half_mirror
+  x = op(x, dpp_move<0x140>(x));  // row_mirror
+  const uint32_t a = __builtin_amdgcn_readlane(x, 0), b = __builtin_amdgcn_readlane(x, 16);
+  const uint32_t c = __builtin_amdgcn_readlane(x, 32), d = __builtin_amdgcn_readlane(x, 48);
+  return op(op(a, b), op(c, d));
+}
 __device__ __forceinline__ float wave_max(float x) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) x = fmaxf(x, __shfl_xor(x, o));
-  return x;
+  return __uint_as_float(wave_reduce_bits(__float_as_uint(x), [](uint32_t p, uint32_t q) {
+    return __float_as_uint(fmaxf(__uint_as_float(p), __uint_as_float(q))); }));
 }
 __device__ __forceinline__ float wave_sum(float x) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o);
-  return x;
+  return __uint_as_float(wave_reduce_bits(__float_as_uint(x), [](uint32_t p, uint32_t q) {
+    return __float_as_uint(__uint_as_float(p) + __uint_as_float(q)); }));
 }
+__device__ __forceinline__ uint32_t wave_umin(uint32_t x) { return wave_reduce_bits(x, [](uint32_t p, uint32_t q) { return min(p, q); }); }
+__device__ __forceinline__ uint32_t wave_umax(uint32_t x) { return wave_reduce_bits(x, [](uint32_t p, uint32_t q) { return max(p, q); }); }
 
 // One row of the score matrix worked off by one wavefront; lane j holds logits j, j+64, ... (NCH per
 // lane).  `srow` may point into global memory or into LDS.  Writes the row's probabilities back over
@@ -71,11 +89,8 @@ __device__ __forceinline__ void coarse_row(float* srow, int Nc, int K, float* ls
       if (valid) kmin = min(kmin, key[ch]);
       kmax = max(kmax, key[ch]);
     }
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) {
-      kmin = min(kmin, (uint32_t)__shfl_xor((int)kmin, o));
-      kmax = max(kmax, (uint32_t)__shfl_xor((int)kmax, o));
-    }
+    kmin = wave_umin(kmin);
+    kmax = wave_umax(kmax);
     auto count_ge = [&](uint32_t x) {
       int cnt = 0;
 #pragma unroll
@@ -83,7 +98,7 @@ __device__ __forceinline__ void coarse_row(float* srow, int Nc, int K, float* ls
         if (ch < nch) cnt += __popcll(__ballot(key[ch] >= x));
       return cnt;
     };
-    unsigned long long lo = __builtin_amdgcn_readfirstlane(kmin), hi = (unsigned long long)__builtin_amdgcn_readfirstlane(kmax) + 1ull;
+    unsigned long long lo = kmin, hi = (unsigned long long)kmax + 1ull;
     uint32_t T = (uint32_t)lo;
     while (hi - lo > 1ull) {
       const uint32_t mid = (uint32_t)((lo + hi) >> 1);
