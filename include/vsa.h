@@ -57,11 +57,12 @@ typedef enum {
                                       call (same parameters, same q, k, v) was given, and nothing has
                                       written to it since: the pooled tensors it still holds are used
                                       instead of being computed again.  Size it for the backward. */
-#define VSA_FLAG_COARSE_FUSED 8u  /* vsa_forward, Nc <= 256 only (ignored above): run the coarse stage as ONE
-                                    launch that keeps the score block in LDS (Sec. 2.4, App. D) instead of
-                                    three launches with the score matrix in the workspace.  Bit-identical
-                                    results; on this chip the three-launch form is the faster one at every
-                                    size measured, so it is the default and this flag is for measuring */
+#define VSA_FLAG_COARSE_FUSED 8u    /* vsa_forward: run the coarse stage as ONE launch that keeps the score block
+                                      in LDS (Sec. 2.4, App. D; up to 1536 cubes, ignored above) ...          */
+#define VSA_FLAG_COARSE_UNFUSED 64u /* ... or as three launches with the score matrix in the workspace.  With
+                                      neither flag the library picks the faster form for the shape.  The two
+                                      forms use different matrix instructions: their logits agree to the last
+                                      few bits, so their selections can differ on near ties only.            */
 #define VSA_FLAG_OUT_TOKEN_MAJOR 16u /* vsa_forward: `out` is written token-major, bf16 [B,Np,H,d] = [B,Np,H*d]
                                        in tiled token order: the layout the output projection consumes
                                        ("b h l d -> b l (h d)", last line of the App. B listing) when

@@ -19,7 +19,8 @@ def main(names=None):
     for name in names or sys.argv[1:] or ["tiny", "mid"]:
         wl = WORKLOADS[name]
         for fused in (False, True):
-            pb = dataclasses.replace(vsa.problem_of(wl), flags=vsa.VSA_FLAG_COARSE_FUSED if fused else 0)
+            pb = dataclasses.replace(vsa.problem_of(wl),
+                                     flags=vsa.VSA_FLAG_COARSE_FUSED if fused else vsa.VSA_FLAG_COARSE_UNFUSED)
             Np, Nc = vsa.vsa_padded_tokens(pb)
             g = torch.Generator(device="cuda")
             g.manual_seed(0)

@@ -3,8 +3,8 @@
 // softmax, top-K and mask->index conversion in one kernel; so does k_coarse_rows below).
 //
 // Everything is fp32: the selection must agree with an fp32 reference except on near ties,
-// and the whole stage is < 0.2 % of the attention FLOPs.  Three launches (up to 256 cubes a
-// single-launch form, k_coarse_fused, exists as well; it is the slower one on this chip):
+// and the whole stage is < 0.2 % of the attention FLOPs.  One launch (k_coarse_fused, the faster
+// form up to several hundred cubes) or three:
 //   S  = scale * Qc Kc^T          fp32 matrix-core GEMM, S materialised [B*H, Nc, Nc]
 //   k_coarse_rows                 one wavefront per row: log-sum-exp, top-K -> index list,
 //                                 probabilities written back over S
@@ -143,68 +143,103 @@ __global__ __launch_bounds__(256) void k_coarse_rows(int rows, int Nc, int K, fl
                   lane);
 }
 
-// The whole coarse stage of a short sequence (Nc <= 256) in ONE launch, the score block never
-// leaving the chip (Sec. 2.4 fuses softmax, top-K and index conversion; App. D notes that the coarse
-// stage weighs most at short sequences).  One workgroup of 16 wavefronts per (b, h, 64 query cubes):
-//   1. four teams of four wavefronts form the [64 x Nc] block of logits, 64 columns per team, with
-//      fp32 matrix instructions into LDS;
-//   2. the 16 wavefronts take the rows one by one (log-sum-exp, top-K list, probabilities written
-//      back into LDS);
-//   3. a second fp32 product of the probabilities with Vc gives the block's rows of O_c, 64 columns
-//      per team.
-// Same arithmetic, in the same order per element, as the three-launch path: bit-identical results.
-constexpr int kFusedMaxCubes = 256;
+// The whole coarse stage in ONE launch, the score block never leaving the chip (Sec. 2.4 fuses
+// softmax, top-K and index conversion; App. D notes that the coarse stage weighs most at short
+// sequences).  One workgroup of 16 wavefronts per (b, h, 16 query cubes) -- small blocks, so that even
+// a short sequence gives every compute unit several workgroups -- with both operands of the two
+// products read straight from L2 (Kc, Vc of a head are a few hundred KB):
+//   1. logits: S[16 x Nc] = scale * Qc_block Kc^T with v_mfma_f32_16x16x4_f32 (fp32 products and
+//      sums), one 16-column block per wavefront and round, into LDS;
+//   2. one row per wavefront: log-sum-exp, top-K list, probabilities written back into LDS;
+//   3. O_c block = P Vc, 16 columns per wavefront; the wavefronts left over split the contraction
+//      and their partial sums are added in a fixed order through LDS.
+// A 16x16x4 step contracts 4 values of k, k-group l/16 of lane l; with one 16-byte load per lane and
+// operand (4 consecutive k) step j of four takes k = k0 + 4*(l/16) + j -- the same relabelling on
+// both operands.  NCH*64 >= Nc bounds the row (and the LDS block: 16 x (NCH*64 + 4) floats).
+typedef float f32x4m __attribute__((ext_vector_type(4)));
+constexpr int kFusedMaxCubes = 1536;  // the LDS block of 16 rows: 98.6 KB at 1536 cubes
 template <int D, int NCH>
 __global__ __launch_bounds__(1024) void k_coarse_fused(int Nc, int K, float scale, const float* __restrict__ qc,
                                                        const float* __restrict__ kc, const float* __restrict__ vc,
                                                        float* __restrict__ oc, float* __restrict__ lse_c,
                                                        int32_t* __restrict__ idx, int emit_idx) {
-  constexpr int LDS_ROW = kFusedMaxCubes + 4;  // + 4: rows start 4 banks apart (conflict-free column reads)
-  constexpr int TEAMS = 4;
-  __shared__ __attribute__((aligned(16))) float S[64 * LDS_ROW];
-  __shared__ __attribute__((aligned(16))) float As[TEAMS][64][36];
-  __shared__ __attribute__((aligned(16))) float Bs[TEAMS][64][36];
-  const int blocks = (Nc + 63) / 64;
-  const int m0 = (blockIdx.x % blocks) * 64;
+  constexpr int R = 16;                  // query cubes per workgroup
+  constexpr int LDS_ROW = NCH * 64 + 4;  // + 4: rows start 4 banks apart
+  constexpr int QROW = D + 4;
+  constexpr int CB = D / 16;             // 16-column blocks of O_c
+  constexpr int KSPLIT = 16 / CB;        // wavefronts sharing one column block of O_c
+  __shared__ __attribute__((aligned(16))) float S[R * LDS_ROW];
+  __shared__ __attribute__((aligned(16))) float Qs[R * QROW];
+  __shared__ __attribute__((aligned(16))) float part[16][64][4];
+  const int blocks = (Nc + R - 1) / R;
+  const int m0 = (blockIdx.x % blocks) * R;
   const long long bh = blockIdx.x / blocks;
-  const int team = threadIdx.x >> 8, tid = threadIdx.x & 255, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave & 1, wn = wave >> 1, l32 = lane & 31, h = lane >> 5;
-  const float* qb = qc + (bh * Nc + m0) * D;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l16 = lane & 15, kq = lane >> 4;
   const float* kb = kc + bh * Nc * D;
   const float* vb = vc + bh * Nc * D;
-  const int rows_valid = min(64, Nc - m0), kpad = (Nc + 31) & ~31;
+  const int rows_valid = min(R, Nc - m0), kpad = (Nc + 15) & ~15;
 
-  // 1. logits: S[m][n] = scale * Qc[m0 + m] . Kc[n]; columns Nc .. kpad-1 are zero for the second product
-  {
-    const int n0 = team * 64;
-    f32x16g acc;
-    gemm_tile_global(As[team], Bs[team], qb, D, 1, rows_valid, kb + (long long)min(n0, Nc - 1) * D, D, 1,
-                     n0 < Nc ? Nc - n0 : 0, D, tid, acc);
-    const int n = n0 + wn * 32 + l32;
+  for (int i = tid; i < R * D; i += 1024) {
+    const int r = i / D, e = i % D;
+    Qs[r * QROW + e] = r < rows_valid ? qc[(bh * Nc + m0 + r) * D + e] : 0.f;
+  }
+  __syncthreads();
+  // 1. logits (columns Nc .. kpad-1 are written as zero for the second product)
+  for (int cb = wave; cb * 16 < kpad; cb += 16) {
+    const int n = cb * 16 + l16;
+    const float* krow = kb + (long long)min(n, Nc - 1) * D + 4 * kq;
+    f32x4m acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const int m = wm * 32 + 8 * (i / 4) + 4 * h + (i % 4);
-      if (n < kpad) S[m * LDS_ROW + n] = n < Nc ? scale * acc[i] : 0.f;
+    for (int k0 = 0; k0 < D; k0 += 16) {
+      const float4 a = *(const float4*)&Qs[l16 * QROW + k0 + 4 * kq];
+      const float4 b = *(const float4*)(krow + k0);
+      acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a.x, b.x, acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a.y, b.y, acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a.z, b.z, acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a.w, b.w, acc, 0, 0, 0);
     }
-  }
-  __syncthreads();
-  // 2. rows: softmax statistics, top-K list, probabilities back into S (rows of the block beyond Nc
-  //    hold the logits of zero queries and are never stored)
-  for (int r = (int)(threadIdx.x >> 6); r < rows_valid; r += 16) {
-    const long long row = bh * Nc + m0 + r;
-    coarse_row<NCH>(S + r * LDS_ROW, Nc, K, lse_c ? lse_c + row : nullptr, idx + row * K, emit_idx, lane);
-  }
-  __syncthreads();
-  // 3. O_c[m0 + m][e] = sum_n P[m][n] Vc[n][e]
-  {
-    const int e0 = team * 64;
-    f32x16g acc;
-    gemm_tile_lds_a(S, LDS_ROW, Bs[team], vb + min(e0, D - 1), 1, D, e0 < D ? D - e0 : 0, Nc, tid, acc);
-    const int e = e0 + wn * 32 + l32;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const int m = wm * 32 + 8 * (i / 4) + 4 * h + (i % 4);
-      if (m < rows_valid && e < D) oc[(bh * Nc + m0 + m) * D + e] = acc[i];
+    for (int i = 0; i < 4; ++i) S[(4 * kq + i) * LDS_ROW + n] = n < Nc ? scale * acc[i] : 0.f;
+  }
+  __syncthreads();
+  // 2. rows (rows of the block beyond Nc hold the logits of zero queries and are never stored)
+  if (wave < rows_valid) {
+    const long long row = bh * Nc + m0 + wave;
+    coarse_row<NCH>(S + wave * LDS_ROW, Nc, K, lse_c ? lse_c + row : nullptr, idx + row * K, emit_idx, lane);
+  }
+  __syncthreads();
+  // 3. O_c[m0 + m][e] = sum_n P[m][n] Vc[n][e]: wavefront (cb, ks) takes columns 16*cb.. and every
+  //    KSPLIT-th group of 16 contraction values
+  {
+    const int cb = wave % CB, ks = wave / CB;
+    f32x4m acc = {0.f, 0.f, 0.f, 0.f};
+    const float* vcol = vb + cb * 16 + l16;
+    for (int k0 = ks * 16; k0 < kpad; k0 += 16 * KSPLIT) {
+      const float4 a = *(const float4*)&S[l16 * LDS_ROW + k0 + 4 * kq];
+      const int kk = k0 + 4 * kq;
+      float b[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) b[j] = kk + j < Nc ? vcol[(long long)(kk + j) * D] : 0.f;
+      acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a.x, b[0], acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a.y, b[1], acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a.z, b[2], acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a.w, b[3], acc, 0, 0, 0);
+    }
+    *(float4*)part[wave][lane] = make_float4(acc[0], acc[1], acc[2], acc[3]);
+    __syncthreads();
+    if (ks == 0) {
+      float4 sum = *(const float4*)part[wave][lane];
+      for (int o = 1; o < KSPLIT; ++o) {
+        const float4 x = *(const float4*)part[o * CB + cb][lane];
+        sum.x += x.x; sum.y += x.y; sum.z += x.z; sum.w += x.w;
+      }
+      const float out[4] = {sum.x, sum.y, sum.z, sum.w};
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int m = 4 * kq + i;
+        if (m < rows_valid) oc[(bh * Nc + m0 + m) * D + cb * 16 + l16] = out[i];
+      }
     }
   }
 }
@@ -275,14 +310,20 @@ hipError_t launch_coarse(int BH, int Nc, int d, int K, float scale, const float*
   const long long sx = (long long)Nc * d, ss = (long long)Nc * Nc;
   hipError_t e;
   if (Nc <= kFusedMaxCubes && fused) {
-    const unsigned fgrid = (unsigned)(BH * ((Nc + 63) / 64));
-#define VSA_FUSED(D_, NCH_) k_coarse_fused<D_, NCH_><<<fgrid, 1024, 0, s>>>(Nc, K, scale, qc, kc, vc, oc, lse_c, idx, emit_idx)
+    const unsigned fgrid = (unsigned)(BH * ((Nc + 15) / 16));
+#define VSA_FUSED(NCH_)                                                                                             \
+  do {                                                                                                              \
+    if (d == 128) k_coarse_fused<128, NCH_><<<fgrid, 1024, 0, s>>>(Nc, K, scale, qc, kc, vc, oc, lse_c, idx, emit_idx); \
+    else k_coarse_fused<64, NCH_><<<fgrid, 1024, 0, s>>>(Nc, K, scale, qc, kc, vc, oc, lse_c, idx, emit_idx);          \
+  } while (0)
     // NCH = logits per lane of the row step: the smallest that covers Nc
-    if (d == 128) {
-      if (Nc <= 64) VSA_FUSED(128, 1); else if (Nc <= 128) VSA_FUSED(128, 2); else VSA_FUSED(128, 4);
-    } else {
-      if (Nc <= 64) VSA_FUSED(64, 1); else if (Nc <= 128) VSA_FUSED(64, 2); else VSA_FUSED(64, 4);
-    }
+    if (Nc <= 64) VSA_FUSED(1);
+    else if (Nc <= 128) VSA_FUSED(2);
+    else if (Nc <= 256) VSA_FUSED(4);
+    else if (Nc <= 512) VSA_FUSED(8);
+    else if (Nc <= 768) VSA_FUSED(12);
+    else if (Nc <= 1024) VSA_FUSED(16);
+    else VSA_FUSED(24);
 #undef VSA_FUSED
     return hipGetLastError();
   }

@@ -18,6 +18,7 @@ namespace {
 using vsa::Geo;
 
 constexpr size_t kAlign = 256;
+constexpr int kCoarseOneLaunchMaxCubes = 768;  // measured: faster up to the 624 cubes of the 480p shape, slower at 1440
 inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 int check_params(const vsa_params_t* p, Geo* g) {
@@ -48,6 +49,13 @@ int check_params(const vsa_params_t* p, Geo* g) {
   if ((long long)p->B * p->H * g->Nb > 0x7fffffffLL / 4) return VSA_ERR_UNSUPPORTED;  // grid sizes stay in 32 bits
   if ((long long)p->B * p->H * g->Nb * p->topk * g->m > 0x7fffffffLL / 2) return VSA_ERR_UNSUPPORTED;
   return VSA_OK;
+}
+
+// Coarse stage as one launch (1) or three (0): the caller's flag, else the faster form for the shape.
+int coarse_form(const vsa_params_t* p, const Geo& g) {
+  if (p->flags & VSA_FLAG_COARSE_UNFUSED) return 0;
+  if (p->flags & VSA_FLAG_COARSE_FUSED) return 1;
+  return g.Nc <= kCoarseOneLaunchMaxCubes ? 1 : 0;
 }
 
 // Mismatched granularity (VSA_FLAG_SELECT_POOLED_2X2): the lists name tiles of (1,2,2) cubes.
@@ -218,7 +226,7 @@ int enqueue_forward(const vsa_params_t* p, const Geo& g, const void* q, const vo
   VSA_TRY("pool", vsa::launch_pool(g, BH, p->d, w.mask, q, k, v, w.qc, w.kc, w.vc, s));
   const bool pooled = pooled_select(p);
   VSA_TRY("coarse", vsa::launch_coarse(BH, g.Nc, p->d, p->topk, scale, w.qc, w.kc, w.vc, w.sc, oc, lse_c, idx, (given || pooled) ? 0 : 1,
-                            (!pooled && (p->flags & VSA_FLAG_COARSE_FUSED)) ? 1 : 0, s));
+                            pooled ? 0 : coarse_form(p, g), s));
   // the fine stage works on 64-row blocks: a cube of m blocks contributes m list entries, a tile of
   // (1,2,2) cubes its four cubes
   const int32_t* lists = idx;

@@ -17,6 +17,7 @@ VSA_FLAG_INDICES_GIVEN = 1
 VSA_FLAG_RASTER_BLHD = 2
 VSA_FLAG_WORKSPACE_KEPT = 4
 VSA_FLAG_COARSE_FUSED = 8
+VSA_FLAG_COARSE_UNFUSED = 64
 VSA_FLAG_OUT_TOKEN_MAJOR = 16
 VSA_FLAG_SELECT_POOLED_2X2 = 32
 STATUS = {0: "VSA_OK", -1: "VSA_ERR_NULL", -2: "VSA_ERR_BAD_ARG", -3: "VSA_ERR_UNSUPPORTED", -4: "VSA_ERR_ALIGN",
