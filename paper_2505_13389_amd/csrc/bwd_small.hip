@@ -315,18 +315,17 @@ __device__ __forceinline__ int block_sum(int x, int* wsum, int tid) {
 //          workgroup, Nc + cap of them per (b, h); unused ones carry key cube -1
 //   split: per (b, h) cap/2 + 1 descriptors: [0] = (number of split lists, 0, 0, 0), then
 //          (key cube, first slot, number of slots, 0) per split list, in cube order
-__global__ __launch_bounds__(1024) void k_map_scan(int Nc, int seg_min, int cap, int32_t* __restrict__ row_ptr,
-                                                   int32_t* __restrict__ order, int32_t* __restrict__ split) {
-  __shared__ int wsum[16];
-  __shared__ int hist[kMaxCubes];  // bucket x: items of length Nc - x (the last bucket also takes
-                                   // what lies beyond it), then the next free slot of the bucket
-  const int bh = blockIdx.x, tid = threadIdx.x;
+// (the body, for the 1024 threads of one workgroup: thread `tid` owns cubes 4*tid .. 4*tid+3, whose
+// in-degrees it passes in `deg`; `v` returns where their lists begin.  wsum[16] and hist[kMaxCubes] are
+// LDS scratch: bucket x of hist counts the items of length Nc - x (the last bucket also takes what
+// lies beyond it), then holds the next free slot of the bucket)
+__device__ __forceinline__ void map_scan_body(int Nc, int seg_min, int cap, int bh, int tid, const int (&deg)[4], int (&v)[4],
+                                              int32_t* __restrict__ row_ptr, int32_t* __restrict__ order,
+                                              int32_t* __restrict__ split, int* wsum, int* hist) {
   int32_t* rp = row_ptr + (long long)bh * (Nc + 1);
   const int j0 = tid * 4;
-  int deg[4], v[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    deg[i] = (j0 + i < Nc) ? rp[j0 + i] : 0;
     v[i] = deg[i];
     hist[j0 + i] = 0;
   }
@@ -404,17 +403,21 @@ __global__ __launch_bounds__(1024) void k_map_scan(int Nc, int seg_min, int cap,
   for (int e = items + tid; e < Nc + cap; e += 1024) ord[e] = make_int4(-1, 0, 0, -1);
 }
 
-// the list of key cube j: positions of the set bits of its row, ascending (one wavefront per row)
-__global__ __launch_bounds__(256) void k_map_fill(int Nc, int W32, long long rows, const uint32_t* __restrict__ bits,
-                                                  const int32_t* __restrict__ row_ptr, int32_t* __restrict__ col,
-                                                  long long col_stride) {
-  const long long row = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);  // bh * Nc + j
-  const int lane = threadIdx.x & 63;
-  if (row >= rows) return;
-  const long long bh = row / Nc;
-  int base = row_ptr[bh * (Nc + 1) + row % Nc];
-  int32_t* cl = col + bh * col_stride;
-  const uint32_t* r = bits + row * W32;
+__global__ __launch_bounds__(1024) void k_map_scan(int Nc, int seg_min, int cap, int32_t* __restrict__ row_ptr,
+                                                   int32_t* __restrict__ order, int32_t* __restrict__ split) {
+  __shared__ int wsum[16];
+  __shared__ int hist[kMaxCubes];
+  const int bh = blockIdx.x, tid = threadIdx.x;
+  const int32_t* rp = row_ptr + (long long)bh * (Nc + 1);
+  int deg[4], v[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) deg[i] = (4 * tid + i < Nc) ? rp[4 * tid + i] : 0;
+  map_scan_body(Nc, seg_min, cap, bh, tid, deg, v, row_ptr, order, split, wsum, hist);
+}
+
+// the list of key cube j: positions of the set bits of its row `r` (W32 words, global memory or LDS),
+// ascending, written to cl[base ..]; one wavefront per row
+__device__ __forceinline__ void map_fill_row(const uint32_t* r, int W32, int base, int32_t* __restrict__ cl, int lane) {
   for (int w0 = 0; w0 < W32; w0 += 64) {
     uint32_t word = (w0 + lane < W32) ? r[w0 + lane] : 0u;
     const int c = __popc(word);
@@ -433,12 +436,83 @@ __global__ __launch_bounds__(256) void k_map_fill(int Nc, int W32, long long row
     base += __shfl(incl, 63);
   }
 }
+__global__ __launch_bounds__(256) void k_map_fill(int Nc, int W32, long long rows, const uint32_t* __restrict__ bits,
+                                                  const int32_t* __restrict__ row_ptr, int32_t* __restrict__ col,
+                                                  long long col_stride) {
+  const long long row = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);  // bh * Nc + j
+  const int lane = threadIdx.x & 63;
+  if (row >= rows) return;
+  const long long bh = row / Nc;
+  map_fill_row(bits + row * W32, W32, row_ptr[bh * (Nc + 1) + row % Nc], col + bh * col_stride, lane);
+}
+
+// The whole map of one (b, h) in ONE launch, for short sequences (the bit matrix of a (b, h) fits in LDS
+// up to kMapOneLaunchMaxCubes key cubes): the four steps above by the 1024 threads of one workgroup --
+// bits OR-ed into LDS, in-degrees, scan and work items, lists -- instead of four launches.
+constexpr int kMapOneLaunchMaxCubes = 384;  // (measured: ahead of the four launches up to here, level at 512)
+__global__ __launch_bounds__(1024) void k_map_one_launch(int Nc, int K, int W32, int seg_min, int cap,
+                                                         const int32_t* __restrict__ idx, int32_t* __restrict__ row_ptr,
+                                                         int32_t* __restrict__ col, long long col_stride,
+                                                         int32_t* __restrict__ order, int32_t* __restrict__ split) {
+  __shared__ uint32_t bits_l[kMapOneLaunchMaxCubes * (kMapOneLaunchMaxCubes / 32 + 1)];
+  const int WS = W32 | 1;  // odd row stride: the rows the OR step and the count step touch together fall into different banks
+  __shared__ int deg_l[kMaxCubes], start_l[kMaxCubes];
+  __shared__ int wsum[16];
+  __shared__ int hist[kMaxCubes];
+  const int bh = blockIdx.x, tid = threadIdx.x;
+  for (int i = tid; i < Nc * WS; i += 1024) bits_l[i] = 0u;
+  __syncthreads();
+  const int32_t* my = idx + (long long)bh * Nc * K;
+  for (int e0 = tid; e0 < Nc * K; e0 += 8 * 1024) {  // (eight loads in flight per thread, then their bits)
+    int c[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) c[u] = e0 + u * 1024 < Nc * K ? my[e0 + u * 1024] : -1;
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int q = (e0 + u * 1024) / K;
+      if (map_takes(c[u], Nc)) atomicOr(&bits_l[c[u] * WS + (q >> 5)], 1u << (q & 31));  // (a caller-supplied list is not trusted)
+    }
+  }
+  __syncthreads();
+  for (int j = tid; j < kMaxCubes; j += 1024) {
+    int c = 0;
+    if (j < Nc)
+      for (int w = 0; w < W32; ++w) c += __popc(bits_l[j * WS + w]);
+    deg_l[j] = c;
+  }
+  __syncthreads();
+  int deg[4], v[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) deg[i] = deg_l[4 * tid + i];
+  map_scan_body(Nc, seg_min, cap, bh, tid, deg, v, row_ptr, order, split, wsum, hist);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) start_l[4 * tid + i] = v[i];
+  __syncthreads();
+  // lists: one thread per word of the bit matrix (a row has at most 12 words here, so the count of the
+  // bits before a word is a short loop over LDS)
+  int32_t* cl = col + bh * col_stride;
+  for (int i = tid; i < Nc * W32; i += 1024) {
+    const int j = i / W32, w = i - j * W32;
+    uint32_t word = bits_l[j * WS + w];
+    if (!word) continue;
+    int pos = start_l[j];
+    for (int x = 0; x < w; ++x) pos += __popc(bits_l[j * WS + x]);
+    while (word) {
+      cl[pos++] = w * 32 + __ffs(word) - 1;
+      word &= word - 1;
+    }
+  }
+}
 
 hipError_t launch_transpose_map(int BH, int Nc, int K, const int32_t* idx, uint32_t* bits, int32_t* row_ptr,
                                 int32_t* col, int32_t* order, int32_t* split, int seg, int cap, hipStream_t s) {
   const int W32 = (Nc + 31) / 32;
   const long long rows = (long long)BH * Nc;
   hipError_t e;
+  if (Nc <= kMapOneLaunchMaxCubes) {
+    k_map_one_launch<<<BH, 1024, 0, s>>>(Nc, K, W32, seg, cap, idx, row_ptr, col, (long long)Nc * K, order, split);
+    return hipGetLastError();
+  }
   k_map_bits<<<(unsigned)(BH * W32), 256, 0, s>>>(Nc, K, W32, idx, bits);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   k_map_degree<<<(unsigned)((rows + 3) / 4), 256, 0, s>>>(Nc, W32, rows, bits, row_ptr);
