@@ -29,6 +29,9 @@
  *   - a partially filled cube has the same weight in the coarse softmax as a full one.
  *   - gate_f == NULL means a gate of ones [Sec. 2.3].
  *   - no gradient flows through the top-K selection.
+ *   - the 64 x 16 row of the tile-size tables [Sec. 3.2] is read as: query cubes (4,4,4), key cubes
+ *     (2,4,2) nested in them (the table writes 16x64, the text 64 x 16; see the section on key
+ *     cubes below).  A key cube with no valid token is dead: never in the softmax, never selected.
  *
  * Parity pins: see tests/test_oracle_*.py.  Unpinned by anything outside this file: the
  * two pad conventions above that are ours by fiat (equal weighting of partial cubes in
@@ -604,6 +607,356 @@ int vsa_oracle_backward(int B, int H, int T, int Hh, int W, int Ct, int Ch, int 
     free(dOc); free(dSc); free(dQc); free(dKc); free(dVc);
   }
   free(valid); free(cnt);
+  return 0;
+}
+
+/* ------------------------------------------------------------------------------------ */
+/* Key cubes smaller than query cubes [Sec. 3.2, tile-size tables: the 64 x 16 row]      */
+/* ------------------------------------------------------------------------------------ */
+/*
+ * Reading: queries keep the (Ct,Ch,Cw) cubes and their token order; keys are grouped in smaller
+ * (Kt,Kh,Kw) cubes that divide the query cube (B=16: (2,4,2) inside (4,4,4)).  The coarse stage
+ * pools Q over query cubes and K, V over key cubes, its map is [Nc x Nk], the top-K of a row
+ * names key cubes, and a query token attends to the valid tokens of the key cubes its cube
+ * selected.  Key cube numbering: R = (Ct/Kt)(Ch/Kh)(Cw/Kw) key cubes per query cube,
+ *   label(t,h,w) = cube(t,h,w) * R + (((t mod Ct)/Kt) (Ch/Kh) + (h mod Ch)/Kh) (Cw/Kw) + (w mod Cw)/Kw.
+ * A key cube of a padded grid may hold no valid token at all: it is then DEAD -- its pooled
+ * rows are zero, it is left out of the coarse softmax and it is never selected (topk must not
+ * exceed the number of live key cubes).
+ * With (Kt,Kh,Kw) == (Ct,Ch,Cw) everything here is the ordinary method.
+ */
+typedef struct {
+  grid_t g;
+  int R, Nk;
+  int32_t* label;  /* [Np] key cube of each tiled slot, -1 for a pad slot */
+  int32_t* kcnt;   /* [Nk] valid tokens per key cube */
+  int64_t* first;  /* [Nk+1] members of key cube j: member[first[j] .. first[j+1]) */
+  int64_t* member; /* tiled slots of the valid tokens, grouped by key cube */
+  uint8_t* valid;  /* [Np] */
+  int32_t* qcnt;   /* [Nc] valid tokens per query cube */
+} kq_t;
+
+static int kq_make(kq_t* x, int T, int Hh, int W, int Ct, int Ch, int Cw, int Kt, int Kh, int Kw) {
+  if (Kt < 1 || Kh < 1 || Kw < 1 || Ct % Kt || Ch % Kh || Cw % Kw) return -1;
+  x->g = make_grid(T, Hh, W, Ct, Ch, Cw);
+  const grid_t* g = &x->g;
+  x->R = (Ct / Kt) * (Ch / Kh) * (Cw / Kw);
+  x->Nk = g->Nc * x->R;
+  x->label = (int32_t*)malloc(sizeof(int32_t) * (size_t)g->Np);
+  x->kcnt = (int32_t*)calloc((size_t)x->Nk, sizeof(int32_t));
+  x->first = (int64_t*)calloc((size_t)x->Nk + 1, sizeof(int64_t));
+  x->member = (int64_t*)malloc(sizeof(int64_t) * (size_t)g->Np);
+  x->valid = (uint8_t*)malloc((size_t)g->Np);
+  x->qcnt = (int32_t*)malloc(sizeof(int32_t) * (size_t)g->Nc);
+  vsa_oracle_valid(T, Hh, W, Ct, Ch, Cw, x->valid, x->qcnt);
+  for (int64_t n = 0; n < g->Np; ++n) x->label[n] = -1;
+  for (int t = 0; t < T; ++t)
+    for (int h = 0; h < Hh; ++h)
+      for (int w = 0; w < W; ++w) {
+        int64_t n = tiled_index(g, t, h, w);
+        int local = (((t % Ct) / Kt) * (Ch / Kh) + (h % Ch) / Kh) * (Cw / Kw) + (w % Cw) / Kw;
+        x->label[n] = (int32_t)(n / g->Bk) * x->R + local;
+        x->kcnt[x->label[n]] += 1;
+      }
+  for (int j = 0; j < x->Nk; ++j) x->first[j + 1] = x->first[j] + x->kcnt[j];
+  int64_t* fill = (int64_t*)malloc(sizeof(int64_t) * (size_t)x->Nk);
+  memcpy(fill, x->first, sizeof(int64_t) * (size_t)x->Nk);
+  for (int64_t n = 0; n < g->Np; ++n)
+    if (x->label[n] >= 0) x->member[fill[x->label[n]]++] = n;
+  free(fill);
+  return 0;
+}
+static void kq_free(kq_t* x) {
+  free(x->label); free(x->kcnt); free(x->first); free(x->member); free(x->valid); free(x->qcnt);
+}
+
+/* label [Np] (-1 on pad slots) and kcnt [Nk] of the key-cube partition; returns Nk, or -1 */
+int vsa_oracle_keycubes(int T, int Hh, int W, int Ct, int Ch, int Cw, int Kt, int Kh, int Kw, int32_t* label,
+                        int32_t* kcnt) {
+  kq_t x;
+  if (kq_make(&x, T, Hh, W, Ct, Ch, Cw, Kt, Kh, Kw)) return -1;
+  if (label) memcpy(label, x.label, sizeof(int32_t) * (size_t)x.g.Np);
+  if (kcnt) memcpy(kcnt, x.kcnt, sizeof(int32_t) * (size_t)x.Nk);
+  int Nk = x.Nk;
+  kq_free(&x);
+  return Nk;
+}
+
+/* mean over the valid tokens of every key cube (zero rows for dead ones).  x: [Np,d] -> xc: [Nk,d] */
+static void kq_pool_keys(const kq_t* x, int d, const real* in, real* xc) {
+  for (int j = 0; j < x->Nk; ++j)
+    for (int e = 0; e < d; ++e) {
+      real s = 0;
+      for (int64_t m = x->first[j]; m < x->first[j + 1]; ++m) s += in[x->member[m] * d + e];
+      xc[(int64_t)j * d + e] = x->kcnt[j] ? s / (real)x->kcnt[j] : (real)0;
+    }
+}
+/* coarse logits of query cube c against every key cube; -inf for dead key cubes */
+static void kq_logits_row(const kq_t* x, int d, real scale, const real* Qc, const real* Kc, int c, real* row) {
+  for (int j = 0; j < x->Nk; ++j) {
+    real s = 0;
+    for (int e = 0; e < d; ++e) s += Qc[(int64_t)c * d + e] * Kc[(int64_t)j * d + e];
+    row[j] = x->kcnt[j] ? s * scale : -INFINITY;
+  }
+}
+/* softmax over a row that may hold -inf entries (they get probability 0); returns logsumexp */
+static real kq_softmax_row(int n, const real* logits, real* prob) {
+  real m = -INFINITY;
+  for (int j = 0; j < n; ++j) if (logits[j] > m) m = logits[j];
+  real l = 0;
+  for (int j = 0; j < n; ++j) { prob[j] = (logits[j] == -INFINITY) ? (real)0 : EXP(logits[j] - m); l += prob[j]; }
+  for (int j = 0; j < n; ++j) prob[j] /= l;
+  return m + LOG(l);
+}
+/* fine attention of query token i over the valid tokens of the K listed key cubes; returns lse */
+static real kq_fine_row(const kq_t* x, int d, real scale, const real* q, const real* k, const real* v, int64_t i,
+                        const int32_t* idx, int K, real* of) {
+  real m = -INFINITY;
+  for (int r = 0; r < K; ++r)
+    for (int64_t mm = x->first[idx[r]]; mm < x->first[idx[r] + 1]; ++mm) {
+      int64_t j = x->member[mm];
+      real acc = 0;
+      for (int e = 0; e < d; ++e) acc += q[i * d + e] * k[j * d + e];
+      acc *= scale;
+      if (acc > m) m = acc;
+    }
+  real l = 0;
+  for (int e = 0; e < d; ++e) of[e] = 0;
+  for (int r = 0; r < K; ++r)
+    for (int64_t mm = x->first[idx[r]]; mm < x->first[idx[r] + 1]; ++mm) {
+      int64_t j = x->member[mm];
+      real acc = 0;
+      for (int e = 0; e < d; ++e) acc += q[i * d + e] * k[j * d + e];
+      real p = EXP(acc * scale - m);
+      l += p;
+      for (int e = 0; e < d; ++e) of[e] += p * v[j * d + e];
+    }
+  for (int e = 0; e < d; ++e) of[e] /= l;
+  return m + LOG(l);
+}
+
+/*
+ * Forward with key cubes (Kt,Kh,Kw).  Arguments as vsa_oracle_forward, except: topk counts key
+ * cubes (1 .. live key cubes); block_idx is [B,H,Nc,topk] of key cube labels, ascending;
+ * out_coarse is [B,H,Nc,d]; sc (optional) is [B,H,Nc,Nk] with -inf for dead key cubes.
+ */
+int vsa_oracle_forward_kq(int B, int H, int T, int Hh, int W, int Ct, int Ch, int Cw, int Kt, int Kh, int Kw, int d,
+                          int topk, double scale_, int indices_given, const real* q, const real* k, const real* v,
+                          const real* gate_c, const real* gate_f, const int32_t* cubes, int ncubes, real* out,
+                          int32_t* block_idx, real* out_fine, real* lse_fine, real* out_coarse, real* lse_coarse,
+                          real* sc) {
+  kq_t x;
+  if (kq_make(&x, T, Hh, W, Ct, Ch, Cw, Kt, Kh, Kw)) return -1;
+  const grid_t g = x.g;
+  int live = 0;
+  for (int j = 0; j < x.Nk; ++j) live += x.kcnt[j] > 0;
+  if (B < 1 || H < 1 || d < 1 || topk < 1 || topk > live || (indices_given && !block_idx)) { kq_free(&x); return -1; }
+  real scale = (real)scale_;
+  int nq = cubes ? ncubes : g.Nc;
+  for (int bh = 0; bh < B * H; ++bh) {
+    const real* qh = q + (int64_t)bh * g.Np * d;
+    const real* kh = k + (int64_t)bh * g.Np * d;
+    const real* vh = v + (int64_t)bh * g.Np * d;
+    real* Qc = (real*)malloc(sizeof(real) * (size_t)g.Nc * d);
+    real* Kc = (real*)malloc(sizeof(real) * (size_t)x.Nk * d);
+    real* Vc = (real*)malloc(sizeof(real) * (size_t)x.Nk * d);
+    pool_mean(&g, d, x.valid, x.qcnt, qh, Qc);
+    kq_pool_keys(&x, d, kh, Kc);
+    kq_pool_keys(&x, d, vh, Vc);
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int ci = 0; ci < nq; ++ci) {
+      int c = cubes ? cubes[ci] : ci;
+      real* row = (real*)malloc(sizeof(real) * (size_t)x.Nk);
+      real* prob = (real*)malloc(sizeof(real) * (size_t)x.Nk);
+      real* oc = (real*)malloc(sizeof(real) * (size_t)d);
+      real* of = (real*)malloc(sizeof(real) * (size_t)d);
+      int32_t* idx = (int32_t*)malloc(sizeof(int32_t) * (size_t)topk);
+      kq_logits_row(&x, d, scale, Qc, Kc, c, row);
+      real lse_c = kq_softmax_row(x.Nk, row, prob);
+      for (int e = 0; e < d; ++e) {
+        real s = 0;
+        for (int j = 0; j < x.Nk; ++j) s += prob[j] * Vc[(int64_t)j * d + e];
+        oc[e] = s;
+      }
+      if (sc) memcpy(sc + ((int64_t)bh * g.Nc + c) * x.Nk, row, sizeof(real) * (size_t)x.Nk);
+      if (out_coarse) memcpy(out_coarse + ((int64_t)bh * g.Nc + c) * d, oc, sizeof(real) * (size_t)d);
+      if (lse_coarse) lse_coarse[(int64_t)bh * g.Nc + c] = lse_c;
+      if (indices_given) memcpy(idx, block_idx + ((int64_t)bh * g.Nc + c) * topk, sizeof(int32_t) * (size_t)topk);
+      else {
+        topk_row(x.Nk, row, topk, idx); /* dead key cubes carry -inf and sort last */
+        if (block_idx) memcpy(block_idx + ((int64_t)bh * g.Nc + c) * topk, idx, sizeof(int32_t) * (size_t)topk);
+      }
+      for (int p = 0; p < g.Bk; ++p) {
+        int64_t i = (int64_t)c * g.Bk + p;
+        int64_t gi = ((int64_t)bh * g.Np + i) * d;
+        if (!x.valid[i]) {
+          for (int e = 0; e < d; ++e) {
+            if (out) out[gi + e] = 0;
+            if (out_fine) out_fine[gi + e] = 0;
+          }
+          if (lse_fine) lse_fine[(int64_t)bh * g.Np + i] = 0;
+          continue;
+        }
+        real lse = kq_fine_row(&x, d, scale, qh, kh, vh, i, idx, topk, of);
+        if (lse_fine) lse_fine[(int64_t)bh * g.Np + i] = lse;
+        for (int e = 0; e < d; ++e) {
+          if (out_fine) out_fine[gi + e] = of[e];
+          if (out) out[gi + e] = oc[e] * gate_c[gi + e] + of[e] * (gate_f ? gate_f[gi + e] : (real)1);
+        }
+      }
+      free(row); free(prob); free(oc); free(of); free(idx);
+    }
+    free(Qc); free(Kc); free(Vc);
+  }
+  kq_free(&x);
+  return 0;
+}
+
+/* Backward with key cubes (Kt,Kh,Kw): the formulas listed at vsa_oracle_backward, with j running
+ * over key cubes in the coarse part and the pooled K, V gradients spread over key cubes. */
+int vsa_oracle_backward_kq(int B, int H, int T, int Hh, int W, int Ct, int Ch, int Cw, int Kt, int Kh, int Kw, int d,
+                           int topk, double scale_, const real* q, const real* k, const real* v, const real* gate_c,
+                           const real* gate_f, const real* dout, const int32_t* block_idx, real* dq, real* dk,
+                           real* dv, real* dgate_c, real* dgate_f) {
+  kq_t x;
+  if (kq_make(&x, T, Hh, W, Ct, Ch, Cw, Kt, Kh, Kw)) return -1;
+  const grid_t g = x.g;
+  if (B < 1 || H < 1 || d < 1 || topk < 1 || topk > x.Nk || !block_idx) { kq_free(&x); return -1; }
+  real scale = (real)scale_;
+  const int Nc = g.Nc, Nk = x.Nk, Bk = g.Bk;
+  const int64_t Np = g.Np;
+  for (int bh = 0; bh < B * H; ++bh) {
+    const int64_t off = (int64_t)bh * Np * d;
+    const real *qh = q + off, *kh = k + off, *vh = v + off, *gch = gate_c + off, *doh = dout + off;
+    const real* gfh = gate_f ? gate_f + off : NULL;
+    const int32_t* idxh = block_idx + (int64_t)bh * Nc * topk;
+    real *dqh = dq + off, *dkh = dk + off, *dvh = dv + off, *dgch = dgate_c + off;
+    real* dgfh = dgate_f ? dgate_f + off : NULL;
+    real* Qc = (real*)malloc(sizeof(real) * (size_t)Nc * d);
+    real* Kc = (real*)malloc(sizeof(real) * (size_t)Nk * d);
+    real* Vc = (real*)malloc(sizeof(real) * (size_t)Nk * d);
+    real* Ac = (real*)malloc(sizeof(real) * (size_t)Nc * Nk);
+    real* Oc = (real*)calloc((size_t)Nc * d, sizeof(real));
+    real* Of = (real*)calloc((size_t)Np * d, sizeof(real));
+    real* lse = (real*)calloc((size_t)Np, sizeof(real));
+    real* dOf = (real*)calloc((size_t)Np * d, sizeof(real));
+    real* Dl = (real*)calloc((size_t)Np, sizeof(real));
+    real* dOc = (real*)calloc((size_t)Nc * d, sizeof(real));
+    real* dSc = (real*)malloc(sizeof(real) * (size_t)Nc * Nk);
+    real* dQc = (real*)calloc((size_t)Nc * d, sizeof(real));
+    real* dKc = (real*)calloc((size_t)Nk * d, sizeof(real));
+    real* dVc = (real*)calloc((size_t)Nk * d, sizeof(real));
+
+    pool_mean(&g, d, x.valid, x.qcnt, qh, Qc);
+    kq_pool_keys(&x, d, kh, Kc);
+    kq_pool_keys(&x, d, vh, Vc);
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int c = 0; c < Nc; ++c) {
+      real* row = (real*)malloc(sizeof(real) * (size_t)Nk);
+      kq_logits_row(&x, d, scale, Qc, Kc, c, row);
+      kq_softmax_row(Nk, row, Ac + (int64_t)c * Nk);
+      for (int e = 0; e < d; ++e) {
+        real s = 0;
+        for (int j = 0; j < Nk; ++j) s += Ac[(int64_t)c * Nk + j] * Vc[(int64_t)j * d + e];
+        Oc[(int64_t)c * d + e] = s;
+      }
+      for (int p = 0; p < Bk; ++p) {
+        int64_t i = (int64_t)c * Bk + p;
+        if (x.valid[i]) lse[i] = kq_fine_row(&x, d, scale, qh, kh, vh, i, idxh + (int64_t)c * topk, topk, Of + i * d);
+      }
+      free(row);
+    }
+    for (int c = 0; c < Nc; ++c)
+      for (int p = 0; p < Bk; ++p) {
+        int64_t i = (int64_t)c * Bk + p;
+        for (int e = 0; e < d; ++e) {
+          dqh[i * d + e] = 0; dkh[i * d + e] = 0; dvh[i * d + e] = 0;
+          if (!x.valid[i]) {
+            dgch[i * d + e] = 0;
+            if (dgfh) dgfh[i * d + e] = 0;
+            continue;
+          }
+          real go = doh[i * d + e];
+          dgch[i * d + e] = go * Oc[(int64_t)c * d + e];
+          if (dgfh) dgfh[i * d + e] = go * Of[i * d + e];
+          dOc[(int64_t)c * d + e] += go * gch[i * d + e];
+          dOf[i * d + e] = go * (gfh ? gfh[i * d + e] : (real)1);
+          Dl[i] += dOf[i * d + e] * Of[i * d + e];
+        }
+      }
+    /* fine backward, dQ: one query token at a time */
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int c = 0; c < Nc; ++c)
+      for (int p = 0; p < Bk; ++p) {
+        int64_t i = (int64_t)c * Bk + p;
+        if (!x.valid[i]) continue;
+        for (int r = 0; r < topk; ++r) {
+          int jc = idxh[(int64_t)c * topk + r];
+          for (int64_t mm = x.first[jc]; mm < x.first[jc + 1]; ++mm) {
+            int64_t j = x.member[mm];
+            real s = 0, dp = 0;
+            for (int e = 0; e < d; ++e) { s += qh[i * d + e] * kh[j * d + e]; dp += dOf[i * d + e] * vh[j * d + e]; }
+            real P = EXP(s * scale - lse[i]);
+            real dS = P * (dp - Dl[i]);
+            for (int e = 0; e < d; ++e) dqh[i * d + e] += scale * dS * kh[j * d + e];
+          }
+        }
+      }
+    /* fine backward, dK and dV: one key cube at a time, over the query cubes that selected it */
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int jc = 0; jc < Nk; ++jc)
+      for (int c = 0; c < Nc; ++c) {
+        int sel = 0;
+        for (int r = 0; r < topk; ++r) if (idxh[(int64_t)c * topk + r] == jc) sel = 1;
+        if (!sel) continue;
+        for (int p = 0; p < Bk; ++p) {
+          int64_t i = (int64_t)c * Bk + p;
+          if (!x.valid[i]) continue;
+          for (int64_t mm = x.first[jc]; mm < x.first[jc + 1]; ++mm) {
+            int64_t j = x.member[mm];
+            real s = 0, dp = 0;
+            for (int e = 0; e < d; ++e) { s += qh[i * d + e] * kh[j * d + e]; dp += dOf[i * d + e] * vh[j * d + e]; }
+            real P = EXP(s * scale - lse[i]);
+            real dS = P * (dp - Dl[i]);
+            for (int e = 0; e < d; ++e) {
+              dkh[j * d + e] += scale * dS * qh[i * d + e];
+              dvh[j * d + e] += P * dOf[i * d + e];
+            }
+          }
+        }
+      }
+    /* coarse backward */
+    for (int c = 0; c < Nc; ++c) {
+      real dot = 0;
+      for (int j = 0; j < Nk; ++j) {
+        real dA = 0;
+        for (int e = 0; e < d; ++e) dA += dOc[(int64_t)c * d + e] * Vc[(int64_t)j * d + e];
+        dSc[(int64_t)c * Nk + j] = dA;
+        dot += Ac[(int64_t)c * Nk + j] * dA;
+      }
+      for (int j = 0; j < Nk; ++j) dSc[(int64_t)c * Nk + j] = Ac[(int64_t)c * Nk + j] * (dSc[(int64_t)c * Nk + j] - dot);
+    }
+    for (int c = 0; c < Nc; ++c)
+      for (int j = 0; j < Nk; ++j)
+        for (int e = 0; e < d; ++e) {
+          dVc[(int64_t)j * d + e] += Ac[(int64_t)c * Nk + j] * dOc[(int64_t)c * d + e];
+          dQc[(int64_t)c * d + e] += scale * dSc[(int64_t)c * Nk + j] * Kc[(int64_t)j * d + e];
+          dKc[(int64_t)j * d + e] += scale * dSc[(int64_t)c * Nk + j] * Qc[(int64_t)c * d + e];
+        }
+    /* pooling backward */
+    for (int64_t i = 0; i < Np; ++i) {
+      if (!x.valid[i]) continue;
+      int c = (int)(i / Bk), j = x.label[i];
+      for (int e = 0; e < d; ++e) {
+        dqh[i * d + e] += dQc[(int64_t)c * d + e] / (real)x.qcnt[c];
+        dkh[i * d + e] += dKc[(int64_t)j * d + e] / (real)x.kcnt[j];
+        dvh[i * d + e] += dVc[(int64_t)j * d + e] / (real)x.kcnt[j];
+      }
+    }
+    free(Qc); free(Kc); free(Vc); free(Ac); free(Oc); free(Of); free(lse); free(dOf); free(Dl);
+    free(dOc); free(dSc); free(dQc); free(dKc); free(dVc);
+  }
+  kq_free(&x);
   return 0;
 }
 

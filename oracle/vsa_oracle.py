@@ -191,6 +191,68 @@ def block_mass(grid: Grid, q, k, scale: float = None, real: str = "f64"):
     return mass
 
 
+def keycubes(grid: Grid, kcube):
+    """Key cubes (Kt,Kh,Kw) nested in the grid's cubes [Sec. 3.2, the 64 x 16 row of the tile-size
+    tables]: (label [Np] of every tiled slot, -1 on pads; kcnt [Nk] valid tokens per key cube)."""
+    Np, Nc, Bk = grid.dims()
+    R = (grid.Ct // kcube[0]) * (grid.Ch // kcube[1]) * (grid.Cw // kcube[2])
+    label = np.zeros(Np, np.int32)
+    kcnt = np.zeros(Nc * R, np.int32)
+    Nk = _lib("f64").vsa_oracle_keycubes(*grid.args(), *kcube, _ptr(label), _ptr(kcnt))
+    if Nk != Nc * R:
+        raise ValueError("vsa_oracle_keycubes: the key cube must divide the query cube")
+    return label, kcnt
+
+
+def forward_kq(grid: Grid, kcube, q, k, v, gate_c, gate_f, topk: int, scale: float = None, block_idx=None,
+               cubes=None, real: str = "f64", want_sc: bool = False):
+    """Forward with key cubes `kcube` = (Kt,Kh,Kw) smaller than the query cubes; block_idx [B,H,Nc,topk]
+    names key cubes.  Otherwise as forward()."""
+    dt = _np_real(real)
+    q, k, v, gate_c, gate_f = (_as(x, dt) for x in (q, k, v, gate_c, gate_f))
+    B, H, Np, d = q.shape
+    Np_, Nc, _ = grid.dims()
+    assert Np == Np_
+    Nk = len(keycubes(grid, kcube)[1])
+    if scale is None:
+        scale = 1.0 / np.sqrt(d)
+    given = block_idx is not None
+    idx = np.ascontiguousarray(block_idx, dtype=np.int32) if given else np.zeros((B, H, Nc, topk), np.int32)
+    assert idx.shape == (B, H, Nc, topk)
+    cub = None if cubes is None else np.ascontiguousarray(cubes, dtype=np.int32)
+    res = dict(
+        out=np.zeros((B, H, Np, d), dt), block_idx=idx, out_fine=np.zeros((B, H, Np, d), dt),
+        lse_fine=np.zeros((B, H, Np), dt), out_coarse=np.zeros((B, H, Nc, d), dt),
+        lse_coarse=np.zeros((B, H, Nc), dt), sc=np.zeros((B, H, Nc, Nk), dt) if want_sc else None)
+    rc = _lib(real).vsa_oracle_forward_kq(
+        B, H, *grid.args(), *kcube, d, topk, C.c_double(scale), int(given), _ptr(q), _ptr(k), _ptr(v), _ptr(gate_c),
+        _ptr(gate_f), _ptr(cub), 0 if cub is None else len(cub), _ptr(res["out"]), _ptr(idx),
+        _ptr(res["out_fine"]), _ptr(res["lse_fine"]), _ptr(res["out_coarse"]), _ptr(res["lse_coarse"]),
+        _ptr(res["sc"]))
+    if rc != 0:
+        raise ValueError("vsa_oracle_forward_kq: bad argument")
+    return res
+
+
+def backward_kq(grid: Grid, kcube, q, k, v, gate_c, gate_f, dout, block_idx, topk: int, scale: float = None,
+                real: str = "f64"):
+    dt = _np_real(real)
+    q, k, v, gate_c, gate_f, dout = (_as(x, dt) for x in (q, k, v, gate_c, gate_f, dout))
+    B, H, Np, d = q.shape
+    if scale is None:
+        scale = 1.0 / np.sqrt(d)
+    idx = np.ascontiguousarray(block_idx, dtype=np.int32)
+    res = dict(dq=np.zeros_like(q), dk=np.zeros_like(q), dv=np.zeros_like(q), dgate_c=np.zeros_like(q),
+               dgate_f=None if gate_f is None else np.zeros_like(q))
+    rc = _lib(real).vsa_oracle_backward_kq(
+        B, H, *grid.args(), *kcube, d, topk, C.c_double(scale), _ptr(q), _ptr(k), _ptr(v), _ptr(gate_c),
+        _ptr(gate_f), _ptr(dout), _ptr(idx), _ptr(res["dq"]), _ptr(res["dk"]), _ptr(res["dv"]),
+        _ptr(res["dgate_c"]), _ptr(res["dgate_f"]))
+    if rc != 0:
+        raise ValueError("vsa_oracle_backward_kq: bad argument")
+    return res
+
+
 def attention_flops(n_query_tokens, n_key_tokens_per_query, d, heads, batch=1, with_backward=False) -> float:
     return float(_lib("f64").vsa_oracle_attention_flops(
         float(n_query_tokens), float(n_key_tokens_per_query), float(d), float(heads), float(batch),

@@ -417,6 +417,139 @@ def test_pooled_selection_is_topk_of_the_block_averaged_attention_map():
         orc.select_pooled(Grid(8, 12, 16, 4, 4, 4), rand(1, 1, 1536, 8), rand(1, 1, 1536, 8), 2)  # 3 cubes along h
 
 
+# ----------------------------------------------------------------------------- key cubes smaller than query cubes
+def keycube_labels_np(grid, kcube):
+    """The key-cube label of every tiled slot by reshape/transpose: number the key cubes on the padded
+    grid (query cube major, then the key cube inside it), broadcast over their tokens, tile."""
+    Ct, Ch, Cw = grid.Ct, grid.Ch, grid.Cw
+    Kt, Kh, Kw = kcube
+    Tp, Hp, Wp = -(-grid.T // Ct) * Ct, -(-grid.Hh // Ch) * Ch, -(-grid.W // Cw) * Cw
+    nt, nh, nw, rt, rh, rw = Tp // Ct, Hp // Ch, Wp // Cw, Ct // Kt, Ch // Kh, Cw // Kw
+    ids = np.arange(nt * nh * nw * rt * rh * rw).reshape(nt, nh, nw, rt, rh, rw)   # [cube..., local...]
+    full = ids.transpose(0, 3, 1, 4, 2, 5)                                        # (nt, rt, nh, rh, nw, rw)
+    full = np.repeat(np.repeat(np.repeat(full, Kt, 1), Kh, 3), Kw, 5).reshape(Tp, Hp, Wp)
+    lab = np.full((Tp, Hp, Wp), -1)
+    lab[:grid.T, :grid.Hh, :grid.W] = full[:grid.T, :grid.Hh, :grid.W]
+    y = lab.reshape(nt, Ct, nh, Ch, nw, Cw).transpose(0, 2, 4, 1, 3, 5)
+    return y.reshape(-1)
+
+
+@pytest.mark.parametrize("grid,kcube", [(Grid(8, 8, 8), (2, 4, 2)), (Grid(5, 6, 7), (2, 4, 2)),
+                                        (Grid(4, 8, 6, 2, 4, 2), (1, 2, 2)), (Grid(4, 4, 8), (4, 4, 4))])
+def test_key_cube_labels_match_reshape_transpose(grid, kcube):
+    label, kcnt = orc.keycubes(grid, kcube)
+    want = keycube_labels_np(grid, kcube)
+    assert np.array_equal(label, want)
+    assert np.array_equal(kcnt, np.bincount(want[want >= 0], minlength=len(kcnt)))
+    valid, _ = orc.valid_mask(grid)
+    assert np.array_equal(label >= 0, valid)
+
+
+def test_key_cubes_equal_to_query_cubes_give_the_ordinary_method():
+    grid = Grid(5, 6, 7)
+    Np, Nc, Bk = grid.dims()
+    B, H, d, topk = 1, 2, 8, 3
+    valid, _ = orc.valid_mask(grid)
+    q, k, v, gc, gf, do = [rand(B, H, Np, d) * valid[None, None, :, None] for _ in range(6)]
+    a = orc.forward(grid, q, k, v, gc, gf, topk, want_sc=True)
+    b = orc.forward_kq(grid, (4, 4, 4), q, k, v, gc, gf, topk, want_sc=True)
+    assert np.array_equal(a["block_idx"], b["block_idx"])
+    for name in ("out", "out_fine", "lse_fine", "out_coarse", "lse_coarse", "sc"):
+        assert np.abs(a[name] - b[name]).max() < 1e-12, name
+    ga = orc.backward(grid, q, k, v, gc, gf, do, a["block_idx"], topk)
+    gb = orc.backward_kq(grid, (4, 4, 4), q, k, v, gc, gf, do, a["block_idx"], topk)
+    for name in ga:
+        assert np.abs(ga[name] - gb[name]).max() < 1e-12, name
+
+
+def test_key_cubes_all_selected_equals_dense_attention_over_valid_tokens():
+    grid, kcube = Grid(5, 6, 7), (2, 4, 2)   # the padded grid holds dead key cubes (t = 6, 7 are all pad)
+    Np, Nc, Bk = grid.dims()
+    label, kcnt = orc.keycubes(grid, kcube)
+    live = int((kcnt > 0).sum())
+    assert live < len(kcnt)
+    valid, _ = orc.valid_mask(grid)
+    B, H, d = 1, 2, 8
+    q, k, v = [rand(B, H, Np, d) * valid[None, None, :, None] for _ in range(3)]
+    ones = np.ones_like(q)
+    f = orc.forward_kq(grid, kcube, q, k, v, np.zeros_like(q), ones, live, want_sc=True)
+    assert np.array_equal(f["block_idx"][0, 0, 0], np.flatnonzero(kcnt > 0))
+    want = dense_attention(q, k, v, key_valid=valid[None, None, None, :]) * valid[None, None, :, None]
+    assert np.abs(f["out"] - want).max() < 1e-12
+    assert np.isneginf(f["sc"][..., kcnt == 0]).all() and np.isfinite(f["sc"][..., kcnt > 0]).all()
+    with pytest.raises(ValueError):
+        orc.forward_kq(grid, kcube, q, k, v, ones, ones, live + 1)
+
+
+def test_key_cube_lists_that_name_whole_cubes_give_the_fine_stage_of_the_ordinary_method():
+    grid, kcube = Grid(4, 8, 8), (2, 4, 2)
+    Np, Nc, Bk = grid.dims()
+    B, H, d, topk = 1, 2, 8, 2
+    q, k, v, gc, gf, do = [rand(B, H, Np, d) for _ in range(6)]
+    a = orc.forward(grid, q, k, v, gc, gf, topk)
+    sub = (a["block_idx"][..., None] * 4 + np.arange(4)).reshape(B, H, Nc, 4 * topk)
+    b = orc.forward_kq(grid, kcube, q, k, v, gc, gf, 4 * topk, block_idx=sub)
+    assert np.abs(a["out_fine"] - b["out_fine"]).max() < 1e-12 and np.abs(a["lse_fine"] - b["lse_fine"]).max() < 1e-12
+
+
+def torch_vsa_kq(grid, kcube, q, k, v, gc, gf, idx, scale):
+    """torch fp64 restatement with key cubes [Sec. 2.2 with the key side pooled and selected in smaller
+    cubes]: membership matrices instead of loops, indices frozen."""
+    Np, Nc, Bk = grid.dims()
+    label_np = keycube_labels_np(grid, kcube)
+    Nk = Nc * (grid.Ct // kcube[0]) * (grid.Ch // kcube[1]) * (grid.Cw // kcube[2])
+    label = torch.from_numpy(label_np)
+    valid = label >= 0
+    B, H, _, d = q.shape
+    memb_k = (label.view(1, Np) == torch.arange(Nk).view(Nk, 1)).double()         # [Nk, Np]
+    memb_q = ((torch.arange(Np) // Bk).view(1, Np) == torch.arange(Nc).view(Nc, 1)).double() * valid.double()
+    kcnt = memb_k.sum(1)
+    qc = memb_q @ q / memb_q.sum(1).view(Nc, 1)
+    kc = memb_k @ k / kcnt.clamp(min=1).view(Nk, 1)
+    vc = memb_k @ v / kcnt.clamp(min=1).view(Nk, 1)
+    sc = (qc @ kc.transpose(-1, -2) * scale).masked_fill(kcnt.view(1, 1, 1, Nk) == 0, float("-inf"))
+    oc = (torch.softmax(sc, dim=-1) @ vc).repeat_interleave(Bk, dim=2)
+    block = torch.zeros(B, H, Nc, Nk, dtype=torch.bool)
+    block.scatter_(-1, torch.from_numpy(idx).long(), True)
+    lab = label.clamp(min=0)
+    mask = block.repeat_interleave(Bk, 2)[..., lab] & valid.view(1, 1, 1, Np)
+    s = (q @ k.transpose(-1, -2) * scale).masked_fill(~mask, float("-inf"))
+    of = torch.softmax(s, dim=-1) @ v
+    out = oc * gc + of * (gf if gf is not None else 1.0)
+    return out * valid.view(1, 1, Np, 1)
+
+
+@pytest.mark.parametrize("grid,kcube,topk,with_gf", [(Grid(4, 8, 8), (2, 4, 2), 5, True), (Grid(5, 6, 7), (2, 4, 2), 7, True),
+                                                     (Grid(5, 6, 7), (2, 4, 2), 3, False), (Grid(4, 4, 6, 2, 2, 2), (1, 2, 1), 6, True)])
+def test_key_cube_forward_and_backward_match_torch_autograd(grid, kcube, topk, with_gf):
+    Np, Nc, Bk = grid.dims()
+    B, H, d = 1, 2, 8
+    valid, _ = orc.valid_mask(grid)
+    q, k, v, gc, gf, do = [rand(B, H, Np, d) * valid[None, None, :, None] for _ in range(6)]
+    if not with_gf:
+        gf = None
+    scale = 0.3
+    f = orc.forward_kq(grid, kcube, q, k, v, gc, gf, topk, scale=scale, want_sc=True)
+    idx = f["block_idx"]
+    # the selection itself: the topk largest finite logits of each row, ascending
+    for c in range(Nc):
+        row = f["sc"][0, 1, c]
+        assert np.array_equal(idx[0, 1, c], np.sort(np.argsort(-row, kind="stable")[:topk]))
+    tq, tk, tv, tgc = (torch.from_numpy(x).requires_grad_(True) for x in (q, k, v, gc))
+    tgf = torch.from_numpy(gf).requires_grad_(True) if with_gf else None
+    out = torch_vsa_kq(grid, kcube, tq, tk, tv, tgc, tgf, idx, scale)
+    assert np.abs(out.detach().numpy() - f["out"]).max() < 1e-12
+    (out * torch.from_numpy(do)).sum().backward()
+    b = orc.backward_kq(grid, kcube, q, k, v, gc, gf, do, idx, topk, scale=scale)
+    vm = valid[None, None, :, None]
+    assert np.abs(b["dq"] - tq.grad.numpy() * vm).max() < 1e-11
+    assert np.abs(b["dk"] - tk.grad.numpy() * vm).max() < 1e-11
+    assert np.abs(b["dv"] - tv.grad.numpy() * vm).max() < 1e-11
+    assert np.abs(b["dgate_c"] - tgc.grad.numpy()).max() < 1e-11
+    if with_gf:
+        assert np.abs(b["dgate_f"] - tgf.grad.numpy()).max() < 1e-11
+
+
 def test_paper_anchors():
     path = os.path.join(os.path.dirname(__file__), "golden", "paper_anchors.txt")
     gold = {}
