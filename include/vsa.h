@@ -80,6 +80,18 @@ typedef enum {
                                          even numbers of cubes along h and w (else VSA_ERR_UNSUPPORTED).
                                          Pass the flag to vsa_forward, vsa_backward and
                                          vsa_workspace_bytes alike. */
+#define VSA_FLAG_KEY_CUBES_16 128u /* the 64 x 16 tiles of the Sec. 3.2 tile-size tables: queries keep the (4,4,4)
+                                     cubes (and the tensors their token order), keys are pooled and selected
+                                     in the (2,4,2) boxes nested in them.  Key cube 4*c + 2a + b holds the
+                                     tokens of cube c with (t mod 4)/2 = a and (w mod 4)/2 = b; Nk = 4*Nc.
+                                     topk counts key cubes, 1 <= topk <= live key cubes =
+                                     ceil(T/2)*ceil(Hh/4)*ceil(W/2) (a key cube of a padded grid may hold
+                                     no valid token: it is left out of the coarse softmax and never
+                                     selected); block_idx is int32 [B,H,Nc,topk] of key cube numbers,
+                                     ascending.  Needs Ct,Ch,Cw = 4,4,4 and at most VSA_MAX_CUBES/4 cubes;
+                                     not together with VSA_FLAG_SELECT_POOLED_2X2; the coarse stage runs
+                                     as three launches.  Pass the flag to vsa_forward, vsa_backward and
+                                     vsa_workspace_bytes alike. */
 #define VSA_MIN_SOFTMAX_SCALE (1.0f / 64.0f) /* smallest explicit softmax_scale accepted (the pad-key bias of
                                                -30000 must still underflow the exponential once scaled) */
 #define VSA_MAX_CUBES 4096        /* largest supported Np / 64 (= Nc for 64-token cubes)  */

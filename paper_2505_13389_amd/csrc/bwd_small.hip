@@ -177,7 +177,8 @@ hipError_t gemm32(int batch, int M, int N, int Kd, float alpha, const float* a, 
 //   dsc holds dOc.Vc^T (dAc) -> becomes dSc = Ac * (dAc - sum_j Ac*dAc)
 // One wavefront per row, fixed reduction order.
 __global__ __launch_bounds__(256) void k_coarse_softmax_bwd(int rows, int Nc, const float* __restrict__ lse_c,
-                                                            float* __restrict__ sc, float* __restrict__ dsc) {
+                                                            float* __restrict__ sc, float* __restrict__ dsc,
+                                                            const int32_t* __restrict__ kcnt) {
   const int row = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
   if (row >= rows) return;
   float* s = sc + (long long)row * Nc;
@@ -185,7 +186,7 @@ __global__ __launch_bounds__(256) void k_coarse_softmax_bwd(int rows, int Nc, co
   const float lse = lse_c[row];
   float dot = 0.f;
   for (int j = lane; j < Nc; j += 64) {
-    const float a = fast_exp2((s[j] - lse) * kLog2e);
+    const float a = (!kcnt || kcnt[j] > 0) ? fast_exp2((s[j] - lse) * kLog2e) : 0.f;  // (a dead key cube: no weight)
     s[j] = a;
     dot = fmaf(a, ds[j], dot);
   }
@@ -194,26 +195,33 @@ __global__ __launch_bounds__(256) void k_coarse_softmax_bwd(int rows, int Nc, co
   for (int j = lane; j < Nc; j += 64) ds[j] = s[j] * (ds[j] - dot);
 }
 
-// Coarse backward: dVc = Ac^T dOc, dQc = scale dSc Kc, dKc = scale dSc^T Qc.
-// `ac` and `dsc` are [BH,Nc,Nc] scratch.
-hipError_t launch_coarse_bwd(int BH, int Nc, int d, float scale, const float* qc, const float* kc, const float* vc,
-                             const float* lse_c, const float* doc, float* ac, float* dsc, float* dqc, float* dkc,
-                             float* dvc, hipStream_t s) {
-  const long long sx = (long long)Nc * d, ss = (long long)Nc * Nc;
+// Coarse backward: dVc = Ac^T dOc, dQc = scale dSc Kc, dKc = scale dSc^T Qc, for Nq query cubes and Nk
+// key cubes (see launch_coarse).  `ac` and `dsc` are [BH,Nq,Nk] scratch.
+hipError_t launch_coarse_bwd(int BH, int Nq, int Nk, int d, float scale, const float* qc, const float* kc,
+                             const float* vc, const float* lse_c, const float* doc, float* ac, float* dsc, float* dqc,
+                             float* dkc, float* dvc, const int32_t* kcnt, hipStream_t s) {
+  const long long sq = (long long)Nq * d, sk = (long long)Nk * d, ss = (long long)Nq * Nk;
   hipError_t e;
   GemmSet set;
   // one launch: sc = scale * Qc Kc^T ; dAc = dOc Vc^T
-  set.p[0] = gemm_operands(scale, qc, sx, d, 1, kc, sx, 1, d, ac, ss);
-  set.p[1] = set.p[2] = gemm_operands(1.f, doc, sx, d, 1, vc, sx, 1, d, dsc, ss);
-  if ((e = gemm32_set(2, BH, Nc, Nc, d, set, s)) != hipSuccess) return e;
-  k_coarse_softmax_bwd<<<(BH * Nc + 3) / 4, 256, 0, s>>>(BH * Nc, Nc, lse_c, ac, dsc);
+  set.p[0] = gemm_operands(scale, qc, sq, d, 1, kc, sk, 1, d, ac, ss);
+  set.p[1] = set.p[2] = gemm_operands(1.f, doc, sq, d, 1, vc, sk, 1, d, dsc, ss);
+  if ((e = gemm32_set(2, BH, Nq, Nk, d, set, s)) != hipSuccess) return e;
+  k_coarse_softmax_bwd<<<(BH * Nq + 3) / 4, 256, 0, s>>>(BH * Nq, Nk, lse_c, ac, dsc, kcnt);
   if ((e = hipGetLastError()) != hipSuccess) return e;
-  // one launch: dVc[j][e] = sum_c Ac[c][j] dOc[c][e] ; dQc[c][e] = scale sum_j dSc[c][j] Kc[j][e] ;
-  //             dKc[j][e] = scale sum_c dSc[c][j] Qc[c][e]
-  set.p[0] = gemm_operands(1.f, ac, ss, 1, Nc, doc, sx, d, 1, dvc, sx);
-  set.p[1] = gemm_operands(scale, dsc, ss, Nc, 1, kc, sx, d, 1, dqc, sx);
-  set.p[2] = gemm_operands(scale, dsc, ss, 1, Nc, qc, sx, d, 1, dkc, sx);
-  return gemm32_set(3, BH, Nc, d, Nc, set, s);
+  // dVc[j][e] = sum_c Ac[c][j] dOc[c][e] ; dQc[c][e] = scale sum_j dSc[c][j] Kc[j][e] ;
+  // dKc[j][e] = scale sum_c dSc[c][j] Qc[c][e]: one launch when the three have the same shape
+  GemmOperands dv_ = gemm_operands(1.f, ac, ss, 1, Nk, doc, sq, d, 1, dvc, sk);
+  GemmOperands dq_ = gemm_operands(scale, dsc, ss, Nk, 1, kc, sk, d, 1, dqc, sq);
+  GemmOperands dk_ = gemm_operands(scale, dsc, ss, 1, Nk, qc, sq, d, 1, dkc, sk);
+  if (Nq == Nk) {
+    set.p[0] = dv_, set.p[1] = dq_, set.p[2] = dk_;
+    return gemm32_set(3, BH, Nq, d, Nq, set, s);
+  }
+  set.p[0] = dv_, set.p[1] = set.p[2] = dk_;
+  if ((e = gemm32_set(2, BH, Nk, d, Nq, set, s)) != hipSuccess) return e;
+  set.p[0] = set.p[1] = set.p[2] = dq_;
+  return gemm32_set(1, BH, Nq, d, Nk, set, s);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -230,21 +238,22 @@ constexpr int kMaxCubes = 4096;  // = 4 entries per thread of the 1024-thread sc
 // One workgroup per (b, h, word column w): the 32 query cubes 32w .. 32w+31 OR their bits into a
 // per-key word held in LDS, then every key row gets its word w written exactly once (no global
 // atomics, nothing to clear beforehand).
-__global__ __launch_bounds__(256) void k_map_bits(int Nc, int K, int W32, const int32_t* __restrict__ idx,
+// (Nq query cubes, Nrows key rows: Nrows = Nq, or 4 Nq when the lists name key cubes of 16 tokens)
+__global__ __launch_bounds__(256) void k_map_bits(int Nq, int Nrows, int K, int W32, const int32_t* __restrict__ idx,
                                                   uint32_t* __restrict__ bits) {
   __shared__ uint32_t word[kMaxCubes];
   const int w = blockIdx.x % W32, tid = threadIdx.x;
   const long long bh = blockIdx.x / W32;
-  for (int j = tid; j < Nc; j += 256) word[j] = 0u;
+  for (int j = tid; j < Nrows; j += 256) word[j] = 0u;
   __syncthreads();
-  const int q_lo = w * 32, nq = min(32, Nc - q_lo);
-  const int32_t* my = idx + (bh * Nc + q_lo) * (long long)K;
+  const int q_lo = w * 32, nq = min(32, Nq - q_lo);
+  const int32_t* my = idx + (bh * Nq + q_lo) * (long long)K;
   for (int e = tid; e < nq * K; e += 256) {
     const int c = my[e];
-    if (map_takes(c, Nc)) atomicOr(&word[c], 1u << (e / K));  // (a caller-supplied list is not trusted)
+    if (map_takes(c, Nrows)) atomicOr(&word[c], 1u << (e / K));  // (a caller-supplied list is not trusted)
   }
   __syncthreads();
-  for (int j = tid; j < Nc; j += 256) bits[(bh * Nc + j) * W32 + w] = word[j];
+  for (int j = tid; j < Nrows; j += 256) bits[(bh * Nrows + j) * W32 + w] = word[j];
 }
 
 // in-degree of every key cube: one wavefront per (b, h, j), written to row_ptr[bh][j] (scanned next)
@@ -446,6 +455,57 @@ __global__ __launch_bounds__(256) void k_map_fill(int Nc, int W32, long long row
   map_fill_row(bits + row * W32, W32, row_ptr[bh * (Nc + 1) + row % Nc], col + bh * col_stride, lane);
 }
 
+// Lists that name key cubes of 16 tokens (Sec. 3.2, the 64 x 16 row of the tile-size tables): the bit
+// matrix has one row per key cube, four per 64-row key block.  The dK/dV pass works on key blocks, so
+// the list of block j is the union of its four rows, and every entry carries, above the query block
+// number (bits 16..19), which of the four key cubes that query block selected.
+__global__ __launch_bounds__(256) void k_map_degree_sub(int Nc, int W32, long long rows, const uint32_t* __restrict__ bits,
+                                                        int32_t* __restrict__ row_ptr) {
+  const long long row = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);  // bh * Nc + j
+  const int lane = threadIdx.x & 63;
+  if (row >= rows) return;
+  const uint32_t* r = bits + row * 4 * W32;
+  int c = 0;
+  for (int w = lane; w < W32; w += 64) c += __popc(r[w] | r[W32 + w] | r[2 * W32 + w] | r[3 * W32 + w]);
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) c += __shfl_xor(c, o);
+  if (lane == 0) row_ptr[(row / Nc) * (Nc + 1) + row % Nc] = c;
+}
+__global__ __launch_bounds__(256) void k_map_fill_sub(int Nc, int W32, long long rows, const uint32_t* __restrict__ bits,
+                                                      const int32_t* __restrict__ row_ptr, int32_t* __restrict__ col,
+                                                      long long col_stride) {
+  const long long row = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);  // bh * Nc + j
+  const int lane = threadIdx.x & 63;
+  if (row >= rows) return;
+  const long long bh = row / Nc;
+  const uint32_t* r = bits + row * 4 * W32;
+  int32_t* cl = col + bh * col_stride;
+  int base = row_ptr[bh * (Nc + 1) + row % Nc];
+  for (int w0 = 0; w0 < W32; w0 += 64) {
+    uint32_t u[4] = {0u, 0u, 0u, 0u};
+    if (w0 + lane < W32) {
+#pragma unroll
+      for (int x = 0; x < 4; ++x) u[x] = r[x * W32 + w0 + lane];
+    }
+    uint32_t word = u[0] | u[1] | u[2] | u[3];
+    const int c = __popc(word);
+    int incl = c;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      int t = __shfl_up(incl, o);
+      if (lane >= o) incl += t;
+    }
+    int pos = base + incl - c;
+    while (word) {
+      const int b = __ffs(word) - 1;
+      const uint32_t sel = ((u[0] >> b) & 1u) | (((u[1] >> b) & 1u) << 1) | (((u[2] >> b) & 1u) << 2) | (((u[3] >> b) & 1u) << 3);
+      cl[pos++] = (int32_t)(((w0 + lane) * 32 + b) | (sel << 16));
+      word &= word - 1;
+    }
+    base += __shfl(incl, 63);
+  }
+}
+
 // The whole map of one (b, h) in ONE launch, for short sequences (the bit matrix of a (b, h) fits in LDS
 // up to kMapOneLaunchMaxCubes key cubes): the four steps above by the 1024 threads of one workgroup --
 // bits OR-ed into LDS, in-degrees, scan and work items, lists -- instead of four launches.
@@ -505,15 +565,26 @@ __global__ __launch_bounds__(1024) void k_map_one_launch(int Nc, int K, int W32,
 }
 
 hipError_t launch_transpose_map(int BH, int Nc, int K, const int32_t* idx, uint32_t* bits, int32_t* row_ptr,
-                                int32_t* col, int32_t* order, int32_t* split, int seg, int cap, hipStream_t s) {
+                                int32_t* col, int32_t* order, int32_t* split, int seg, int cap, int key_cubes_16,
+                                hipStream_t s) {
   const int W32 = (Nc + 31) / 32;
   const long long rows = (long long)BH * Nc;
   hipError_t e;
+  if (key_cubes_16) {  // K entries per query block, each a key cube of 16 tokens; bits is [BH, 4 Nc, W32]
+    k_map_bits<<<(unsigned)(BH * W32), 256, 0, s>>>(Nc, 4 * Nc, K, W32, idx, bits);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    k_map_degree_sub<<<(unsigned)((rows + 3) / 4), 256, 0, s>>>(Nc, W32, rows, bits, row_ptr);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    k_map_scan<<<BH, 1024, 0, s>>>(Nc, seg, cap, row_ptr, order, split);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    k_map_fill_sub<<<(unsigned)((rows + 3) / 4), 256, 0, s>>>(Nc, W32, rows, bits, row_ptr, col, (long long)Nc * K);
+    return hipGetLastError();
+  }
   if (Nc <= kMapOneLaunchMaxCubes) {
     k_map_one_launch<<<BH, 1024, 0, s>>>(Nc, K, W32, seg, cap, idx, row_ptr, col, (long long)Nc * K, order, split);
     return hipGetLastError();
   }
-  k_map_bits<<<(unsigned)(BH * W32), 256, 0, s>>>(Nc, K, W32, idx, bits);
+  k_map_bits<<<(unsigned)(BH * W32), 256, 0, s>>>(Nc, Nc, K, W32, idx, bits);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   k_map_degree<<<(unsigned)((rows + 3) / 4), 256, 0, s>>>(Nc, W32, rows, bits, row_ptr);
   if ((e = hipGetLastError()) != hipSuccess) return e;

@@ -52,13 +52,18 @@ __device__ __forceinline__ uint32_t wave_umax(uint32_t x) { return wave_reduce_b
 // lane).  `srow` may point into global memory or into LDS.  Writes the row's probabilities back over
 // the logits, its log-sum-exp to *lse_out (if given) and, with emit_idx, the ascending list of its K
 // largest logits (ties to the lower index) to `out`.
+// `kcnt` (optional): valid tokens per key cube; a key cube with none is dead -- its logit counts as -inf,
+// so it gets probability 0 and, K not exceeding the number of live key cubes, is never selected.
 template <int NCH>
 __device__ __forceinline__ void coarse_row(float* srow, int Nc, int K, float* lse_out, int32_t* out, int emit_idx,
-                                           int lane) {
+                                           int lane, const int32_t* __restrict__ kcnt = nullptr) {
   const int nch = (Nc + 63) / 64;
   float s[NCH];
 #pragma unroll
-  for (int ch = 0; ch < NCH; ++ch) s[ch] = (ch * 64 + lane < Nc) ? srow[ch * 64 + lane] + 0.f : -INFINITY;
+  for (int ch = 0; ch < NCH; ++ch) {
+    const int j = ch * 64 + lane;
+    s[ch] = (j < Nc && (!kcnt || kcnt[j] > 0)) ? srow[j] + 0.f : -INFINITY;
+  }
 
   float m = -INFINITY;
 #pragma unroll
@@ -136,11 +141,11 @@ __device__ __forceinline__ void coarse_row(float* srow, int Nc, int K, float* ls
 template <int NCH>
 __global__ __launch_bounds__(256) void k_coarse_rows(int rows, int Nc, int K, float* __restrict__ sc,
                                                      float* __restrict__ lse_c, int32_t* __restrict__ idx,
-                                                     int emit_idx) {
+                                                     int emit_idx, const int32_t* __restrict__ kcnt) {
   const int row = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
   if (row >= rows) return;
   coarse_row<NCH>(sc + (long long)row * Nc, Nc, K, lse_c ? lse_c + row : nullptr, idx + (long long)row * K, emit_idx,
-                  lane);
+                  lane, kcnt);
 }
 
 // The whole coarse stage in ONE launch, the score block never leaving the chip (Sec. 2.4 fuses
@@ -305,11 +310,15 @@ hipError_t launch_expand_lists(int BH, int Nc, int K, int m, const int32_t* idx,
   return hipGetLastError();
 }
 
-hipError_t launch_coarse(int BH, int Nc, int d, int K, float scale, const float* qc, const float* kc, const float* vc,
-                         float* sc, float* oc, float* lse_c, int32_t* idx, int emit_idx, int fused, hipStream_t s) {
-  const long long sx = (long long)Nc * d, ss = (long long)Nc * Nc;
+// Nq query cubes against Nk key cubes (Nk = Nq, or 4 Nq with key cubes of 16 tokens, where `kcnt` marks
+// the dead ones); sc is [BH,Nq,Nk].
+hipError_t launch_coarse(int BH, int Nq, int Nk, int d, int K, float scale, const float* qc, const float* kc,
+                         const float* vc, float* sc, float* oc, float* lse_c, int32_t* idx, int emit_idx, int fused,
+                         const int32_t* kcnt, hipStream_t s) {
+  const long long sq = (long long)Nq * d, sk = (long long)Nk * d, ss = (long long)Nq * Nk;
   hipError_t e;
-  if (Nc <= kFusedMaxCubes && fused) {
+  if (Nq == Nk && !kcnt && Nk <= kFusedMaxCubes && fused) {
+    const int Nc = Nq;
     const unsigned fgrid = (unsigned)(BH * ((Nc + 15) / 16));
 #define VSA_FUSED(NCH_)                                                                                             \
   do {                                                                                                              \
@@ -327,28 +336,23 @@ hipError_t launch_coarse(int BH, int Nc, int d, int K, float scale, const float*
 #undef VSA_FUSED
     return hipGetLastError();
   }
-  if ((e = gemm32(BH, Nc, Nc, d, scale, qc, sx, d, 1, kc, sx, 1, d, sc, ss, s)) != hipSuccess) return e;
-  const int rows = BH * Nc;
+  if ((e = gemm32(BH, Nq, Nk, d, scale, qc, sq, d, 1, kc, sk, 1, d, sc, ss, s)) != hipSuccess) return e;
+  const int rows = BH * Nq;
   const unsigned grid = (unsigned)((rows + 3) / 4);
-  // NCH = logits per lane (compile-time bound of the per-lane loops): the smallest that covers Nc
-  if (Nc <= 64)
-    k_coarse_rows<1><<<grid, 256, 0, s>>>(rows, Nc, K, sc, lse_c, idx, emit_idx);
-  else if (Nc <= 128)
-    k_coarse_rows<2><<<grid, 256, 0, s>>>(rows, Nc, K, sc, lse_c, idx, emit_idx);
-  else if (Nc <= 256)
-    k_coarse_rows<4><<<grid, 256, 0, s>>>(rows, Nc, K, sc, lse_c, idx, emit_idx);
-  else if (Nc <= 512)
-    k_coarse_rows<8><<<grid, 256, 0, s>>>(rows, Nc, K, sc, lse_c, idx, emit_idx);
-  else if (Nc <= 768)
-    k_coarse_rows<12><<<grid, 256, 0, s>>>(rows, Nc, K, sc, lse_c, idx, emit_idx);
-  else if (Nc <= 1024)
-    k_coarse_rows<16><<<grid, 256, 0, s>>>(rows, Nc, K, sc, lse_c, idx, emit_idx);
-  else if (Nc <= 1536)
-    k_coarse_rows<24><<<grid, 256, 0, s>>>(rows, Nc, K, sc, lse_c, idx, emit_idx);
-  else
-    k_coarse_rows<64><<<grid, 256, 0, s>>>(rows, Nc, K, sc, lse_c, idx, emit_idx);
+  // NCH = logits per lane (compile-time bound of the per-lane loops): the smallest that covers Nk
+#define VSA_ROWS(NCH_) k_coarse_rows<NCH_><<<grid, 256, 0, s>>>(rows, Nk, K, sc, lse_c, idx, emit_idx, kcnt)
+  if (Nk <= 64) VSA_ROWS(1);
+  else if (Nk <= 128) VSA_ROWS(2);
+  else if (Nk <= 256) VSA_ROWS(4);
+  else if (Nk <= 512) VSA_ROWS(8);
+  else if (Nk <= 768) VSA_ROWS(12);
+  else if (Nk <= 1024) VSA_ROWS(16);
+  else if (Nk <= 1536) VSA_ROWS(24);
+  else if (Nk <= 2560) VSA_ROWS(40);
+  else VSA_ROWS(64);
+#undef VSA_ROWS
   if ((e = hipGetLastError()) != hipSuccess) return e;
-  return gemm32(BH, Nc, d, Nc, 1.f, sc, ss, Nc, 1, vc, sx, d, 1, oc, sx, s);
+  return gemm32(BH, Nq, d, Nk, 1.f, sc, ss, Nk, 1, vc, sk, d, 1, oc, sq, s);
 }
 
 // Top-K on the pooled coarse map: P [BH,Nc,Nc] (probabilities, as launch_coarse leaves them in its
@@ -362,11 +366,11 @@ hipError_t launch_pooled_select(int BH, int Nt, int Nh, int Nw, int K, const flo
   if (e != hipSuccess) return e;
   const int rows = BH * Ns;
   const unsigned grid = (unsigned)((rows + 3) / 4);
-  if (Ns <= 64) k_coarse_rows<1><<<grid, 256, 0, s>>>(rows, Ns, K, ps, nullptr, tile_idx, 1);
-  else if (Ns <= 128) k_coarse_rows<2><<<grid, 256, 0, s>>>(rows, Ns, K, ps, nullptr, tile_idx, 1);
-  else if (Ns <= 256) k_coarse_rows<4><<<grid, 256, 0, s>>>(rows, Ns, K, ps, nullptr, tile_idx, 1);
-  else if (Ns <= 512) k_coarse_rows<8><<<grid, 256, 0, s>>>(rows, Ns, K, ps, nullptr, tile_idx, 1);
-  else k_coarse_rows<16><<<grid, 256, 0, s>>>(rows, Ns, K, ps, nullptr, tile_idx, 1);
+  if (Ns <= 64) k_coarse_rows<1><<<grid, 256, 0, s>>>(rows, Ns, K, ps, nullptr, tile_idx, 1, nullptr);
+  else if (Ns <= 128) k_coarse_rows<2><<<grid, 256, 0, s>>>(rows, Ns, K, ps, nullptr, tile_idx, 1, nullptr);
+  else if (Ns <= 256) k_coarse_rows<4><<<grid, 256, 0, s>>>(rows, Ns, K, ps, nullptr, tile_idx, 1, nullptr);
+  else if (Ns <= 512) k_coarse_rows<8><<<grid, 256, 0, s>>>(rows, Ns, K, ps, nullptr, tile_idx, 1, nullptr);
+  else k_coarse_rows<16><<<grid, 256, 0, s>>>(rows, Ns, K, ps, nullptr, tile_idx, 1, nullptr);
   return hipGetLastError();
 }
 

@@ -20,7 +20,7 @@ namespace vsa {
 // ---------------------------------------------------------------------------------------------
 // dQ pass: one workgroup per (b, h, query cube); streams the K selected (K tile, V tile) pairs.
 // Wavefront (qh, kh): query rows qh*32..+31, key rows kh*32..+31 of each tile.
-template <int D>
+template <int D, class LIST>
 __global__ __launch_bounds__(256, 2) void k_fine_bwd_dq(int Nc, int K, float sl2, float scale, const uint4* __restrict__ q,
                                                         const uint4* __restrict__ k, const uint4* __restrict__ v,
                                                         const uint4* __restrict__ dof, const int32_t* __restrict__ idx,
@@ -36,12 +36,13 @@ __global__ __launch_bounds__(256, 2) void k_fine_bwd_dq(int Nc, int K, float sl2
   static_assert(2 * 32 * OS * 4 <= STAGE, "merge buffer must fit in one stage");
 
   // (K = Nc: plain blockIdx order and staggered walks, as in the forward kernel)
-  const bool same_lists = K == Nc;
+  const int NT = (K + LIST::kEntriesPerTile - 1) / LIST::kEntriesPerTile;  // the walk is in tiles of 64 keys
+  const bool same_lists = K == Nc * LIST::kEntriesPerTile;
   const unsigned wg = same_lists ? blockIdx.x : xcd_chunked_id(blockIdx.x, gridDim.x);
   const int c = wg % Nc;
   const long long bh = wg / Nc;
-  const int rot = same_lists ? ((c >> 3) & 15) % K : 0;
-  auto ent = [&](int t) { const int e = t + rot; return e >= K ? e - K : e; };
+  const int rot = same_lists ? ((c >> 3) & 15) % NT : 0;
+  auto ent = [&](int t) { const int e = t + rot; return e >= NT ? e - NT : e; };
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int qh = wave & 1, kh = wave >> 1, l32 = lane & 31, h = lane >> 5;
   const long long rows0 = bh * (long long)Nc * kTile;
@@ -54,13 +55,13 @@ __global__ __launch_bounds__(256, 2) void k_fine_bwd_dq(int Nc, int K, float sl2
   // place its wait for them right there (it also drains the copy, which it cannot see), and its own
   // vmcnt bookkeeping has nothing left to wait for inside the loop (see Tile::async_load).
   unsigned goff[TL::IPW];
-  TL::lane_offsets(wave, lane, goff);
-  CubeList cubes;
-  cubes.init(my_idx, mask, K, kh, lane, Nc);
+  LIST::template offsets<TL>(wave, lane, goff);
+  LIST cubes;
+  cubes.init(my_idx, mask, K, kh, wave, lane, Nc);
   {
-    const int jt = cubes.cube(ent(0));
-    TL::async_load(k, rows0 + (long long)jt * kTile, stage0, wave, goff);
-    TL::async_load(v, rows0 + (long long)jt * kTile, stage0 + TL::BYTES, wave, goff);
+    const int jt = cubes.first_row(ent(0));  // first source row of this wave's share
+    TL::async_load(k, rows0 + jt, stage0, wave, goff);
+    TL::async_load(v, rows0 + jt, stage0 + TL::BYTES, wave, goff);
   }
   cubes.load_masks();
   const long long qrow_g = rows0 + c * kTile + qh * 32 + l32;
@@ -83,7 +84,7 @@ __global__ __launch_bounds__(256, 2) void k_fine_bwd_dq(int Nc, int K, float sl2
   uint32_t km_cur;  // valid-key mask (this wave's key half) of the tile of this iteration
   {
     int jt;
-    cubes.get(ent(0), jt, km_cur);
+    cubes.get_tile(ent(0), jt, km_cur);
   }
 
   f32x16 acc[DVB];
@@ -124,9 +125,9 @@ __global__ __launch_bounds__(256, 2) void k_fine_bwd_dq(int Nc, int K, float sl2
     // the same moment queue up behind one another in the load path and stall -- but one
     // instruction per matrix step below.
     int jt = 0;
-    if (COPY) cubes.get(ent(t + 1), jt, km_cur);
-    const void* gk = uniform_ptr(k + (rows0 + (long long)jt * kTile) * CPR);
-    const void* gv = uniform_ptr(v + (rows0 + (long long)jt * kTile) * CPR);
+    if (COPY) cubes.get_tile(ent(t + 1), jt, km_cur);
+    const void* gk = uniform_ptr(k + (rows0 + jt) * CPR);
+    const void* gv = uniform_ptr(v + (rows0 + jt) * CPR);
     const unsigned ln = __builtin_amdgcn_readfirstlane(lds_address(nxt) + (unsigned)(wave * TL::IPW) * 1024u);
     auto copy_piece = [&](int i) {
       if (!COPY) return;
@@ -200,11 +201,11 @@ __global__ __launch_bounds__(256, 2) void k_fine_bwd_dq(int Nc, int K, float sl2
     const std::true_type copy;
     const std::false_type last;
     int t = 0;
-    for (; t + 2 < K; t += 2) {
+    for (; t + 2 < NT; t += 2) {
       body(copy, stage0, stage1, t);
       body(copy, stage1, stage0, t + 1);
     }
-    if (t + 1 < K) {
+    if (t + 1 < NT) {
       body(copy, stage0, stage1, t);
       body(last, stage1, stage0, t + 1);
     } else {
@@ -253,16 +254,34 @@ __global__ __launch_bounds__(256, 2) void k_fine_bwd_dq(int Nc, int K, float sl2
 
 hipError_t launch_fine_bwd_dq(int BH, int Nc, int d, int K, float scale, const void* q, const void* k, const void* v,
                               const void* dof, const int32_t* idx, const float* ld,
-                              const float* dqc, const uint64_t* mask, void* dq, int m_blocks, hipStream_t s) {
+                              const float* dqc, const uint64_t* mask, void* dq, int m_blocks, int key_cubes_16,
+                              hipStream_t s) {
   const float sl2 = scale * kLog2e;
   const unsigned grid = (unsigned)(BH * Nc);
-  if (d == 128)
-    k_fine_bwd_dq<128><<<grid, 256, 0, s>>>(Nc, K, sl2, scale, (const uint4*)q, (const uint4*)k, (const uint4*)v,
-                                            (const uint4*)dof, idx, ld, dqc, mask, (uint4*)dq, m_blocks);
-  else
-    k_fine_bwd_dq<64><<<grid, 256, 0, s>>>(Nc, K, sl2, scale, (const uint4*)q, (const uint4*)k, (const uint4*)v,
-                                           (const uint4*)dof, idx, ld, dqc, mask, (uint4*)dq, m_blocks);
+#define VSA_DQ(D_, LIST_)                                                                                          \
+  k_fine_bwd_dq<D_, LIST_><<<grid, 256, 0, s>>>(Nc, K, sl2, scale, (const uint4*)q, (const uint4*)k, (const uint4*)v, \
+                                                (const uint4*)dof, idx, ld, dqc, mask, (uint4*)dq, m_blocks)
+  if (key_cubes_16) {  // K counts key cubes of 16 tokens
+    if (d == 128) VSA_DQ(128, SubCubeList);
+    else VSA_DQ(64, SubCubeList);
+  } else {
+    if (d == 128) VSA_DQ(128, CubeList);
+    else VSA_DQ(64, CubeList);
+  }
+#undef VSA_DQ
   return hipGetLastError();
+}
+
+// Key cubes of 16 tokens: the pooled-gradient term of row r of a key block, chunk ch -- the pooled
+// gradient of the row's key cube (rows 4*block .. 4*block+3 of `pooled`) over the cube's valid tokens.
+__device__ __forceinline__ void subcube_pooled_term(const float* __restrict__ pooled, long long first_row, uint64_t kmask,
+                                                    int r, int D, int ch, float* out) {
+  const int sc = 2 * (r >> 5) + ((r >> 1) & 1);
+  const float inv = 1.0f / (float)__popcll(kmask & subcube_pattern(sc));  // (row r is valid: at least 1)
+  const float* p = pooled + (first_row + sc) * D + ch * 8;
+  const float4 p0 = *(const float4*)p, p1 = *(const float4*)(p + 4);
+  out[0] = p0.x * inv; out[1] = p0.y * inv; out[2] = p0.z * inv; out[3] = p0.w * inv;
+  out[4] = p1.x * inv; out[5] = p1.y * inv; out[6] = p1.z * inv; out[7] = p1.w * inv;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -286,7 +305,12 @@ hipError_t launch_fine_bwd_dq(int BH, int Nc, int d, int K, float scale, const v
 // complete; every wave done reading tile t), refill the stage of tile t with tile t+4.  Past the
 // end of the list the last tile is fetched again, so the number of copies in flight is the same
 // in every iteration.
-template <int D>
+//
+// SUB: the lists name key cubes of 16 tokens (Sec. 3.2, the 64 x 16 row of the tile-size tables).  The
+// workgroup still owns a 64-row key block; its list is the union of the lists of the block's four key
+// cubes, and every entry says (bits 16..19) which of them the query block selected: the other key rows
+// get the pad-key bias for that tile.  The pooled-gradient terms are per key cube.
+template <int D, bool SUB>
 __global__ __launch_bounds__(256, 1) void k_fine_bwd_dkv(int Nc, int K, float sl2, float scale, const uint4* __restrict__ q,
                                                          const uint4* __restrict__ k, const uint4* __restrict__ v,
                                                          const uint4* __restrict__ dof,
@@ -350,7 +374,7 @@ __global__ __launch_bounds__(256, 1) void k_fine_bwd_dkv(int Nc, int K, float sl
     unsigned goff[TL::IPW];
     TL::lane_offsets(wave, lane, goff);
     const unsigned lds0 = lds_address(smem);
-    auto entry = [&](int t) {  // cube of list entry min(t, end - 1)
+    auto entry = [&](int t) {  // list entry min(t, end - 1): the query block (SUB: and the selected key cubes above it)
       const int e = min(t, end - 1) - beg;
       if ((e >> 6) != chunk) {
         chunk = e >> 6;
@@ -361,7 +385,8 @@ __global__ __launch_bounds__(256, 1) void k_fine_bwd_dkv(int Nc, int K, float sl
     };
     // fill stage `st` with the tiles of list entry min(t, end-1); every wave issues NLP copies
     auto fill = [&](int st, int t) {
-      const long long r0 = rows0 + (long long)entry(t) * kTile;
+      const int raw = entry(t);
+      const long long r0 = rows0 + (long long)(SUB ? raw & 0xffff : raw) * kTile;
       unsigned char* sp = smem + st * STAGE;
       TL::async_load(q, r0, sp, wave, goff);
       TL::async_load(dof, r0, sp + TL::BYTES, wave, goff);
@@ -380,6 +405,16 @@ __global__ __launch_bounds__(256, 1) void k_fine_bwd_dkv(int Nc, int K, float sl
       bias_b[0] = bias_b[1] = bias_b[2] = (__bf16)1.f;
       bias_b[3] = kvalid ? (__bf16)0.f : (__bf16)-30000.f;
     }
+    // SUB: slot 3 per tile -- this lane's key row takes part iff it is valid and its key cube
+    // (2*kh + (row/2)%2 of the block's four) is among those the query block of the tile selected
+    const int my_sub = 2 * kh + ((l32 >> 1) & 1);
+    auto set_bias = [&](int raw_entry) {
+      if (!SUB) return;
+      const bool on = kvalid && (((raw_entry >> 16) >> my_sub) & 1);
+      uint4 u = __builtin_bit_cast(uint4, bias_b);
+      u.y = h == 0 ? (0x3f80u | (on ? 0u : 0xc6ea0000u)) : 0u;  // (1, bias): bf16 1.0 and bf16(-29952)
+      bias_b = __builtin_bit_cast(bf16x8, u);
+    };
     auto row_read = [&](const unsigned char* stage) {
       return *(const uint4*)(stage + 2 * TL::BYTES + (qh * 32 + l32) * 16);
     };
@@ -417,10 +452,20 @@ __global__ __launch_bounds__(256, 1) void k_fine_bwd_dkv(int Nc, int K, float sl
     fill(1, beg + 1);
     fill(2, beg + 2);
     fill(3, beg + 3);
+    // SUB: the entries of tiles t+2 and t+3 at the top of iteration t (iteration t forms S' of tile t+2),
+    // kept from the fills that fetched them; the first two tiles are formed right here
+    int ent_first = 0, ent_second = 0, ent_hist0 = 0, ent_hist1 = 0;
+    if (SUB) {
+      ent_first = entry(beg);
+      ent_second = entry(beg + 1);
+      ent_hist0 = entry(beg + 2);
+      ent_hist1 = entry(beg + 3);
+    }
     wait_vmcnt<2 * NLP>();
     __builtin_amdgcn_s_barrier();
     {
       f32x16 s0, dp0;
+      set_bias(ent_first);
       s_dp(0, s0, dp0);
       float p[16], ds[16];
 #pragma unroll
@@ -437,6 +482,7 @@ __global__ __launch_bounds__(256, 1) void k_fine_bwd_dkv(int Nc, int K, float sl
         qt[x][0] = TL::transposed_operand(smem, qh * 32, 0, x * 32, lane);
         qt[x][1] = TL::transposed_operand(smem, qh * 32, 1, x * 32, lane);
       }
+      set_bias(ent_second);
       s_dp(1, sA, dpA);
     }
 
@@ -459,7 +505,11 @@ __global__ __launch_bounds__(256, 1) void k_fine_bwd_dkv(int Nc, int K, float sl
       wait_vmcnt<NLP>();  // this wave's share of tile t+2 has landed
       __builtin_amdgcn_s_barrier();
       __builtin_amdgcn_sched_barrier(0);
-      const long long r0 = rows0 + (long long)entry(t + 4) * kTile;
+      const int raw4 = entry(t + 4);
+      const int raw2 = ent_hist0;  // SUB: the entry of tile t+2, whose S' this iteration forms
+      ent_hist0 = ent_hist1;
+      ent_hist1 = raw4;
+      const long long r0 = rows0 + (long long)(SUB ? raw4 & 0xffff : raw4) * kTile;
       const void* gq = uniform_ptr(q + r0 * CPR);
       const void* gd = uniform_ptr(dof + r0 * CPR);
       const void* gl = uniform_ptr(ldb + r0);
@@ -541,6 +591,7 @@ __global__ __launch_bounds__(256, 1) void k_fine_bwd_dkv(int Nc, int K, float sl
         if (i == NB - 4) {  // the operands of the two bias steps are put together here, not earlier
           asm volatile("" : "+v"(rowv.x), "+v"(rowv.y), "+v"(rowv.z), "+v"(rowv.w));
           row_slots(rowv, la, dla);
+          set_bias(raw2);
         }
         __builtin_amdgcn_sched_barrier(0);
       }
@@ -559,8 +610,8 @@ __global__ __launch_bounds__(256, 1) void k_fine_bwd_dkv(int Nc, int K, float sl
   // the pooled-gradient terms of this thread's column chunk (the same chunk for all of its items),
   // requested before the partial results go through LDS
   static_assert(256 % CPR == 0, "a thread keeps its column chunk");
-  float4 pk[2], pv[2];
-  {
+  float4 pk[2] = {}, pv[2] = {};
+  if (!SUB) {
     const float* a = dkc + ((bh * Nc + j) / m_blocks) * D + (tid % CPR) * 8;  // per cube = m_blocks blocks
     const float* b = dvc + ((bh * Nc + j) / m_blocks) * D + (tid % CPR) * 8;
     pk[0] = *(const float4*)a, pk[1] = *(const float4*)(a + 4);
@@ -623,8 +674,15 @@ __global__ __launch_bounds__(256, 1) void k_fine_bwd_dkv(int Nc, int K, float sl
       uint4 ov = make_uint4(0, 0, 0, 0);
       if ((kmask >> r) & 1) {
         float res[8];
+        if (SUB) {
+          float pl[8];
+          subcube_pooled_term(pass == 0 ? dkc : dvc, (bh * Nc + j) * 4, kmask, r, D, ch, pl);
 #pragma unroll
-        for (int e = 0; e < 8; ++e) res[e] = fmaf(sum[e], mul, pooled[e]);
+          for (int e = 0; e < 8; ++e) res[e] = fmaf(sum[e], mul, pl[e]);
+        } else {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) res[e] = fmaf(sum[e], mul, pooled[e]);
+        }
         ov = pack8(res);
       }
       dst[(rows0 + j * kTile + r) * CPR + ch] = ov;
@@ -635,7 +693,7 @@ __global__ __launch_bounds__(256, 1) void k_fine_bwd_dkv(int Nc, int K, float sl
 // Sums the fp32 partial results of the split lists in slot order and finishes them like the dK/dV
 // epilogue does (scale, pooled-gradient term, zero pad rows, one rounding to bf16).  One workgroup
 // per possible split list of a (b, h); those beyond the actual number exit at once.
-template <int D>
+template <int D, bool SUB>
 __global__ __launch_bounds__(256) void k_dkv_reduce(int Nc, int cap, float scale, const int32_t* __restrict__ split,
                                                     const float* __restrict__ parts, const float* __restrict__ dkc,
                                                     const float* __restrict__ dvc, const uint64_t* __restrict__ mask,
@@ -671,8 +729,15 @@ __global__ __launch_bounds__(256) void k_dkv_reduce(int Nc, int cap, float scale
       uint4 ov = make_uint4(0, 0, 0, 0);
       if ((kmask >> r) & 1) {
         float res[8];
+        if (SUB) {
+          float pl[8];
+          subcube_pooled_term(pass == 0 ? dkc : dvc, (bh * Nc + j) * 4, kmask, r, D, ch, pl);
 #pragma unroll
-        for (int e = 0; e < 8; ++e) res[e] = fmaf(sum[e], mul, pooled[e]);
+          for (int e = 0; e < 8; ++e) res[e] = fmaf(sum[e], mul, pl[e]);
+        } else {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) res[e] = fmaf(sum[e], mul, pooled[e]);
+        }
         ov = pack8(res);
       }
       dst[(rows0 + j * kTile + r) * CPR + ch] = ov;
@@ -683,21 +748,26 @@ __global__ __launch_bounds__(256) void k_dkv_reduce(int Nc, int cap, float scale
 hipError_t launch_fine_bwd_dkv(int BH, int Nc, int d, int K, float scale, const void* q, const void* k, const void* v,
                                const void* dof, const int32_t* col, const int32_t* order, const int32_t* split,
                                float* parts, int cap, const void* ldb, const float* dkc, const float* dvc,
-                               const uint64_t* mask, void* dk, void* dv, int m_blocks, hipStream_t s) {
+                               const uint64_t* mask, void* dk, void* dv, int m_blocks, int key_cubes_16, hipStream_t s) {
   const float sl2 = scale * kLog2e;
   const int items = Nc + cap;
   const unsigned grid = (unsigned)(BH * items), rgrid = (unsigned)(BH * (cap / 2));
-  if (d == 128) {
-    k_fine_bwd_dkv<128><<<grid, 256, 0, s>>>(Nc, K, sl2, scale, (const uint4*)q, (const uint4*)k, (const uint4*)v,
-                                             (const uint4*)dof, col, order, items, parts, cap, (const uint4*)ldb, dkc,
-                                             dvc, mask, (uint4*)dk, (uint4*)dv, m_blocks);
-    k_dkv_reduce<128><<<rgrid, 256, 0, s>>>(Nc, cap, scale, split, parts, dkc, dvc, mask, (uint4*)dk, (uint4*)dv, m_blocks);
+#define VSA_DKV(D_, SUB_)                                                                                                \
+  do {                                                                                                                   \
+    k_fine_bwd_dkv<D_, SUB_><<<grid, 256, 0, s>>>(Nc, K, sl2, scale, (const uint4*)q, (const uint4*)k, (const uint4*)v,    \
+                                                  (const uint4*)dof, col, order, items, parts, cap, (const uint4*)ldb,   \
+                                                  dkc, dvc, mask, (uint4*)dk, (uint4*)dv, m_blocks);                      \
+    k_dkv_reduce<D_, SUB_><<<rgrid, 256, 0, s>>>(Nc, cap, scale, split, parts, dkc, dvc, mask, (uint4*)dk, (uint4*)dv,    \
+                                                 m_blocks);                                                              \
+  } while (0)
+  if (key_cubes_16) {  // lists of key cubes of 16 tokens: the pooled terms dkc, dvc are [BH, 4 Nc, d]
+    if (d == 128) VSA_DKV(128, true);
+    else VSA_DKV(64, true);
   } else {
-    k_fine_bwd_dkv<64><<<grid, 256, 0, s>>>(Nc, K, sl2, scale, (const uint4*)q, (const uint4*)k, (const uint4*)v,
-                                            (const uint4*)dof, col, order, items, parts, cap, (const uint4*)ldb, dkc,
-                                            dvc, mask, (uint4*)dk, (uint4*)dv, m_blocks);
-    k_dkv_reduce<64><<<rgrid, 256, 0, s>>>(Nc, cap, scale, split, parts, dkc, dvc, mask, (uint4*)dk, (uint4*)dv, m_blocks);
+    if (d == 128) VSA_DKV(128, false);
+    else VSA_DKV(64, false);
   }
+#undef VSA_DKV
   return hipGetLastError();
 }
 

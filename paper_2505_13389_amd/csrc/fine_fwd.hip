@@ -32,7 +32,7 @@ __device__ __forceinline__ float max_across_halves(float x) {
   return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
 }
 
-template <int D>
+template <int D, class LIST>
 __global__ __launch_bounds__(256, 2) void k_fine_fwd(int Nc, int K, float sl2, const uint4* __restrict__ q,
                                                      const uint4* __restrict__ k, const uint4* __restrict__ v,
                                                      const uint4* __restrict__ gc, const uint4* __restrict__ gf,
@@ -56,12 +56,14 @@ __global__ __launch_bounds__(256, 2) void k_fine_fwd(int Nc, int K, float sl2, c
   // (plain blockIdx order), which keeps that list's tiles shared chip-wide, and the workgroups that
   // run side by side on an XCD (cubes c, c+8, ...) start their walk a few entries apart and wrap
   // around -- otherwise they ask for the same cache lines in the same cycles.
-  const bool same_lists = K == Nc;
+  // (The walk is in tiles of 64 keys: one list entry, or four entries that name key cubes of 16 tokens.)
+  const int NT = (K + LIST::kEntriesPerTile - 1) / LIST::kEntriesPerTile;
+  const bool same_lists = K == Nc * LIST::kEntriesPerTile;
   const unsigned wg = same_lists ? blockIdx.x : xcd_chunked_id(blockIdx.x, gridDim.x);
   const int c = wg % Nc;
   const long long bh = wg / Nc;
-  const int rot = same_lists ? ((c >> 3) & 15) % K : 0;
-  auto ent = [&](int t) { const int e = t + rot; return e >= K ? e - K : e; };
+  const int rot = same_lists ? ((c >> 3) & 15) % NT : 0;
+  auto ent = [&](int t) { const int e = t + rot; return e >= NT ? e - NT : e; };
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int qh = wave & 1, kh = wave >> 1, l32 = lane & 31, h = lane >> 5;
   const long long rows0 = bh * (long long)Nc * kTile;  // first row of this (b,h)
@@ -74,19 +76,19 @@ __global__ __launch_bounds__(256, 2) void k_fine_fwd(int Nc, int K, float sl2, c
   // The barrier is a raw s_barrier (no fence): a fence would drain the copy still in flight.
   // vmcnt is waited by hand (the compiler cannot see the copies; see Tile::async_load).
   unsigned goff[TL::IPW];
-  TL::lane_offsets(wave, lane, goff);
-  auto issue = [&](unsigned char* st, int j) {
-    TL::async_load(k, rows0 + (long long)j * kTile, st, wave, goff);
-    TL::async_load(v, rows0 + (long long)j * kTile, st + TL::BYTES, wave, goff);
+  LIST::template offsets<TL>(wave, lane, goff);
+  auto issue = [&](unsigned char* st, int row) {  // `row`: first source row of this wave's share
+    TL::async_load(k, rows0 + row, st, wave, goff);
+    TL::async_load(v, rows0 + row, st + TL::BYTES, wave, goff);
   };
   // Start-up order: the list first (one round trip), then the copy of tile 0, and only then the
   // loads of the key masks and of Q, so that everything the first iteration needs is in flight
   // together.  The empty asm below consumes the loaded registers: the compiler has to place its
   // wait for them right there (it also drains the copy), and its own vmcnt bookkeeping has nothing
   // left to wait for inside the loop.
-  CubeList cubes;
-  cubes.init(my_idx, mask, K, kh, lane, Nc);
-  issue(stage0, cubes.cube(ent(0)));
+  LIST cubes;
+  cubes.init(my_idx, mask, K, kh, wave, lane, Nc);
+  issue(stage0, cubes.first_row(ent(0)));
   cubes.load_masks();
   bf16x8 qreg[KS];
   {
@@ -100,7 +102,7 @@ __global__ __launch_bounds__(256, 2) void k_fine_fwd(int Nc, int K, float sl2, c
   uint32_t km_cur;  // valid-key mask (this wave's key half) of the tile of this iteration
   {
     int j0;
-    cubes.get(ent(0), j0, km_cur);
+    cubes.get_tile(ent(0), j0, km_cur);
   }
   const int lane_a = TL::rowmajor_lane(kh * 32, lane);
   int lane_b0, lane_b1;
@@ -125,9 +127,9 @@ __global__ __launch_bounds__(256, 2) void k_fine_fwd(int Nc, int K, float sl2, c
     // the same moment queue up behind one another in the load path and stall -- but one
     // instruction per S^T step below.
     int jn = 0;
-    if (COPY) cubes.get(ent(t + 1), jn, km_cur);
-    const void* gk = uniform_ptr(k + (rows0 + (long long)jn * kTile) * CPR);
-    const void* gv = uniform_ptr(v + (rows0 + (long long)jn * kTile) * CPR);
+    if (COPY) cubes.get_tile(ent(t + 1), jn, km_cur);
+    const void* gk = uniform_ptr(k + (rows0 + jn) * CPR);
+    const void* gv = uniform_ptr(v + (rows0 + jn) * CPR);
     const unsigned ln = __builtin_amdgcn_readfirstlane(lds_address(nxt) + (unsigned)(wave * TL::IPW) * 1024u);
     auto copy_piece = [&](int i) {
       if (!COPY) return;
@@ -228,11 +230,11 @@ __global__ __launch_bounds__(256, 2) void k_fine_fwd(int Nc, int K, float sl2, c
     const std::true_type copy;
     const std::false_type last;
     int t = 0;
-    for (; t + 2 < K; t += 2) {
+    for (; t + 2 < NT; t += 2) {
       body(copy, stage0, stage1, t);
       body(copy, stage1, stage0, t + 1);
     }
-    if (t + 1 < K) {
+    if (t + 1 < NT) {
       body(copy, stage0, stage1, t);
       body(last, stage1, stage0, t + 1);
     } else {
@@ -285,8 +287,11 @@ __global__ __launch_bounds__(256, 2) void k_fine_fwd(int Nc, int K, float sl2, c
     const float ma = ml[(wa * 32 + ql) * 2], la = ml[(wa * 32 + ql) * 2 + 1];
     const float mb = ml[(wb * 32 + ql) * 2], lb = ml[(wb * 32 + ql) * 2 + 1];
     const float M = fmaxf(ma, mb);
-    float fa = fast_exp2(ma - M), fb = fast_exp2(mb - M);
-    const float inv = 1.0f / (la * fa + lb * fb);
+    // (M = -inf: the list named no valid key at all -- only a caller-supplied list can, e.g. one made of
+    // dead key cubes; the row then gets O_f = 0 and lse = 0 instead of NaN)
+    const bool none = M == -INFINITY;
+    float fa = none ? 0.f : fast_exp2(ma - M), fb = none ? 0.f : fast_exp2(mb - M);
+    const float inv = none ? 0.f : 1.0f / (la * fa + lb * fb);
     fa *= inv; fb *= inv;
     const int m0 = merge_offset(r, ch * 8, OS), m1 = merge_offset(r, ch * 8 + 4, OS);
     const float* Oa = (const float*)stage0;
@@ -319,26 +324,30 @@ __global__ __launch_bounds__(256, 2) void k_fine_fwd(int Nc, int K, float sl2, c
     const float mb = ml[(wb * 32 + ql) * 2], lb = ml[(wb * 32 + ql) * 2 + 1];
     const float M = fmaxf(ma, mb);
     const float Lt = la * fast_exp2(ma - M) + lb * fast_exp2(mb - M);
-    lse_f[rows0 + c * kTile + r] = ((qmask >> r) & 1) ? (M + fast_log2(Lt)) * kLn2 : 0.f;
+    lse_f[rows0 + c * kTile + r] = (((qmask >> r) & 1) && M != -INFINITY) ? (M + fast_log2(Lt)) * kLn2 : 0.f;
   }
 }
 
 hipError_t launch_fine_fwd(int BH, int Nc, int d, int K, float scale, const void* q, const void* k, const void* v,
                            const void* gate_c, const void* gate_f, const int32_t* idx, const float* oc,
                            const uint64_t* mask, void* out, void* out_fine, float* lse_f, int H, int out_token_major,
-                           int m_blocks, hipStream_t s) {
+                           int m_blocks, int key_cubes_16, hipStream_t s) {
   const float sl2 = scale * kLog2e;
   const unsigned grid = (unsigned)(BH * Nc);
   const long long cpr = d / 8, Np = (long long)Nc * kTile;
   const long long ohs = out_token_major ? cpr : Np * cpr, ors = out_token_major ? H * cpr : cpr;
-  if (d == 128)
-    k_fine_fwd<128><<<grid, 256, 0, s>>>(Nc, K, sl2, (const uint4*)q, (const uint4*)k, (const uint4*)v,
-                                         (const uint4*)gate_c, (const uint4*)gate_f, idx, oc, mask, (uint4*)out,
-                                         (uint4*)out_fine, lse_f, H, ohs, ors, m_blocks);
-  else
-    k_fine_fwd<64><<<grid, 256, 0, s>>>(Nc, K, sl2, (const uint4*)q, (const uint4*)k, (const uint4*)v,
-                                        (const uint4*)gate_c, (const uint4*)gate_f, idx, oc, mask, (uint4*)out,
-                                        (uint4*)out_fine, lse_f, H, ohs, ors, m_blocks);
+#define VSA_FWD(D_, LIST_)                                                                                           \
+  k_fine_fwd<D_, LIST_><<<grid, 256, 0, s>>>(Nc, K, sl2, (const uint4*)q, (const uint4*)k, (const uint4*)v,           \
+                                             (const uint4*)gate_c, (const uint4*)gate_f, idx, oc, mask, (uint4*)out, \
+                                             (uint4*)out_fine, lse_f, H, ohs, ors, m_blocks)
+  if (key_cubes_16) {  // K counts key cubes of 16 tokens
+    if (d == 128) VSA_FWD(128, SubCubeList);
+    else VSA_FWD(64, SubCubeList);
+  } else {
+    if (d == 128) VSA_FWD(128, CubeList);
+    else VSA_FWD(64, CubeList);
+  }
+#undef VSA_FWD
   return hipGetLastError();
 }
 

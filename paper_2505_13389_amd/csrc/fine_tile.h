@@ -94,8 +94,8 @@ struct CubeList {
   // After init() the cube indices of the first chunk are there (cube() works); the key masks are
   // still in flight until the caller's next wait for its own loads, so that the first copies can
   // be issued one memory round trip earlier.
-  __device__ __forceinline__ void init(const int32_t* list_, const uint64_t* mask_, int n_, int half_, int lane_,
-                                       int ncubes_) {
+  __device__ __forceinline__ void init(const int32_t* list_, const uint64_t* mask_, int n_, int half_, int /*wave*/,
+                                       int lane_, int ncubes_) {
     list = list_, mask = mask_, n = n_, half = half_, lane = lane_, ncubes = ncubes_;
     load_indices(0);
   }
@@ -106,6 +106,67 @@ struct CubeList {
     cube = __builtin_amdgcn_readlane(idx_v, e & 63);
     km = (uint32_t)__builtin_amdgcn_readlane((int)km_v, e & 63);
   }
+  // The walk in tiles (one tile = one list entry here): number of tiles, whether the list names every
+  // cube, the first source row of this wave's share of tile t (valid after init for the first chunk),
+  // and row + key mask of tile t.
+  static constexpr int kEntriesPerTile = 1;
+  __device__ __forceinline__ int tiles() const { return n; }
+  __device__ __forceinline__ int first_row(int t) const { return cube(t) * kTile; }
+  __device__ __forceinline__ void get_tile(int t, int& row, uint32_t& km) {
+    int c;
+    get(t, c, km);
+    row = c * kTile;
+  }
+  template <class TL>
+  __device__ static __forceinline__ void offsets(int wave, int lane, unsigned* off) { TL::lane_offsets(wave, lane, off); }
+};
+
+// Lists that name key cubes of 16 tokens (see subcube_* in list_rules.h): a streamed 64-key tile is
+// gathered from four list entries, wavefront w copying the 16 rows of entry 4t + w into LDS rows
+// 16w .. 16w+15 (a wave's copy instructions cover exactly those rows).  The per-lane source offsets
+// are those of token order x inside a key cube, the key cube's first slot goes into the wave's base
+// pointer.  Entries past the end of the list repeat the last one with an empty key mask.
+struct SubCubeList {
+  const int32_t* list;
+  const uint64_t* mask;
+  int n, half, wave, lane, chunk, idx_v, ncubes;
+  uint32_t km_v;  // 16 validity bits of the lane's entry
+  __device__ __forceinline__ void load_indices(int c) {
+    chunk = c;
+    idx_v = list[list_slot(c, lane, n)];
+    asm volatile("" : "+v"(idx_v));
+    idx_v = clamp_cube(idx_v, 4 * ncubes);  // (a caller-supplied list is not trusted)
+  }
+  __device__ __forceinline__ void load_masks() { km_v = subcube_mask16(mask[idx_v >> 2], idx_v & 3); }
+  __device__ __forceinline__ void load_chunk(int c) {
+    load_indices(c);
+    load_masks();
+    asm volatile("" : "+v"(km_v));
+  }
+  __device__ __forceinline__ void init(const int32_t* list_, const uint64_t* mask_, int n_, int half_, int wave_,
+                                       int lane_, int ncubes_) {
+    list = list_, mask = mask_, n = n_, half = half_, lane = lane_, ncubes = ncubes_;
+    wave = __builtin_amdgcn_readfirstlane(wave_);
+    load_indices(0);
+  }
+  static constexpr int kEntriesPerTile = 4;
+  __device__ __forceinline__ int tiles() const { return (n + 3) >> 2; }
+  __device__ __forceinline__ int row_of_entry(int e) const {  // e in the current chunk
+    const int id = __builtin_amdgcn_readlane(idx_v, min(e, n - 1) & 63);
+    return (id >> 2) * kTile + subcube_first_slot(id & 3);
+  }
+  __device__ __forceinline__ int first_row(int t) const { return row_of_entry(4 * t + wave); }
+  __device__ __forceinline__ void get_tile(int t, int& row, uint32_t& km) {
+    const int e0 = 4 * t;
+    if ((e0 >> 6) != chunk) load_chunk(e0 >> 6);
+    row = row_of_entry(e0 + wave);
+    const int ea = e0 + 2 * half, eb = ea + 1;
+    const uint32_t ma = (uint32_t)__builtin_amdgcn_readlane((int)km_v, ea & 63);
+    const uint32_t mb = (uint32_t)__builtin_amdgcn_readlane((int)km_v, eb & 63);
+    km = (ea < n ? ma : 0u) | ((eb < n ? mb : 0u) << 16);
+  }
+  template <class TL>
+  __device__ static __forceinline__ void offsets(int wave, int lane, unsigned* off) { TL::lane_offsets_sub(wave, lane, off); }
 };
 
 template <int D>
@@ -162,6 +223,17 @@ struct Tile {
     for (int i = 0; i < N; ++i) {
       const int r = (part * N + i) * RPI + lane / CPR, pc = lane % CPR;
       off[i] = (unsigned)((r * CPR + (pc ^ swz(r))) * 16) - (unsigned)i * 1024u;
+    }
+  }
+  // The same for a tile gathered from four key cubes of 16 tokens (SubCubeList), four wavefronts
+  // copying: the base pointer of wave `part` is the first slot of its key cube, LDS row 16*part + x
+  // takes token x of that key cube, and the swizzle follows the LDS row.
+  __device__ static __forceinline__ void lane_offsets_sub(int part, int lane, unsigned* off) {
+    constexpr int N = kTile / RPI / 4;
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+      const int x = i * RPI + lane / CPR, r = part * 16 + x, pc = lane % CPR;
+      off[i] = (unsigned)((subcube_slot(x) * CPR + (pc ^ swz(r))) * 16) - (unsigned)i * 1024u;
     }
   }
   // copy i (compile-time) of this wave's share; M0 must hold the LDS address of the share

@@ -39,6 +39,23 @@ VSA_RULE int tile_of_cube(int c, int Nh, int Nw) {
   return (ct * (Nh / 2) + ch / 2) * (Nw / 2) + cw / 2;
 }
 
+// Key cubes of 16 tokens (Sec. 3.2, the 64 x 16 row of the tile-size tables): the (2,4,2) boxes inside a
+// (4,4,4) cube.  Key cube 4*c + s, s = 2a + b, holds the in-cube slots (2a + tt)*16 + hh*4 + 2b + ww of
+// cube c (tt, ww in {0,1}, hh in 0..3); its token x = tt*8 + hh*2 + ww sits at slot
+// subcube_first_slot(s) + subcube_slot(x).
+VSA_RULE int subcube_first_slot(int s) { return (s >> 1) * 32 + (s & 1) * 2; }
+VSA_RULE int subcube_slot(int x) { return (x >> 3) * 16 + ((x >> 1) & 3) * 4 + (x & 1); }
+// the in-cube slots of key cube s as a 64-bit pattern, and the 16 validity bits of its tokens (bit x =
+// token x) out of the cube's 64-bit mask
+VSA_RULE uint64_t subcube_pattern(int s) { return 0x33333333ull << (subcube_first_slot(s)); }
+VSA_RULE uint32_t subcube_mask16(uint64_t cube_mask, int s) {
+  uint32_t y = (uint32_t)(cube_mask >> subcube_first_slot(s)) & 0x33333333u;
+  y = (y | (y >> 2)) & 0x0F0F0F0Fu;
+  y = (y | (y >> 4)) & 0x00FF00FFu;
+  y = (y | (y >> 8)) & 0x0000FFFFu;
+  return y;
+}
+
 // Slot of the list read by lane `lane` for 64-entry chunk `chunk` of a list of n entries.
 VSA_RULE int list_slot(int chunk, int lane, int n) {
   const int e = (chunk << 6) + lane;

@@ -1,5 +1,6 @@
 // Token permutation (raster <-> cube-contiguous), cube validity masks and mean pooling.
 // All three are pure data movement / fp32 adds: HBM-bandwidth bound, 16-byte accesses.
+#include "list_rules.h"
 #include "vsa_kernels.h"
 
 namespace vsa {
@@ -128,9 +129,69 @@ __global__ __launch_bounds__(256) void k_pool(Geo g, long long Np, uint64_t* __r
   }
 }
 
+// Key cubes of 16 tokens (Sec. 3.2, the 64 x 16 row of the tile-size tables): K and V are pooled over the
+// four (2,4,2) boxes of every (4,4,4) cube, rows 4c .. 4c+3 of kc, vc.  One workgroup per (tensor, b*h,
+// cube).  Thread (row group rg, chunk ch) adds rows rg, rg + RG, ...: of those, row r belongs to key
+// cube 2a + b with a = r / 32 and b = (r / 2) % 2 = (rg / 2) % 2, so a thread keeps one partial sum per
+// a, and key cube (a, b) is the sum over the row groups with that b, in ascending order.  A key cube
+// without a valid token (a padded grid has them) gets zero rows and kcnt = 0: it is dead, left out of
+// the coarse softmax and never selected.
+template <int D>
+__global__ __launch_bounds__(256) void k_pool_keys16(int Nc, int32_t* __restrict__ kcnt, const uint64_t* __restrict__ mask,
+                                                     const uint4* __restrict__ k, const uint4* __restrict__ v,
+                                                     float* __restrict__ kc, float* __restrict__ vc) {
+  constexpr int CPR = D / 8, RG = 256 / CPR, RPT = kTile / RG;
+  static_assert(RG % 4 == 0 && 32 % RG == 0, "a thread's rows share b, and a changes between its rows only");
+  __shared__ float part[2][RG][D + 4];
+  const int c = blockIdx.x % Nc;
+  const long long bh = blockIdx.x / Nc;
+  const uint4* src = blockIdx.y == 0 ? k : v;
+  float* dst = blockIdx.y == 0 ? kc : vc;
+  const int ch = threadIdx.x % CPR, rg = threadIdx.x / CPR;
+  const uint64_t m = mask[c];
+  float acc[2][8] = {{0, 0, 0, 0, 0, 0, 0, 0}, {0, 0, 0, 0, 0, 0, 0, 0}};
+  const uint4* base = src + (bh * Nc + c) * (long long)kTile * CPR;
+#pragma unroll
+  for (int i = 0; i < RPT; ++i) {
+    const int r = rg + i * RG;
+    const uint4 u = base[r * CPR + ch];
+    if ((m >> r) & 1) {
+      float f[8];
+      unpack8(u, f);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[(i * RG) >> 5][e] += f[e];  // = r / 32: rg < RG, and RG divides 32
+    }
+  }
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) part[a][rg][ch * 8 + e] = acc[a][e];
+  __syncthreads();
+  for (int o = threadIdx.x; o < 4 * D; o += 256) {
+    const int sc = o / D, e = o % D, a = sc >> 1, b = sc & 1;
+    const int cnt = __popcll(m & subcube_pattern(sc));
+    float sum = 0;
+    for (int r = 0; r < RG; ++r)
+      if (((r >> 1) & 1) == b) sum += part[a][r][e];
+    dst[((bh * Nc + c) * 4 + sc) * D + e] = cnt ? sum / (float)cnt : 0.f;
+    if (e == 0 && bh == 0 && blockIdx.y == 0) kcnt[c * 4 + sc] = cnt;
+  }
+}
+
+hipError_t launch_pool_keys16(int BH, int Nc, int d, const uint64_t* mask, int32_t* kcnt, const void* k, const void* v,
+                              float* kc, float* vc, hipStream_t s) {
+  dim3 grid((unsigned)(BH * Nc), 2);
+  if (d == 128)
+    k_pool_keys16<128><<<grid, 256, 0, s>>>(Nc, kcnt, mask, (const uint4*)k, (const uint4*)v, kc, vc);
+  else
+    k_pool_keys16<64><<<grid, 256, 0, s>>>(Nc, kcnt, mask, (const uint4*)k, (const uint4*)v, kc, vc);
+  return hipGetLastError();
+}
+
+// tensors = 3: Q, K and V pooled per cube; tensors = 1: Q only (K and V are pooled by launch_pool_keys16)
 hipError_t launch_pool(const Geo& g, int BH, int d, uint64_t* mask, const void* q, const void* k, const void* v,
-                       float* qc, float* kc, float* vc, hipStream_t s) {
-  dim3 grid((unsigned)(BH * g.Nc), 3);
+                       float* qc, float* kc, float* vc, int tensors, hipStream_t s) {
+  dim3 grid((unsigned)(BH * g.Nc), (unsigned)tensors);
   if (d == 128)
     k_pool<128><<<grid, 256, 0, s>>>(g, g.Np, mask, (const uint4*)q, (const uint4*)k, (const uint4*)v, qc, kc, vc);
   else

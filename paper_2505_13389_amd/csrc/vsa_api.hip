@@ -63,8 +63,18 @@ bool pooled_select(const vsa_params_t* p) { return (p->flags & VSA_FLAG_SELECT_P
 int list_rows(const vsa_params_t* p, const Geo& g) { return pooled_select(p) ? g.Nc / 4 : g.Nc; }  // rows of block_idx per (b,h)
 int blocks_per_entry(const vsa_params_t* p, const Geo& g) { return pooled_select(p) ? 4 : g.m; }    // 64-row blocks a list entry stands for
 
+// Key cubes of 16 tokens (VSA_FLAG_KEY_CUBES_16): four per cube, the lists name them.
+bool key16(const vsa_params_t* p) { return (p->flags & VSA_FLAG_KEY_CUBES_16) != 0; }
+int key_rows(const vsa_params_t* p, const Geo& g) { return key16(p) ? 4 * g.Nc : g.Nc;  }  // key cubes of the coarse stage
+
 int check_topk(const vsa_params_t* p, const Geo& g) {
   if (pooled_select(p) && (g.m != 1 || g.Nh % 2 || g.Nw % 2)) return VSA_ERR_UNSUPPORTED;
+  if (key16(p)) {
+    if (pooled_select(p) || p->Ct != 4 || p->Ch != 4 || p->Cw != 4 || 4 * g.Nc > VSA_MAX_CUBES) return VSA_ERR_UNSUPPORTED;
+    // a (2,4,2) box of the padded grid is live iff its first token lies inside the valid grid
+    const long long live = (long long)((p->T + 1) / 2) * ((p->Hh + 3) / 4) * ((p->W + 1) / 2);
+    return (p->topk < 1 || p->topk > live) ? VSA_ERR_BAD_ARG : VSA_OK;
+  }
   return (p->topk < 1 || p->topk > list_rows(p, g)) ? VSA_ERR_BAD_ARG : VSA_OK;
 }
 
@@ -87,6 +97,7 @@ struct Carver {
 
 struct FwdWs {
   uint64_t* mask;
+  int32_t* kcnt;
   float *qc, *kc, *vc, *oc, *lse_c, *sc, *ps;
   int32_t *idx, *idx_blocks;
   size_t bytes;
@@ -95,15 +106,17 @@ FwdWs carve_fwd(const vsa_params_t* p, const Geo& g, void* ws) {
   Carver c(ws);
   size_t bh = (size_t)p->B * p->H;
   FwdWs w;
+  const size_t nk = (size_t)key_rows(p, g);
   w.mask = c.take<uint64_t>(g.Nb);
+  w.kcnt = key16(p) ? c.take<int32_t>(nk) : nullptr;
   w.qc = c.take<float>(bh * g.Nc * p->d);
-  w.kc = c.take<float>(bh * g.Nc * p->d);
-  w.vc = c.take<float>(bh * g.Nc * p->d);
+  w.kc = c.take<float>(bh * nk * p->d);
+  w.vc = c.take<float>(bh * nk * p->d);
   w.oc = c.take<float>(bh * g.Nc * p->d);
   w.lse_c = c.take<float>(bh * g.Nc);
   const size_t bpe = (size_t)blocks_per_entry(p, g), rows = (size_t)list_rows(p, g);
   w.idx = c.take<int32_t>(bh * rows * p->topk);
-  w.sc = c.take<float>(bh * g.Nc * g.Nc);
+  w.sc = c.take<float>(bh * g.Nc * nk);
   w.idx_blocks = bpe > 1 ? c.take<int32_t>(bh * g.Nb * p->topk * bpe) : nullptr;
   w.ps = pooled_select(p) ? c.take<float>(bh * rows * rows) : nullptr;
   w.bytes = c.used;
@@ -112,6 +125,7 @@ FwdWs carve_fwd(const vsa_params_t* p, const Geo& g, void* ws) {
 
 struct BwdWs {
   uint64_t* mask;
+  int32_t* kcnt;
   float *qc, *kc, *vc, *ld, *doc, *ac, *dsc, *dqc, *dkc, *dvc;
   void *dof, *ldb;
   int32_t *row_ptr, *col, *order, *split, *idx_blocks;
@@ -140,22 +154,24 @@ BwdWs carve_bwd(const vsa_params_t* p, const Geo& g, void* ws) {
   size_t bh = (size_t)p->B * p->H;
   BwdWs w;
   const size_t kb = (size_t)p->topk * blocks_per_entry(p, g);
+  const size_t nk = (size_t)key_rows(p, g);
   w.mask = c.take<uint64_t>(g.Nb);
+  w.kcnt = key16(p) ? c.take<int32_t>(nk) : nullptr;
   w.qc = c.take<float>(bh * g.Nc * p->d);
-  w.kc = c.take<float>(bh * g.Nc * p->d);
-  w.vc = c.take<float>(bh * g.Nc * p->d);
+  w.kc = c.take<float>(bh * nk * p->d);
+  w.vc = c.take<float>(bh * nk * p->d);
   w.ld = c.take<float>(2 * bh * g.Np);
   w.ldb = c.take<uint32_t>(4 * bh * g.Np);
   w.doc = c.take<float>(bh * g.Nc * p->d);
-  w.ac = c.take<float>(bh * g.Nc * g.Nc);
-  w.dsc = c.take<float>(bh * g.Nc * g.Nc);
+  w.ac = c.take<float>(bh * g.Nc * nk);
+  w.dsc = c.take<float>(bh * g.Nc * nk);
   w.dqc = c.take<float>(bh * g.Nc * p->d);
-  w.dkc = c.take<float>(bh * g.Nc * p->d);
-  w.dvc = c.take<float>(bh * g.Nc * p->d);
+  w.dkc = c.take<float>(bh * nk * p->d);
+  w.dvc = c.take<float>(bh * nk * p->d);
   w.dof = c.take<uint16_t>(bh * g.Np * p->d);
   w.row_ptr = c.take<int32_t>(bh * (g.Nb + 1));
   w.col = c.take<int32_t>(bh * g.Nb * kb);
-  w.bits = c.take<uint32_t>(bh * g.Nb * ((g.Nb + 31) / 32));
+  w.bits = c.take<uint32_t>(bh * (key16(p) ? 4 : 1) * g.Nb * ((g.Nb + 31) / 32));
   w.idx_blocks = blocks_per_entry(p, g) > 1 ? c.take<int32_t>(bh * g.Nb * kb) : nullptr;
   split_plan(p, g, &w.seg, &w.cap);
   w.order = c.take<int32_t>(4 * bh * (g.Nb + w.cap));  // (block, run begin, run end, slot) per dK/dV workgroup
@@ -223,10 +239,12 @@ int enqueue_forward(const vsa_params_t* p, const Geo& g, const void* q, const vo
   float* lse_c = lse_coarse ? lse_coarse : w.lse_c;
   int32_t* idx = block_idx ? block_idx : w.idx;
 
-  VSA_TRY("pool", vsa::launch_pool(g, BH, p->d, w.mask, q, k, v, w.qc, w.kc, w.vc, s));
+  const bool sub = key16(p);
+  VSA_TRY("pool", vsa::launch_pool(g, BH, p->d, w.mask, q, k, v, w.qc, w.kc, w.vc, sub ? 1 : 3, s));
+  if (sub) VSA_TRY("pool", vsa::launch_pool_keys16(BH, g.Nc, p->d, w.mask, w.kcnt, k, v, w.kc, w.vc, s));
   const bool pooled = pooled_select(p);
-  VSA_TRY("coarse", vsa::launch_coarse(BH, g.Nc, p->d, p->topk, scale, w.qc, w.kc, w.vc, w.sc, oc, lse_c, idx, (given || pooled) ? 0 : 1,
-                            pooled ? 0 : coarse_form(p, g), s));
+  VSA_TRY("coarse", vsa::launch_coarse(BH, g.Nc, key_rows(p, g), p->d, p->topk, scale, w.qc, w.kc, w.vc, w.sc, oc, lse_c, idx,
+                            (given || pooled) ? 0 : 1, (pooled || sub) ? 0 : coarse_form(p, g), w.kcnt, s));
   // the fine stage works on 64-row blocks: a cube of m blocks contributes m list entries, a tile of
   // (1,2,2) cubes its four cubes
   const int32_t* lists = idx;
@@ -239,7 +257,7 @@ int enqueue_forward(const vsa_params_t* p, const Geo& g, const void* q, const vo
     lists = w.idx_blocks;
   }
   VSA_TRY("fine_fwd", vsa::launch_fine_fwd(BH, g.Nb, p->d, p->topk * blocks_per_entry(p, g), scale, q, k, v, gate_c, gate_f, lists, oc, w.mask, out,
-                               out_fine, lse_fine, p->H, (p->flags & VSA_FLAG_OUT_TOKEN_MAJOR) ? 1 : 0, g.m, s));
+                               out_fine, lse_fine, p->H, (p->flags & VSA_FLAG_OUT_TOKEN_MAJOR) ? 1 : 0, g.m, sub ? 1 : 0, s));
   return VSA_OK;
 }
 
@@ -345,13 +363,15 @@ int vsa_backward(const vsa_params_t* p, const void* q, const void* k, const void
   const float scale = scale_of(p);
 
   // forward and backward carve the cube masks and the pooled tensors at the same offsets
+  const bool sub = key16(p);
   if (!(p->flags & VSA_FLAG_WORKSPACE_KEPT)) {
-    VSA_TRY("pool", vsa::launch_pool(g, BH, p->d, w.mask, q, k, v, w.qc, w.kc, w.vc, s));
+    VSA_TRY("pool", vsa::launch_pool(g, BH, p->d, w.mask, q, k, v, w.qc, w.kc, w.vc, sub ? 1 : 3, s));
+    if (sub) VSA_TRY("pool", vsa::launch_pool_keys16(BH, g.Nc, p->d, w.mask, w.kcnt, k, v, w.kc, w.vc, s));
   }
   VSA_TRY("bwd_pre", vsa::launch_bwd_pre(BH, g.Nc, g.m, p->d, w.mask, dout, gate_c, gate_f, out_fine, out_coarse, dgate_c, dgate_f,
                               w.dof, w.ld, w.ldb, scale, w.doc, lse_fine, p->H, (p->flags & VSA_FLAG_OUT_TOKEN_MAJOR) ? 1 : 0, s));
-  VSA_TRY("coarse_bwd", vsa::launch_coarse_bwd(BH, g.Nc, p->d, scale, w.qc, w.kc, w.vc, lse_coarse, w.doc, w.ac, w.dsc, w.dqc, w.dkc,
-                                 w.dvc, s));
+  VSA_TRY("coarse_bwd", vsa::launch_coarse_bwd(BH, g.Nc, key_rows(p, g), p->d, scale, w.qc, w.kc, w.vc, lse_coarse, w.doc, w.ac, w.dsc,
+                                 w.dqc, w.dkc, w.dvc, w.kcnt, s));
   const int32_t* lists = block_idx;
   const int kb = p->topk * blocks_per_entry(p, g);
   if (pooled_select(p)) {
@@ -361,11 +381,11 @@ int vsa_backward(const vsa_params_t* p, const void* q, const void* k, const void
     VSA_TRY("expand_lists", vsa::launch_expand_lists(BH, g.Nc, p->topk, g.m, block_idx, w.idx_blocks, s));
     lists = w.idx_blocks;
   }
-  VSA_TRY("transpose_map", vsa::launch_transpose_map(BH, g.Nb, kb, lists, w.bits, w.row_ptr, w.col, w.order, w.split, w.seg, w.cap, s));
+  VSA_TRY("transpose_map", vsa::launch_transpose_map(BH, g.Nb, kb, lists, w.bits, w.row_ptr, w.col, w.order, w.split, w.seg, w.cap, sub ? 1 : 0, s));
   VSA_TRY("fine_bwd_dq", vsa::launch_fine_bwd_dq(BH, g.Nb, p->d, kb, scale, q, k, v, w.dof, lists, w.ld,
-                                  w.dqc, w.mask, dq, g.m, s));
+                                  w.dqc, w.mask, dq, g.m, sub ? 1 : 0, s));
   VSA_TRY("fine_bwd_dkv", vsa::launch_fine_bwd_dkv(BH, g.Nb, p->d, kb, scale, q, k, v, w.dof, w.col, w.order, w.split, w.parts,
-                                   w.cap, w.ldb, w.dkc, w.dvc, w.mask, dk, dv, g.m, s));
+                                   w.cap, w.ldb, w.dkc, w.dvc, w.mask, dk, dv, g.m, sub ? 1 : 0, s));
   return VSA_OK;
 }
 
@@ -392,23 +412,28 @@ int vsa_host_replay_lists(const vsa_params_t* p, const int32_t* host_block_idx, 
                                         e % 4, g.Nt, g.Nh, g.Nw)
                 : vsa::expanded_entry(host_block_idx[(bh * g.Nc + row / g.m) * p->topk + e / g.m], g.m, e % g.m);
     const int32_t* lists = expanded.data();
+    // key cubes of 16 tokens: an entry names key cube 4*block + s, clamped or skipped against 4*Nc; the
+    // fetch starts at the key cube's first slot and reaches at most subcube_slot(15) rows further
+    const int per = key16(p) ? 4 : 1;
     // forward and dQ pass: every lane of every 64-entry chunk reads a list slot, then fetches a cube
     for (int c = 0; c < Nc; ++c)
       for (int chunk = 0; chunk * 64 < K; ++chunk)
         for (int lane = 0; lane < 64; ++lane) {
           const int slot = vsa::list_slot(chunk, lane, K);
           if (slot < 0 || slot >= K) { ++bad; continue; }
-          const int cube = vsa::clamp_cube(lists[(size_t)c * K + slot], Nc);
-          if (cube < 0 || cube >= Nc) ++bad;
+          const int id = vsa::clamp_cube(lists[(size_t)c * K + slot], per * Nc);
+          const int cube = id / per;
+          if (id < 0 || cube >= Nc) ++bad;
+          if (per == 4 && vsa::subcube_first_slot(id & 3) + vsa::subcube_slot(15) > 63) ++bad;
         }
     // transposed map: one bit per (query cube, key cube) pair that names a cube
     std::fill(bit.begin(), bit.end(), 0);
     for (int c = 0; c < Nc; ++c)
       for (int e = 0; e < K; ++e) {
         const int raw = lists[(size_t)c * K + e];
-        if (vsa::map_takes(raw, Nc)) {
-          if (raw < 0 || raw >= Nc) { ++bad; continue; }
-          bit[(size_t)raw * Nc + c] = 1;
+        if (vsa::map_takes(raw, per * Nc)) {
+          if (raw < 0 || raw / per >= Nc) { ++bad; continue; }
+          bit[(size_t)(raw / per) * Nc + c] = 1;  // (the dK/dV pass works on the union over a block's key cubes)
         }
       }
     long long total = 0;

@@ -20,6 +20,7 @@ VSA_FLAG_COARSE_FUSED = 8
 VSA_FLAG_COARSE_UNFUSED = 64
 VSA_FLAG_OUT_TOKEN_MAJOR = 16
 VSA_FLAG_SELECT_POOLED_2X2 = 32
+VSA_FLAG_KEY_CUBES_16 = 128
 STATUS = {0: "VSA_OK", -1: "VSA_ERR_NULL", -2: "VSA_ERR_BAD_ARG", -3: "VSA_ERR_UNSUPPORTED", -4: "VSA_ERR_ALIGN",
           -5: "VSA_ERR_WORKSPACE", -6: "VSA_ERR_HIP", -7: "VSA_ERR_SCRATCH_LIMIT"}
 EXPORTS = ["vsa_padded_tokens", "vsa_workspace_bytes", "vsa_tile_permute", "vsa_forward", "vsa_backward",

@@ -86,6 +86,38 @@ def test_list_index_rules_with_tile_lists(lib):
         assert rep["longest_list"] <= Nc and rep["col_entries"] <= Nc * 20
 
 
+def test_key_cubes_16_parameter_checks(lib):
+    """Key cubes of 16 tokens: topk counts LIVE key cubes; needs (4,4,4) cubes, no pooled selection, <= 4096 key cubes."""
+    import dataclasses
+    flag = vsa.VSA_FLAG_KEY_CUBES_16
+    ok = dataclasses.replace(vsa.Problem(1, 1, 7, 14, 30, 64, 4 * 4 * 15), flags=flag)   # every live key cube of 256
+    assert vsa.vsa_workspace_bytes(ok, True) > vsa.vsa_workspace_bytes(ok, False) > 0
+    assert vsa.vsa_workspace_bytes(dataclasses.replace(ok, topk=4 * 4 * 15 + 1), False) == 0  # ... and a dead one
+    big_cube = dataclasses.replace(vsa.Problem(1, 1, 8, 16, 32, 64, 2, cube=(4, 4, 8)), flags=flag)
+    assert vsa.vsa_workspace_bytes(big_cube, False) == 0
+    both = dataclasses.replace(vsa.Problem(1, 1, 8, 16, 32, 64, 2), flags=flag | vsa.VSA_FLAG_SELECT_POOLED_2X2)
+    assert vsa.vsa_workspace_bytes(both, False) == 0
+    assert vsa.vsa_workspace_bytes(dataclasses.replace(vsa.Problem(1, 1, 32, 32, 64, 64, 8), flags=flag), False) > 0  # 4096 key cubes
+    assert vsa.vsa_workspace_bytes(dataclasses.replace(vsa.Problem(1, 1, 24, 48, 64, 64, 8), flags=flag), False) == 0  # 4608
+
+
+def test_list_index_rules_with_key_cube_lists(lib):
+    """Lists of key cubes of 16 tokens: hostile entries are clamped (fetches) or skipped (transposed map) against 4*Nc."""
+    import dataclasses
+    import numpy as np
+    pb = dataclasses.replace(vsa.Problem(2, 2, 7, 14, 30, 64, 21), flags=vsa.VSA_FLAG_KEY_CUBES_16)
+    _, Nc = vsa.vsa_padded_tokens(pb)
+    rng = np.random.Generator(np.random.PCG64(5))
+    hostile = rng.integers(-9, 4 * Nc + 9, size=(2, 2, Nc, 21), dtype=np.int64).astype(np.int32)
+    hostile[0, 0, 0, :] = np.iinfo(np.int32).max
+    hostile[1, 1, 1, :] = np.iinfo(np.int32).min
+    same = np.broadcast_to(np.arange(21, dtype=np.int32) * 3, (2, 2, Nc, 21))
+    for lists in (hostile, same):
+        rc, rep = vsa.vsa_host_replay_lists(pb, lists)
+        assert rc == 0 and rep["violations"] == 0, rep
+        assert rep["longest_list"] <= Nc and rep["col_entries"] <= Nc * 21
+
+
 def test_status_strings(lib):
     seen = set()
     for s in range(0, -8, -1):
