@@ -107,3 +107,81 @@ def test_hostile_key_cube_lists_stay_inside_the_buffers(vsa):
         t = bf16_to_np(getattr(buf, n))
         assert np.isfinite(t).all(), n
         assert not t[:, :, ~valid].any(), f"{n}: pad rows must be zero"
+
+
+def _head(dev, b, h):
+    return {n: (None if t is None else bf16_to_np(t[b:b + 1, h:h + 1].contiguous())) for n, t in dev.items()}
+
+
+def test_key_cubes_16_at_the_pretraining_shape_one_head_forward_backward(vsa):
+    """16x32x32 latent, 12 heads, d=128, 128 of 1024 key cubes (87.5 % sparse): the 12-head launch, one
+    head against the oracle -- selection, forward values where the selections agree, and the backward
+    of that head re-run on the oracle's lists."""
+    import torch
+    from paper_2505_13389_amd import synth
+    wl = Workload("mid_key16", 1, 12, 16, 32, 32, 128, 128)
+    dev = synth.device_iid_inputs(wl, seed=4, tiled_rows=wl.Np)
+    pb = dataclasses.replace(problem_of(wl), flags=vsa.VSA_FLAG_KEY_CUBES_16)
+    buf = vsa.Buffers(pb, backward=True)
+    a = (dev["q"], dev["k"], dev["v"], dev["gate_c"], dev["gate_f"])
+    buf.forward(*a)
+    buf.backward(*a, dev["dout"], workspace_kept=True)
+    torch.cuda.synchronize()
+    h = 7
+    one = Workload("slice", 1, 1, wl.T, wl.Hh, wl.W, wl.d, wl.topk)
+    g = grid_of(one)
+    x = _head(dev, 0, h)
+    ref = orc.forward_kq(g, KCUBE, x["q"], x["k"], x["v"], x["gate_c"], x["gate_f"], wl.topk, real="f32", want_sc=True)
+    gi = buf.block_idx[:, h:h + 1].cpu().numpy()
+    differ = check_index_sets(gi, ref["block_idx"], ref["sc"])
+    assert len(differ) <= 12
+    same = np.repeat((gi[0, 0] == ref["block_idx"][0, 0]).all(-1), 64)
+    assert same.mean() > 0.9
+    assert_close(bf16_to_np(buf.out[:, h:h + 1])[0, 0, same], ref["out"][0, 0, same], "out")
+    assert np.abs(buf.lse_fine[:, h:h + 1].cpu().numpy()[0, 0, same] - ref["lse_fine"][0, 0, same]).max() < 2e-3
+    gref = orc.backward_kq(g, KCUBE, x["q"], x["k"], x["v"], x["gate_c"], x["gate_f"], x["dout"], ref["block_idx"],
+                           wl.topk, real="f32")
+    for n in ("dq", "dgate_c", "dgate_f"):  # row-local: the 12-head launch itself, where the selections agree
+        assert_close(bf16_to_np(getattr(buf, n)[:, h:h + 1])[0, 0, same], gref[n][0, 0, same], n + " (12-head launch)")
+    b1 = vsa.Buffers(dataclasses.replace(problem_of(one), flags=vsa.VSA_FLAG_KEY_CUBES_16), backward=True)
+    d1 = {n: (None if t is None else t[:, h:h + 1].contiguous()) for n, t in dev.items()}
+    b1.block_idx.copy_(torch.from_numpy(ref["block_idx"]))
+    a1 = (d1["q"], d1["k"], d1["v"], d1["gate_c"], d1["gate_f"])
+    b1.forward(*a1, indices_given=True)
+    b1.backward(*a1, d1["dout"])
+    torch.cuda.synchronize()
+    for n in ("dq", "dk", "dv", "dgate_c", "dgate_f"):
+        assert_close(bf16_to_np(getattr(b1, n)), gref[n], n)
+
+
+def test_key_cubes_16_at_the_wan13b_shape_sampled_cubes(vsa):
+    """21x30x52 latent (dead and partial key cubes, 2496 key cubes per head, lists of 312): the 12-head
+    forward, sampled query cubes of one head against the oracle."""
+    import torch
+    from paper_2505_13389_amd import synth
+    wl = Workload("wan13b_key16", 1, 12, 21, 30, 52, 128, 312)
+    dev = synth.device_iid_inputs(wl, seed=5, tiled_rows=wl.Np)
+    pb = dataclasses.replace(problem_of(wl), flags=vsa.VSA_FLAG_KEY_CUBES_16)
+    buf = vsa.Buffers(pb, backward=False)
+    buf.forward(dev["q"], dev["k"], dev["v"], dev["gate_c"], dev["gate_f"])
+    torch.cuda.synchronize()
+    h = 3
+    g = grid_of(Workload("slice", 1, 1, wl.T, wl.Hh, wl.W, wl.d, wl.topk))
+    cubes = np.array([0, 1, 77, 300, 519, 520, 611, 623], dtype=np.int32)  # the last ones lie in the padded t, h slabs
+    x = _head(dev, 0, h)
+    ref = orc.forward_kq(g, KCUBE, x["q"], x["k"], x["v"], x["gate_c"], x["gate_f"], wl.topk, real="f32", want_sc=True,
+                         cubes=cubes)
+    gi = buf.block_idx[:, h:h + 1].cpu().numpy()
+    _, kcnt = orc.keycubes(g, KCUBE)
+    assert (kcnt[gi] > 0).all(), "a dead key cube was selected"
+    sc = np.where(np.isfinite(ref["sc"]), ref["sc"], -1e30)
+    differ = check_index_sets(gi[:, :, cubes], ref["block_idx"][:, :, cubes], sc[:, :, cubes])
+    assert len(differ) <= 2
+    assert_close(buf.out_coarse[:, h:h + 1].cpu().numpy()[:, :, cubes], ref["out_coarse"][:, :, cubes], "out_coarse", 1e-4, 1e-4)
+    same_c = np.zeros(g.Nc, bool)
+    same_c[cubes] = (gi[0, 0, cubes] == ref["block_idx"][0, 0, cubes]).all(-1)
+    same = np.repeat(same_c, 64)
+    assert same_c[cubes].sum() >= len(cubes) - 2
+    assert_close(bf16_to_np(buf.out[:, h:h + 1])[0, 0, same], ref["out"][0, 0, same], "out")
+    valid, _ = orc.valid_mask(g)
+    assert not bf16_to_np(buf.out)[:, :, ~valid].any()
