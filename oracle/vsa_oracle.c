@@ -34,8 +34,9 @@
  *     cubes below).  A key cube with no valid token is dead: never in the softmax, never selected.
  *
  * Parity pins: see tests/test_oracle_*.py.  Unpinned by anything outside this file: the
- * two pad conventions above that are ours by fiat (equal weighting of partial cubes in
- * the coarse softmax; zero rows for pad queries) -- "parity unpinned" for those two.
+ * pad conventions above that are ours by fiat (equal weighting of partial cubes in the
+ * coarse softmax; zero rows for pad queries; and, with key cubes of 16 tokens, leaving a
+ * dead key cube out of the coarse softmax) -- "parity unpinned" for those three.
  *
  * Layout: every tensor is [B,H,Np,d] in TILED order (each cube = Bk consecutive rows),
  * Np = padded token count, row-major, contiguous.  Pooled tensors are [B,H,Nc,d].
