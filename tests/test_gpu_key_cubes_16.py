@@ -24,6 +24,28 @@ CASES = {
 }
 
 
+def random_cases(n, seed=20250515, tag="rnd16"):
+    """Seeded random grids (2..5 cubes per axis, each possibly ragged), head dims, head counts and list
+    lengths from 1 to all live key cubes."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    out = {}
+    while len(out) < n:
+        dims = [int(4 * rng.integers(2, 6) - rng.integers(0, 4)) for _ in range(3)]
+        nc = np.prod([(x + 3) // 4 for x in dims])
+        if nc > 60:
+            continue
+        live = ((dims[0] + 1) // 2) * ((dims[1] + 3) // 4) * ((dims[2] + 1) // 2)
+        topk = int(rng.integers(1, live + 1)) if rng.random() < 0.8 else live
+        B, H = (1, 2) if rng.random() < 0.7 else (2, 1)
+        name = f"{tag}{len(out)}-{dims[0]}x{dims[1]}x{dims[2]}-k{topk}"
+        out[name] = Workload(name, B, H, dims[0], dims[1], dims[2], int(rng.choice([64, 128])), topk,
+                             planted=bool(rng.random() < 0.3))
+    return out
+
+
+CASES.update(random_cases(8))
+
+
 @pytest.fixture(scope="module")
 def vsa():
     import torch
@@ -37,7 +59,8 @@ def vsa():
 def test_key_cubes_16_forward_backward(vsa, name):
     import torch
     wl = CASES[name]
-    bits = tiled_bits(wl, seed=33, pad_garbage=True)
+    with_gate_f = not (name.startswith("rnd16") and wl.topk % 2)   # some of the random cases run without a fine gate
+    bits = tiled_bits(wl, seed=33, with_gate_f=with_gate_f, pad_garbage=True)
     x = widen(bits)
     g = grid_of(wl)
     fwd = orc.forward_kq(g, KCUBE, x["q"], x["k"], x["v"], x["gate_c"], x["gate_f"], wl.topk, real="f32", want_sc=True)
@@ -46,7 +69,7 @@ def test_key_cubes_16_forward_backward(vsa, name):
 
     dev = to_dev(bits)
     pb = dataclasses.replace(problem_of(wl), flags=vsa.VSA_FLAG_KEY_CUBES_16)
-    buf = vsa.Buffers(pb, backward=True)
+    buf = vsa.Buffers(pb, backward=True, with_gate_f=with_gate_f)
     a = (dev["q"], dev["k"], dev["v"], dev["gate_c"], dev["gate_f"])
     buf.forward(*a)
     torch.cuda.synchronize()
@@ -69,7 +92,7 @@ def test_key_cubes_16_forward_backward(vsa, name):
     assert_close(bf16_to_np(buf.out), fwd["out"], "out")
     assert_close(bf16_to_np(buf.out_fine), fwd["out_fine"], "out_fine")
     assert np.abs(buf.lse_fine.cpu().numpy() - fwd["lse_fine"]).max() < 2e-3
-    for n in ("dq", "dk", "dv", "dgate_c", "dgate_f"):
+    for n in ("dq", "dk", "dv", "dgate_c") + (("dgate_f",) if with_gate_f else ()):
         assert_close(bf16_to_np(getattr(buf, n)), ref[n], n)
     valid, _ = orc.valid_mask(g)
     for n in ("out", "dq", "dk", "dv"):
