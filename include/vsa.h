@@ -138,7 +138,9 @@ int vsa_tile_permute(const vsa_params_t* p, const void* src, void* dst, int inve
  *                in   when flags has VSA_FLAG_INDICES_GIVEN (must be ascending, distinct,
  *                     each in [0,Nc); not validated: for a list that breaks this the results
  *                     are unspecified, but entries outside [0,Nc) are clamped or skipped, so
- *                     no access leaves the buffers)
+ *                     no access leaves the buffers; a query row whose list holds no valid key at
+ *                     all -- possible only with such a list, e.g. one made of dead key cubes of 16
+ *                     tokens -- gets O_f = 0 and lse_fine = 0)
  *   out_fine     out  bf16 [B,H,Np,d]  O_f           } saved for vsa_backward;
  *   lse_fine     out  fp32 [B,H,Np]    log-sum-exp of the scaled fine logits (0 on pads)
  *   out_coarse   out  fp32 [B,H,Nc,d]  O_c per cube  } any of these four may be NULL
@@ -190,7 +192,8 @@ int vsa_backward(const vsa_params_t* p, const void* q, const void* k, const void
  * partial-result slots -- through the very functions the kernels use, and counts every replayed
  * access that would leave its buffer.  For checking on the CPU that caller-supplied lists of any
  * content (VSA_FLAG_INDICES_GIVEN: entries outside [0,Nc), duplicates, disorder) stay in bounds.
- *   host_block_idx  HOST int32 [B,H,Nc,topk]
+ *   host_block_idx  HOST int32 [B,H,Nc,topk] ([B,H,Nc/4,topk] of tiles with VSA_FLAG_SELECT_POOLED_2X2; entries
+ *                   are key cube numbers below 4*Nc with VSA_FLAG_KEY_CUBES_16)
  *   report          HOST int64[8] or NULL: violations, longest transposed list, most dK/dV work
  *                   items and partial-result slots and split lists of a (b,h), most transposed
  *                   entries of a (b,h), split length, slot capacity
