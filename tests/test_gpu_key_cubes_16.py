@@ -208,3 +208,60 @@ def test_key_cubes_16_at_the_wan13b_shape_sampled_cubes(vsa):
     assert_close(bf16_to_np(buf.out[:, h:h + 1])[0, 0, same], ref["out"][0, 0, same], "out")
     valid, _ = orc.valid_mask(g)
     assert not bf16_to_np(buf.out)[:, :, ~valid].any()
+
+
+def test_key_cubes_16_with_the_other_entry_points_and_flags(vsa):
+    """The same results, bit for bit, (a) with `out` / `dout` token-major, (b) from the static-scratch
+    forward, (c) from three replays of a captured HIP graph with the outputs and the workspace
+    poisoned in between."""
+    import torch
+    wl = CASES["ragged_d128"]
+    dev = to_dev(tiled_bits(wl, seed=12, pad_garbage=True))
+    a = (dev["q"], dev["k"], dev["v"], dev["gate_c"], dev["gate_f"])
+    flag = vsa.VSA_FLAG_KEY_CUBES_16
+    ref = vsa.Buffers(dataclasses.replace(problem_of(wl), flags=flag), backward=True)
+    ref.forward(*a)
+    ref.backward(*a, dev["dout"])
+    torch.cuda.synchronize()
+    names = ("out", "block_idx", "out_fine", "lse_fine", "out_coarse", "lse_coarse", "dq", "dk", "dv", "dgate_c", "dgate_f")
+    same = lambda x, y: torch.equal(x.contiguous().view(torch.uint8), y.contiguous().view(torch.uint8))
+
+    tm = vsa.Buffers(dataclasses.replace(problem_of(wl), flags=flag | vsa.VSA_FLAG_OUT_TOKEN_MAJOR), backward=True)
+    tm.forward(*a)
+    tm.backward(*a, dev["dout"].permute(0, 2, 1, 3).contiguous())
+    torch.cuda.synchronize()
+    assert same(tm.out.view(wl.B, tm.Np, wl.H, wl.d).permute(0, 2, 1, 3), ref.out)
+    for n in names[1:]:
+        assert same(getattr(tm, n), getattr(ref, n)), n
+
+    st = vsa.Buffers(ref.pb, backward=False)
+    for n in names[:6]:
+        t = getattr(st, n)
+        t.fill_(-1) if t.dtype == torch.int32 else t.fill_(float("nan"))
+    vsa.vsa_forward_static(ref.pb, *a, st.out, st.block_idx, st.out_fine, st.lse_fine, st.out_coarse, st.lse_coarse)
+    torch.cuda.synchronize()
+    for n in names[:6]:
+        assert same(getattr(st, n), getattr(ref, n)), n
+
+    want = [getattr(ref, n).clone() for n in names]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        ref.forward(*a)
+        ref.backward(*a, dev["dout"])
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        ref.forward(*a)
+        ref.backward(*a, dev["dout"])
+    for rep in range(3):
+        for n in names:
+            t = getattr(ref, n)
+            t.fill_(-1) if t.dtype == torch.int32 else t.fill_(float("nan"))
+        ref.workspace.fill_(0xFF)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for n, w in zip(names, want):
+            assert same(getattr(ref, n), w), f"replay {rep}: {n}"
