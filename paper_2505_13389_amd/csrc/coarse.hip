@@ -128,7 +128,7 @@ __device__ __forceinline__ void coarse_row(float* srow, int Nc, int K, float* ls
       if (ch < nch) {
         const bool eq = (key[ch] == T) && (ch * 64 + lane < Nc);
         const uint64_t beq = __ballot(eq);
-        const bool take = (key[ch] > T) || (eq && (eq_seen + __popcll(beq & lt) < need));
+        const bool take = (key[ch] > T) || (eq && (eq_seen + (int)__popcll(beq & lt) < need));
         eq_seen += __popcll(beq);
         const uint64_t bsel = __ballot(take);
         const int pos = base + __popcll(bsel & lt);

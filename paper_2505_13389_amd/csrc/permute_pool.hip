@@ -104,7 +104,7 @@ __global__ __launch_bounds__(256) void k_pool(Geo g, long long Np, uint64_t* __r
   int cnt = 0;
   for (int sb = 0; sb < g.m; ++sb) {
     const uint64_t m = block_valid_mask_wave(g, c * g.m + sb, threadIdx.x & 63);
-    if (blockIdx.x < Nc && blockIdx.y == 0 && threadIdx.x == 0) mask[c * g.m + sb] = m;
+    if (blockIdx.x < (unsigned)Nc && blockIdx.y == 0 && threadIdx.x == 0) mask[c * g.m + sb] = m;
     cnt += __popcll(m);
     const uint4* base = src + (bh * Np + ((long long)c * g.m + sb) * kTile) * CPR;
 #pragma unroll
