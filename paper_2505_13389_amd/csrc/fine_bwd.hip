@@ -19,7 +19,8 @@ namespace vsa {
 
 // ---------------------------------------------------------------------------------------------
 // dQ pass: one workgroup per (b, h, query cube); streams the K selected (K tile, V tile) pairs.
-// Wavefront (qh, kh): query rows qh*32..+31, key rows kh*32..+31 of each tile.
+// Wavefront (qh, kh): query rows qh*32..+31, key rows kh*32..+31 of each tile.  LIST as in the forward
+// kernel: one list entry per tile, or four key cubes of 16 tokens gathered into one.
 template <int D, class LIST>
 __global__ __launch_bounds__(256, 2) void k_fine_bwd_dq(int Nc, int K, float sl2, float scale, const uint4* __restrict__ q,
                                                         const uint4* __restrict__ k, const uint4* __restrict__ v,

@@ -3,8 +3,9 @@
 //
 // One workgroup (4 wavefronts) per (b, h, 64-row query block); "cube" below means such a block (a
 // cube of 64*m tokens is m consecutive blocks, and the lists the kernel gets name blocks).  The K
-// selected key blocks are walked
-// through a double-buffered LDS stage (K tile + V tile).  Work split inside the workgroup:
+// selected key blocks are walked through a double-buffered LDS stage (K tile + V tile).  LIST says how
+// list entries turn into streamed 64-key tiles: CubeList, one entry = one block; SubCubeList, four
+// entries that name key cubes of 16 tokens are gathered into one tile (Sec. 3.2, 64 x 16 tiles).  Work split inside the workgroup:
 // wavefront (qh, kh) owns query rows qh*32..+31 and key rows kh*32..+31 of every key tile and
 // keeps its OWN online-softmax state (running max, running sum, unnormalised O); the two
 // key halves of a query row are merged once, after the last tile.  Splitting keys instead of
